@@ -1,0 +1,152 @@
+"""CPU oracle for READER's draft-tree verification step -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes loader around ``reader_oracle.c`` (plain C, IEEE double arithmetic, no
+tiling, explicit masks).  Only the tests, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this package; the product package
+never does, and this package never imports the product package.
+
+All arrays are numpy, C-contiguous.  bf16 tensors are passed as ``uint16`` bit
+patterns.  Layouts are the ones listed at the top of ``reader_oracle.c``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "reader_oracle.c")
+_LIB = os.path.join(_HERE, "libreader_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over independent (sequence, kv head) pairs)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.run(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+             _SRC, "-o", tmp, "-lm"],
+            check=True,
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _p(a, dtype):
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags["C_CONTIGUOUS"], (
+        "expected C-contiguous %s array, got %r %r" % (dtype, getattr(a, "dtype", None), type(a)))
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def ancestor_mask(parents: np.ndarray):
+    """parents: int32 [T].  Returns (mask uint8 [T, T] with mask[query, key], depth int32 [T])."""
+    parents = np.ascontiguousarray(parents, dtype=np.int32)
+    T = parents.shape[0]
+    mask = np.zeros((T, T), dtype=np.uint8)
+    depth = np.zeros(T, dtype=np.int32)
+    rc = _load().oracle_ancestor_mask(_p(parents, np.int32), T, _p(mask, np.uint8), _p(depth, np.int32))
+    if rc:
+        raise ValueError("oracle_ancestor_mask: malformed tree (rc=%d)" % rc)
+    return mask, depth
+
+
+def _attn_common(q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents):
+    B, T, Hq, D = q.shape
+    Hkv = k_tree.shape[2]
+    assert k_tree.shape == (B, T, Hkv, D) and v_tree.shape == (B, T, Hkv, D)
+    num_pages, Hkv2, page_size, D2 = k_cache.shape
+    assert Hkv2 == Hkv and D2 == D and v_cache.shape == k_cache.shape
+    assert page_table.shape[0] == B and seq_lens.shape == (B,) and parents.shape == (B, T)
+    if B:
+        used = (seq_lens.astype(np.int64) + page_size - 1) // page_size
+        for b in range(B):
+            pt = page_table[b, : used[b]]
+            assert pt.size == 0 or (pt.min() >= 0 and pt.max() < num_pages), "page table out of range"
+    return B, T, Hq, Hkv, D, page_size, page_table.shape[1]
+
+
+def tree_attn(q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, sm_scale=0.0):
+    """Tree-masked attention (Section 3.2).  Returns (out float64 [B,T,Hq,D], lse float64 [B,Hq,T])."""
+    B, T, Hq, Hkv, D, page_size, max_pages = _attn_common(
+        q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents)
+    out = np.zeros((B, T, Hq, D), dtype=np.float64)
+    lse = np.zeros((B, Hq, T), dtype=np.float64)
+    rc = _load().oracle_tree_attn(
+        B, T, Hq, Hkv, D, page_size, max_pages, ctypes.c_double(sm_scale),
+        _p(q, np.uint16), _p(k_tree, np.uint16), _p(v_tree, np.uint16),
+        _p(k_cache, np.uint16), _p(v_cache, np.uint16), _p(page_table, np.int32),
+        _p(seq_lens, np.int32), _p(parents, np.int32), _p(out, np.float64), _p(lse, np.float64))
+    if rc:
+        raise ValueError("oracle_tree_attn failed (rc=%d)" % rc)
+    return out, lse
+
+
+def tree_attn_rows(q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, rows,
+                   sm_scale=0.0):
+    """Same, for selected (b, hq, node) triples.  rows int32 [n,3] -> (out [n,D], lse [n])."""
+    B, T, Hq, Hkv, D, page_size, max_pages = _attn_common(
+        q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents)
+    rows = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 3)
+    n = rows.shape[0]
+    out = np.zeros((n, D), dtype=np.float64)
+    lse = np.zeros((n,), dtype=np.float64)
+    rc = _load().oracle_tree_attn_rows(
+        B, T, Hq, Hkv, D, page_size, max_pages, ctypes.c_double(sm_scale),
+        _p(q, np.uint16), _p(k_tree, np.uint16), _p(v_tree, np.uint16),
+        _p(k_cache, np.uint16), _p(v_cache, np.uint16), _p(page_table, np.int32),
+        _p(seq_lens, np.int32), _p(parents, np.int32), n, _p(rows, np.int32),
+        _p(out, np.float64), _p(lse, np.float64))
+    if rc:
+        raise ValueError("oracle_tree_attn_rows failed (rc=%d)" % rc)
+    return out, lse
+
+
+def accept_path(draft_tokens, target_tokens, parents, max_path):
+    """Greedy lossless acceptance (Algorithm 5).  Returns (accept_len [B], path [B,max_path], bonus [B])."""
+    B, T = parents.shape
+    assert draft_tokens.shape == (B, T) and target_tokens.shape == (B, T)
+    accept_len = np.zeros(B, dtype=np.int32)
+    path = np.full((B, max_path), -1, dtype=np.int32)
+    bonus = np.zeros(B, dtype=np.int32)
+    rc = _load().oracle_accept_path(
+        B, T, int(max_path), _p(draft_tokens, np.int32), _p(target_tokens, np.int32),
+        _p(parents, np.int32), _p(accept_len, np.int32), _p(path, np.int32), _p(bonus, np.int32))
+    if rc:
+        raise ValueError("oracle_accept_path failed (rc=%d)" % rc)
+    return accept_len, path, bonus
+
+
+def kv_compact(k_tree, v_tree, path, accept_len, k_cache, v_cache, page_table, seq_lens):
+    """Append the accepted path's K/V rows to each sequence's paged cache IN PLACE
+    (Section 4.3 / Algorithm 4); seq_lens is updated in place."""
+    B, T, Hkv, D = k_tree.shape
+    num_pages, Hkv2, page_size, D2 = k_cache.shape
+    assert (Hkv2, D2) == (Hkv, D) and v_cache.shape == k_cache.shape and v_tree.shape == k_tree.shape
+    max_path = path.shape[1]
+    if B:
+        used = (seq_lens.astype(np.int64) + accept_len + 1 + page_size - 1) // page_size
+        for b in range(B):
+            pt = page_table[b, : used[b]]
+            assert pt.min() >= 0 and pt.max() < num_pages, "page table out of range"
+    rc = _load().oracle_kv_compact(
+        B, T, Hkv, D, page_size, page_table.shape[1], max_path,
+        _p(k_tree, np.uint16), _p(v_tree, np.uint16), _p(path, np.int32), _p(accept_len, np.int32),
+        _p(k_cache, np.uint16), _p(v_cache, np.uint16), _p(page_table, np.int32), _p(seq_lens, np.int32))
+    if rc:
+        raise ValueError("oracle_kv_compact failed (rc=%d)" % rc)
