@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the draft-tree verification step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+reader_tree_attn -> reader_accept_path -> reader_kv_compact, all on one stream,
+inputs resident in HBM before the clock starts.  The metric is tree tokens per
+second (B * T draft-tree nodes verified per step) together with the achieved HBM
+bandwidth of the attention kernel, which streams the K/V cache and dominates.
+
+    python bench.py --gpus 1 --steps 200 --warmup 20
+
+prints ONE JSON line.  The headline workload is the batched ragged serving preset
+(B=16, L in [1024,4096], T=32), the HBM-bound shape the 70 %-of-peak target is
+stated for; the other presets are timed with fewer steps and reported inside the
+same line under "other_workloads".  `--gpus N` with N > 1 is refused: this build
+is single-GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+ROTATE_BYTES = 512 << 20       # K/V copies cycled per step so the 256 MB Infinity Cache cannot serve the stream
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class StepRunner:
+    """Pre-marshalled C-ABI calls for K steps of one workload (no per-step Python marshalling)."""
+
+    def __init__(self, R, torch, w, n_steps):
+        self.R, self.torch, self.w = R, torch, w
+        self.lib = R.load()
+        dw = R.to_device(w)
+        self.dw = dw
+        kv_bytes = 2 * w.k_cache.nbytes
+        self.n_copies = int(max(1, min(32, -(-ROTATE_BYTES // max(kv_bytes, 1)))))
+        self.kc = [dw.k_cache] + [dw.k_cache.clone() for _ in range(self.n_copies - 1)]
+        self.vc = [dw.v_cache] + [dw.v_cache.clone() for _ in range(self.n_copies - 1)]
+        # compaction grows seq_lens: every step gets its own fresh copy of the lengths
+        self.seq_rows = dw.seq_lens.unsqueeze(0).repeat(n_steps, 1).contiguous()
+        self.n_steps = n_steps
+        self.dims = ctypes.byref(dw.dims)
+        p = lambda t: ctypes.c_void_p(t.data_ptr())
+        self.attn_args, self.compact_args = [], []
+        ws_bytes = dw.workspace.numel()
+        for k in range(n_steps):
+            r = k % self.n_copies
+            seq = ctypes.c_void_p(self.seq_rows[k].data_ptr())
+            self.attn_args.append((self.dims, p(dw.q), p(dw.k_tree), p(dw.v_tree), p(self.kc[r]), p(self.vc[r]),
+                                   p(dw.page_table), seq, p(dw.parents), p(dw.out), None, dw.max_seq_len,
+                                   p(dw.workspace), ws_bytes, p(dw.status)))
+            self.compact_args.append((self.dims, p(dw.k_tree), p(dw.v_tree), p(dw.path), p(dw.accept_len),
+                                      p(self.kc[r]), p(self.vc[r]), p(dw.page_table), seq, p(dw.status)))
+        self.accept_args = (self.dims, p(dw.draft_tokens), p(dw.target_tokens), p(dw.parents), p(dw.accept_len),
+                            p(dw.path), p(dw.bonus), p(dw.status))
+
+    def reset(self):
+        self.seq_rows.copy_(self.dw.seq_lens.unsqueeze(0).expand(self.n_steps, -1))
+
+    def run(self, first, count):
+        lib = self.lib
+        stream = ctypes.c_void_p(self.torch.cuda.current_stream().cuda_stream)
+        for k in range(first, first + count):
+            rc = lib.reader_tree_attn(*self.attn_args[k], stream)
+            rc |= lib.reader_accept_path(*self.accept_args, stream)
+            rc |= lib.reader_kv_compact(*self.compact_args[k], stream)
+            if rc:
+                raise RuntimeError("library call failed in step %d" % k)
+
+
+def time_workload(R, torch, w, steps, warmup, use_graph=True):
+    total = warmup + steps
+    run = StepRunner(R, torch, w, total)
+    res = {"workload": w.name, "kv_copies_rotated": run.n_copies}
+
+    # ---- eager: warmup, then exactly `steps` steps between two synchronisations
+    run.run(0, warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run.run(warmup, steps)
+    torch.cuda.synchronize()
+    eager_s = time.perf_counter() - t0
+    assert int(run.dw.status.item()) == 0, "device status flagged an input problem"
+    out_eager = run.dw.out.clone()
+    seq_eager = run.seq_rows.clone()
+    res["eager_ms_per_step"] = eager_s / steps * 1e3
+
+    # ---- the same `steps` steps captured once into a HIP graph and replayed
+    graph_s = None
+    if use_graph:
+        try:
+            run.reset()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                run.run(warmup, steps)
+            for _ in range(2):                      # replay is checked against eager every time
+                run.reset()
+                run.dw.out.zero_()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                g.replay()
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                ok = torch.equal(run.dw.out, out_eager) and torch.equal(run.seq_rows[warmup:], seq_eager[warmup:])
+                if not ok:
+                    raise RuntimeError("graph replay differs from eager execution")
+                graph_s = dt if graph_s is None else min(graph_s, dt)
+            res["graph_ms_per_step"] = graph_s / steps * 1e3
+        except Exception as e:  # the eager number stands on its own
+            log("graph mode unavailable:", repr(e))
+            graph_s = None
+    best_s = eager_s if graph_s is None else min(graph_s, eager_s)
+    res["launch_mode"] = "hip_graph" if (graph_s is not None and graph_s <= eager_s) else "eager"
+    res["ms_per_step"] = best_s / steps * 1e3
+    res["tree_tokens_per_s"] = w.B * w.T * steps / best_s
+
+    # ---- roofline of the dominant kernel: HIP events around the attention main kernel,
+    # recorded by the library on the launch stream, over the same `steps` steps
+    run.reset()
+    torch.cuda.synchronize()
+    R.reader_profile_enable(True)
+    run.run(warmup, steps)
+    torch.cuda.synchronize()
+    ms_sum, n = R.reader_profile_collect()
+    R.reader_profile_enable(False)
+    kernel_ms = ms_sum / max(n, 1)
+    alg_bytes = w.algorithmic_bytes()
+    flops = w.attention_flops()
+    gbs = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    tflops = flops / (kernel_ms * 1e-3) / 1e12
+    hbm_t = alg_bytes / (HBM_PEAK_GBS * 1e9)
+    mfma_t = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if hbm_t >= mfma_t:
+        roof = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+    else:
+        roof = {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tflops / MFMA_BF16_PEAK_TFLOPS}
+    roof.update({"kernel": "tree_attn_mfma_kernel", "kernel_ms": kernel_ms, "launches_timed": n,
+                 "algorithmic_bytes": alg_bytes, "algorithmic_flops": flops, "hbm_gbs": gbs,
+                 "hbm_frac": gbs / HBM_PEAK_GBS, "mfma_tflops": tflops, "traffic": None})
+    res["roofline"] = roof
+    return res
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """The CPU oracle, as it stands, on the same workload: whole steps until the budget is used."""
+    import oracle
+    import numpy as np
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        kc, vc, sl = w.k_cache, w.v_cache, w.seq_lens.copy()
+        oracle.tree_attn(w.q, w.k_tree, w.v_tree, kc, vc, w.page_table, sl, w.parents)
+        al, path, bonus = oracle.accept_path(w.draft_tokens, w.target_tokens, w.parents, w.max_path)
+        # compaction writes behind the sequences' ends (canary slots); lengths are a scratch copy
+        oracle.kv_compact(w.k_tree, w.v_tree, path, al, kc, vc, w.page_table, sl)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or reps >= 50:
+            break
+    return {"value": w.B * w.T * reps / dt, "unit": "tree tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "%d whole step(s) of %s (attention + acceptance + compaction), %.1f s" % (reps, w.name, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="headline preset (0..4)")
+    ap.add_argument("--others", type=str, default="0,1,3,4", help="presets also timed (comma list, '' for none)")
+    ap.add_argument("--other-steps", type=int, default=30)
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2508_09072_amd import binding as R
+    from paper_2508_09072_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    R.load()   # raises if the HIP library is missing: there is no fallback path
+    torch.cuda.set_device(0)
+
+    log("generating", W.CONFIG_NAMES[args.config])
+    w = W.make_config(args.config)
+    head = time_workload(R, torch, w, args.steps, args.warmup, use_graph=not args.no_graph)
+    log("headline:", json.dumps(head))
+
+    line = {
+        "metric": "tree_verify_tokens_per_sec",
+        "value": head["tree_tokens_per_s"],
+        "unit": "tree tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "T": w.T, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
+                   "sum_L": int(w.seq_lens.sum()), "page_size": w.page_size,
+                   "launch_mode": head["launch_mode"], "kv_copies_rotated": head["kv_copies_rotated"]},
+        "eager_ms_per_step": head["eager_ms_per_step"],
+        "graph_ms_per_step": head.get("graph_ms_per_step"),
+        "roofline": head["roofline"],
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle")
+        line["cpu_baseline"] = cpu_baseline(w)
+    del head
+
+    others = {}
+    for idx in [int(x) for x in args.others.split(",") if x.strip() != ""]:
+        if idx == args.config:
+            continue
+        log("generating", W.CONFIG_NAMES[idx])
+        wo = W.make_config(idx)
+        r = time_workload(R, torch, wo, args.other_steps, min(args.warmup, 5), use_graph=not args.no_graph)
+        others[wo.name] = {"tree_tokens_per_s": r["tree_tokens_per_s"], "ms_per_step": r["ms_per_step"],
+                           "launch_mode": r["launch_mode"], "steps": args.other_steps,
+                           "kernel_ms": r["roofline"]["kernel_ms"], "bound": r["roofline"]["bound"],
+                           "frac": r["roofline"]["frac"], "hbm_gbs": r["roofline"]["hbm_gbs"],
+                           "hbm_frac": r["roofline"]["hbm_frac"], "mfma_tflops": r["roofline"]["mfma_tflops"]}
+        log(wo.name, json.dumps(others[wo.name]))
+        del wo, r
+        torch.cuda.empty_cache()
+    line["other_workloads"] = others
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

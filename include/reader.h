@@ -1,0 +1,200 @@
+/*
+ * reader.h - C ABI of the MI355X (gfx950) draft-tree verification library for
+ * READER (arXiv 2508.09072), the lossless retrieval-drafted speculative decoder.
+ *
+ * One verification step of the base model over a draft tree (Algorithm 1, "Verify
+ * and accept"; Algorithm 5) is, per transformer layer, a tree-masked attention
+ * (Section 3.2) and, once per step, a greedy acceptance of the longest draft path
+ * that agrees with the base model (Algorithm 5, Appendix C) followed by the
+ * append of that path's K/V rows to each sample's cache so that it stays tight
+ * (Section 4.3, Algorithm 4).  This library is those three operations.
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless its name ends in `_host`.  All
+ *    buffers are borrowed: the caller allocates, owns and frees them.  The library
+ *    allocates nothing, frees nothing and never synchronises; each call enqueues
+ *    its kernels on `stream` (a hipStream_t passed as void*, NULL = default
+ *    stream) and returns.  Results are valid once the stream reaches that point.
+ *  - bf16 tensors are passed as `void*`; element (i,j,k,l) of a tensor of shape
+ *    [A,B,C,D] sits at ((i*B + j)*C + k)*D + l (C order, no padding).
+ *  - Return value: READER_OK (0) or a negative READER_E* code.  Argument checks
+ *    happen on the host before anything is enqueued, so a failed call has no
+ *    effect.  Nothing is printed, no exception crosses the boundary.
+ *  - Data-dependent problems that only the device can see (a malformed tree, a
+ *    page id outside the pool, an accepted length that does not fit) never fault:
+ *    the kernel skips the offending item and ORs a READER_STATUS_* bit into the
+ *    optional device word `status`.
+ *  - Tree convention: node 0 is the root = the last committed token (it comes
+ *    from the base model, acceptance rate 1, Section 3.3); parents[b][0] = -1 and
+ *    0 <= parents[b][i] < i.  Trees may differ between sequences; the paper's
+ *    fixed per-batch shape is the case where all rows of `parents` are equal.
+ *  - Grouped-query attention: query head hq reads kv head hq / (Hq / Hkv).
+ *  - Paged cache: position j of sequence b lives in physical page
+ *    page_table[b][j / page_size], slot j % page_size.
+ */
+#ifndef READER_H
+#define READER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    READER_OK = 0,
+    READER_EINVAL = -1,       /* null pointer, non-positive size, inconsistent dims, malformed host tree */
+    READER_EUNSUPPORTED = -2, /* a size outside what the kernels are built for */
+    READER_EWORKSPACE = -3,   /* workspace pointer missing or too small */
+    READER_EHIP = -4          /* the HIP runtime refused a launch */
+};
+
+enum {
+    READER_STATUS_BAD_TREE = 1, /* parents[b][0] != -1 or parents[b][i] not in [0, i) */
+    READER_STATUS_BAD_PAGE = 2, /* a page id outside [0, num_pages) was met */
+    READER_STATUS_BAD_PATH = 4  /* accept_len/path entry out of range, or path longer than max_path */
+};
+
+enum {
+    READER_MAX_T = 128,  /* draft-tree nodes per sequence */
+    READER_PAGE_SIZE = 16
+};
+
+/* Problem sizes; plain data, passed by const pointer (host memory). */
+typedef struct reader_dims {
+    int32_t B;                 /* sequences in the batch, >= 0 (0 = nothing to do) */
+    int32_t T;                 /* draft-tree nodes per sequence, 1..READER_MAX_T */
+    int32_t Hq;                /* query heads */
+    int32_t Hkv;               /* kv heads, Hq % Hkv == 0, Hq / Hkv <= 16 */
+    int32_t D;                 /* head dimension, 64 or 128 */
+    int32_t page_size;         /* tokens per cache page, must be READER_PAGE_SIZE */
+    int32_t max_pages_per_seq; /* row stride of page_table */
+    int32_t max_path;          /* row stride of `path`: >= deepest node's depth + 1, <= T */
+    int64_t num_pages;         /* pages in the pool (first dim of k_cache / v_cache) */
+    float sm_scale;            /* softmax scale; <= 0 selects 1/sqrt(D) */
+    int32_t variant;           /* 0 = default kernel selection.  1 = force the scalar reference
+                                  kernel of reader_tree_attn (slow; for cross-checks only) */
+} reader_dims;
+
+/* Library version string (static storage). */
+const char *reader_version(void);
+
+/* Text for a READER_E* code (static storage). */
+const char *reader_strerror(int code);
+
+/* Which HIP call failed last and how, after a READER_EHIP return ("" if none so far; static storage). */
+const char *reader_last_error_detail(void);
+
+/*
+ * Host-side check of the tree convention above on HOST arrays parents_host[B][T].
+ * Pure function, no GPU needed.  READER_OK or READER_EINVAL.
+ */
+int reader_validate_tree(const int32_t *parents_host, int32_t B, int32_t T);
+
+/*
+ * Bytes of device workspace reader_tree_attn needs for these dims when no
+ * sequence is longer than max_seq_len.  Pure host function.  Returns 0 when the
+ * dims are invalid.  The workspace holds the partial (unnormalised output, running
+ * max, running sum) records of key ranges that were split across workgroups; its
+ * contents are meaningless between calls and it may be shared by calls that are
+ * ordered on one stream.
+ */
+size_t reader_workspace_bytes(const reader_dims *dims, int32_t max_seq_len);
+
+/*
+ * Tree-masked attention (Section 3.2; Appendix C invariant 2).
+ * For every sequence b, query head hq and tree node i:
+ *     out[b,i,hq,:] = sum_j softmax_j( sm_scale * <q[b,i,hq,:], k_j> ) * v_j
+ * where j runs over the seq_lens[b] cached positions of b (kv head hq/(Hq/Hkv))
+ * and over the tree nodes that are i itself or an ancestor of i.
+ *
+ *   q            bf16 [B, T, Hq, D]                     in
+ *   k_tree,v_tree bf16 [B, T, Hkv, D]                   in   K/V rows of the tree nodes
+ *   k_cache,v_cache bf16 [num_pages, Hkv, page_size, D] in   paged prefix cache
+ *   page_table   i32 [B, max_pages_per_seq]             in   must map pages for [0, seq_lens[b])
+ *   seq_lens     i32 [B]                                in   prefix length L_b, tree rows excluded
+ *   parents      i32 [B, T]                             in
+ *   out          bf16 [B, T, Hq, D]                     out  fp32 accumulation, rounded to nearest even
+ *   lse          f32 [B, Hq, T] or NULL                 out  natural-log sum of exp of the scaled scores
+ *   max_seq_len  upper bound of seq_lens[b] (host value) used to size the launch; a sequence
+ *                longer than this is truncated to it and nothing faults
+ *   workspace    >= reader_workspace_bytes(dims, max_seq_len) bytes, 256-byte aligned
+ *   status       i32 [1] or NULL                        in/out  READER_STATUS_* bits are ORed in
+ *
+ * Arithmetic: bf16 products accumulated in fp32 on the matrix cores; softmax
+ * weights are rounded to bf16 before they multiply V.  Rows of a malformed tree
+ * are computed as if the bad node were a root.
+ */
+int reader_tree_attn(const reader_dims *dims,
+                     const void *q, const void *k_tree, const void *v_tree,
+                     const void *k_cache, const void *v_cache,
+                     const int32_t *page_table, const int32_t *seq_lens, const int32_t *parents,
+                     void *out, float *lse,
+                     int32_t max_seq_len, void *workspace, size_t workspace_bytes,
+                     int32_t *status, void *stream);
+
+/*
+ * Greedy lossless acceptance (Algorithm 5; Appendix C invariants 2 and 3).
+ * target_tokens[b][i] is the base model's own next token after the prefix that
+ * ends at node i.  A non-root node is accepted iff its parent is accepted and
+ * draft_tokens[b][i] == target_tokens[b][parents[b][i]]; draft_tokens[b][0] is
+ * ignored.  Among accepted nodes the deepest wins, the lowest node id among
+ * equally deep ones (siblings may carry equal tokens, Section 4.2 "deepening").
+ *
+ *   draft_tokens, target_tokens, parents   i32 [B, T]       in
+ *   accept_len   i32 [B]            out  number of accepted non-root nodes, 0..max_path-1
+ *   path         i32 [B, max_path]  out  node ids root..terminal, then -1
+ *   bonus_token  i32 [B]            out  target token at the terminal node (always committed)
+ *   status       i32 [1] or NULL    in/out
+ *
+ * A path deeper than max_path-1 is cut at max_path-1 and READER_STATUS_BAD_PATH is set.
+ * Integer work; results are exact.
+ */
+int reader_accept_path(const reader_dims *dims,
+                       const int32_t *draft_tokens, const int32_t *target_tokens,
+                       const int32_t *parents,
+                       int32_t *accept_len, int32_t *path, int32_t *bonus_token,
+                       int32_t *status, void *stream);
+
+/*
+ * Compaction of the accepted path into the cache (Section 4.3; Algorithm 4, done
+ * every step so that no padding ever enters a sample's cache).  For every b and
+ * j = 0..accept_len[b]: the K and V rows (all kv heads) of tree node path[b][j]
+ * are copied to cache position seq_lens[b] + j, then seq_lens[b] += accept_len[b] + 1.
+ * The root row (j = 0) is included: its K/V were first computed in this step.
+ *
+ *   k_tree, v_tree   bf16 [B, T, Hkv, D]                    in
+ *   path             i32 [B, max_path], accept_len i32 [B]  in
+ *   k_cache, v_cache bf16 [num_pages, Hkv, page_size, D]    in/out
+ *   page_table       i32 [B, max_pages_per_seq]             in   must map pages for
+ *                                                                [0, seq_lens[b] + accept_len[b] + 1)
+ *   seq_lens         i32 [B]                                in/out
+ *   status           i32 [1] or NULL                        in/out
+ *
+ * A sequence whose accept_len, path entry, target position or page id is out of
+ * range is left untouched (cache and seq_lens) and a status bit is set.  Bit-exact copy.
+ */
+int reader_kv_compact(const reader_dims *dims,
+                      const void *k_tree, const void *v_tree,
+                      const int32_t *path, const int32_t *accept_len,
+                      void *k_cache, void *v_cache, const int32_t *page_table,
+                      int32_t *seq_lens, int32_t *status, void *stream);
+
+/*
+ * Measurement hooks for benchmarks (not operations of the method).  While enabled,
+ * every reader_tree_attn call records a HIP event pair on `stream` right before and
+ * right after its main streaming kernel (the merge kernel is outside the pair).
+ * reader_profile_collect waits for the recorded events (it synchronises the host with
+ * them), adds up the elapsed times of all pairs recorded since the last collect into
+ * *kernel_ms_sum, stores their count in *launches, and forgets them.  The event
+ * objects are host-side handles owned by the library; at most 65536 pairs are kept
+ * between collects (further launches are simply not timed).  Not thread-safe.
+ */
+int reader_profile_enable(int32_t on);
+int reader_profile_collect(double *kernel_ms_sum, int32_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* READER_H */

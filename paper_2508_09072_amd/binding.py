@@ -1,0 +1,235 @@
+"""ctypes binding of libreader_hip.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+``include/reader.h``; tensors are torch CUDA (ROCm) tensors whose ``data_ptr()`` is
+handed through, and every kernel is enqueued on torch's current stream.  Nothing is
+computed here, and there is no fallback: if the library has not been built, or a
+tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import dataclasses
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libreader_hip.so")
+
+READER_OK = 0
+READER_EINVAL = -1
+READER_EUNSUPPORTED = -2
+READER_EWORKSPACE = -3
+READER_EHIP = -4
+STATUS_BAD_TREE = 1
+STATUS_BAD_PAGE = 2
+STATUS_BAD_PATH = 4
+
+EXPORTS = (
+    "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",
+    "reader_tree_attn", "reader_accept_path", "reader_kv_compact",
+    "reader_profile_enable", "reader_profile_collect",
+)
+
+
+class ReaderDims(ctypes.Structure):
+    """Mirror of ``struct reader_dims``."""
+    _fields_ = [
+        ("B", ctypes.c_int32), ("T", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("D", ctypes.c_int32), ("page_size", ctypes.c_int32), ("max_pages_per_seq", ctypes.c_int32),
+        ("max_path", ctypes.c_int32), ("num_pages", ctypes.c_int64), ("sm_scale", ctypes.c_float),
+        ("variant", ctypes.c_int32),
+    ]
+
+
+class ReaderError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        detail = load().reader_last_error_detail().decode() if code == READER_EHIP else ""
+        super().__init__("%s: %s (code %d) %s" % (where, strerror(code), code, detail))
+
+
+_lib = None
+
+
+def load():
+    """Load the library; raises if it has not been built (python -m paper_2508_09072_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("HIP library missing: %s (run `python -m paper_2508_09072_amd.build`)" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, dp = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ReaderDims)
+    lib.reader_version.restype = ctypes.c_char_p
+    lib.reader_version.argtypes = []
+    lib.reader_strerror.restype = ctypes.c_char_p
+    lib.reader_strerror.argtypes = [ctypes.c_int]
+    lib.reader_last_error_detail.restype = ctypes.c_char_p
+    lib.reader_last_error_detail.argtypes = []
+    lib.reader_validate_tree.restype = ctypes.c_int
+    lib.reader_validate_tree.argtypes = [vp, i32, i32]
+    lib.reader_workspace_bytes.restype = ctypes.c_size_t
+    lib.reader_workspace_bytes.argtypes = [dp, i32]
+    lib.reader_tree_attn.restype = ctypes.c_int
+    lib.reader_tree_attn.argtypes = [dp] + [vp] * 10 + [i32, vp, ctypes.c_size_t, vp, vp]
+    lib.reader_accept_path.restype = ctypes.c_int
+    lib.reader_accept_path.argtypes = [dp] + [vp] * 8
+    lib.reader_kv_compact.restype = ctypes.c_int
+    lib.reader_kv_compact.argtypes = [dp] + [vp] * 10
+    lib.reader_profile_enable.restype = ctypes.c_int
+    lib.reader_profile_enable.argtypes = [i32]
+    lib.reader_profile_collect.restype = ctypes.c_int
+    lib.reader_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    _lib = lib
+    return lib
+
+
+def make_dims(B, T, Hq, Hkv, D, max_pages_per_seq, max_path, num_pages, page_size=16, sm_scale=0.0,
+              variant=0) -> ReaderDims:
+    return ReaderDims(B, T, Hq, Hkv, D, page_size, max_pages_per_seq, max_path, num_pages, sm_scale, variant)
+
+
+def version() -> str:
+    return load().reader_version().decode()
+
+
+def strerror(code: int) -> str:
+    return load().reader_strerror(int(code)).decode()
+
+
+def _dev(t, dtype=None, optional=False):
+    """Device pointer of a contiguous GPU tensor (None -> NULL when optional)."""
+    if t is None:
+        if optional:
+            return None
+        raise ValueError("required tensor is None")
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("expected %s, got %s" % (dtype, t.dtype))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(code, where):
+    if code != READER_OK:
+        raise ReaderError(code, where)
+
+
+def reader_validate_tree(parents_host) -> int:
+    """parents_host: CPU int32 tensor or numpy array [B, T].  Returns the C return code."""
+    import numpy as np
+    arr = np.ascontiguousarray(parents_host.numpy() if hasattr(parents_host, "numpy") else parents_host,
+                               dtype=np.int32)
+    B, T = arr.shape
+    return int(load().reader_validate_tree(arr.ctypes.data_as(ctypes.c_void_p), B, T))
+
+
+def reader_workspace_bytes(dims: ReaderDims, max_seq_len: int) -> int:
+    return int(load().reader_workspace_bytes(ctypes.byref(dims), int(max_seq_len)))
+
+
+def reader_tree_attn(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, out,
+                     lse, max_seq_len, workspace, status=None):
+    import torch
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    code = load().reader_tree_attn(
+        ctypes.byref(dims), _dev(q, torch.bfloat16), _dev(k_tree, torch.bfloat16), _dev(v_tree, torch.bfloat16),
+        _dev(k_cache, torch.bfloat16), _dev(v_cache, torch.bfloat16), _dev(page_table, torch.int32),
+        _dev(seq_lens, torch.int32), _dev(parents, torch.int32), _dev(out, torch.bfloat16),
+        _dev(lse, torch.float32, optional=True), int(max_seq_len), _dev(workspace, optional=True),
+        ws_bytes, _dev(status, torch.int32, optional=True), _stream())
+    _check(code, "reader_tree_attn")
+
+
+def reader_accept_path(dims, draft_tokens, target_tokens, parents, accept_len, path, bonus_token, status=None):
+    import torch
+    code = load().reader_accept_path(
+        ctypes.byref(dims), _dev(draft_tokens, torch.int32), _dev(target_tokens, torch.int32),
+        _dev(parents, torch.int32), _dev(accept_len, torch.int32), _dev(path, torch.int32),
+        _dev(bonus_token, torch.int32), _dev(status, torch.int32, optional=True), _stream())
+    _check(code, "reader_accept_path")
+
+
+def reader_kv_compact(dims, k_tree, v_tree, path, accept_len, k_cache, v_cache, page_table, seq_lens, status=None):
+    import torch
+    code = load().reader_kv_compact(
+        ctypes.byref(dims), _dev(k_tree, torch.bfloat16), _dev(v_tree, torch.bfloat16), _dev(path, torch.int32),
+        _dev(accept_len, torch.int32), _dev(k_cache, torch.bfloat16), _dev(v_cache, torch.bfloat16),
+        _dev(page_table, torch.int32), _dev(seq_lens, torch.int32), _dev(status, torch.int32, optional=True),
+        _stream())
+    _check(code, "reader_kv_compact")
+
+
+def reader_profile_enable(on: bool) -> None:
+    _check(load().reader_profile_enable(1 if on else 0), "reader_profile_enable")
+
+
+def reader_profile_collect():
+    """Returns (sum of main-kernel milliseconds, number of timed launches) since the last collect."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int32(0)
+    _check(load().reader_profile_collect(ctypes.byref(ms), ctypes.byref(n)), "reader_profile_collect")
+    return ms.value, n.value
+
+
+# ------------------------------------------------------------------ convenience (allocation only)
+
+@dataclasses.dataclass
+class DeviceWorkload:
+    """A workload's arrays as GPU tensors plus the buffers the three calls write."""
+    dims: ReaderDims
+    max_seq_len: int
+    q: object
+    k_tree: object
+    v_tree: object
+    k_cache: object
+    v_cache: object
+    page_table: object
+    seq_lens: object
+    parents: object
+    draft_tokens: object
+    target_tokens: object
+    out: object
+    lse: object
+    accept_len: object
+    path: object
+    bonus: object
+    status: object
+    workspace: object
+
+
+def to_device(w, device="cuda:0", variant=0, sm_scale=0.0) -> DeviceWorkload:
+    """Upload a workloads.Workload (numpy) and allocate outputs and workspace.  No arithmetic."""
+    import numpy as np
+    import torch
+
+    def bf16(a):
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+
+    def i32(a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(device)
+
+    # a bound with room for one accepted path, so that the same buffers serve a second step
+    max_seq_len = (int(w.seq_lens.max()) + w.max_path) if w.B else 0
+    dims = make_dims(w.B, w.T, w.Hq, w.Hkv, w.D, w.max_pages, w.max_path, w.num_pages,
+                     page_size=w.page_size, sm_scale=sm_scale, variant=variant)
+    ws = reader_workspace_bytes(dims, max_seq_len)
+    return DeviceWorkload(
+        dims=dims, max_seq_len=max_seq_len,
+        q=bf16(w.q), k_tree=bf16(w.k_tree), v_tree=bf16(w.v_tree), k_cache=bf16(w.k_cache), v_cache=bf16(w.v_cache),
+        page_table=i32(w.page_table), seq_lens=i32(w.seq_lens), parents=i32(w.parents),
+        draft_tokens=i32(w.draft_tokens), target_tokens=i32(w.target_tokens),
+        out=torch.empty((w.B, w.T, w.Hq, w.D), dtype=torch.bfloat16, device=device),
+        lse=torch.empty((w.B, w.Hq, w.T), dtype=torch.float32, device=device),
+        accept_len=torch.empty((w.B,), dtype=torch.int32, device=device),
+        path=torch.empty((w.B, w.max_path), dtype=torch.int32, device=device),
+        bonus=torch.empty((w.B,), dtype=torch.int32, device=device),
+        status=torch.zeros((1,), dtype=torch.int32, device=device),
+        workspace=torch.empty((max(ws, 256),), dtype=torch.uint8, device=device),
+    )

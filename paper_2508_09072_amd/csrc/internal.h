@@ -1,0 +1,70 @@
+// Internal declarations shared by the translation units of libreader_hip.so.
+// Nothing here is part of the C ABI (see include/reader.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "reader.h"
+
+namespace reader {
+
+// Remember which HIP call failed (text returned by reader_last_error_detail()); returns e.
+hipError_t note_hip_error(const char *where, hipError_t e);
+
+// MI355X: 256 compute units in 8 XCDs; the launch planner is written for this part only.
+constexpr int kNumCU = 256;
+constexpr int kNumXCD = 8;
+
+constexpr int kTile = 64;          // keys per tile of the attention main loop
+constexpr int kRowsPerWG = 128;    // query rows (node, grouped head) one workgroup carries
+constexpr int kThreads = 256;      // 4 wavefronts
+constexpr int kMaxBatchScan = 4096;  // sequences the in-kernel prefix scan is sized for
+
+// Everything the attention kernels need, passed by value as the kernel argument.
+struct AttnParams {
+    const uint16_t *q, *k_tree, *v_tree, *k_cache, *v_cache;
+    const int32_t *page_table, *seq_lens, *parents;
+    uint16_t *out;
+    float *lse;
+    float *workspace;  // partial records, see attn_slot_floats()
+    int32_t *status;
+    int32_t B, T, Hq, Hkv, D, G, M;       // G = Hq/Hkv, M = T*G query rows per (sequence, kv head)
+    int32_t max_pages, max_seq_len;
+    int32_t n_tree_tiles;                  // ceil(T / kTile)
+    int32_t n_row_chunks;                  // ceil(M / kRowsPerWG)
+    int32_t n_ranges;                      // workgroups along the flattened (pair, tile) axis
+    int64_t num_pages;
+    float scale_log2;                      // sm_scale * log2(e)
+};
+
+// Floats in one partial record: kRowsPerWG rows of D outputs, then running max, then running sum.
+__host__ __device__ inline size_t attn_slot_floats(int D) { return (size_t)kRowsPerWG * (size_t)(D + 2); }
+
+// Number of range workgroups the planner picks; a pure function of the dims so that
+// reader_workspace_bytes and the launch agree.
+int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len);
+
+// ev_start / ev_stop: optional events recorded around the main kernel only.
+hipError_t launch_tree_attn_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
+hipError_t launch_tree_attn_scalar(const AttnParams &p, hipStream_t stream);
+
+struct AcceptParams {
+    const int32_t *draft, *target, *parents;
+    int32_t *accept_len, *path, *bonus, *status;
+    int32_t B, T, max_path;
+};
+hipError_t launch_accept_path(const AcceptParams &p, hipStream_t stream);
+
+struct CompactParams {
+    const uint16_t *k_tree, *v_tree;
+    const int32_t *path, *accept_len, *page_table;
+    uint16_t *k_cache, *v_cache;
+    int32_t *seq_lens, *status;
+    int32_t B, T, Hkv, D, max_pages, max_path;
+    int64_t num_pages;
+};
+hipError_t launch_kv_compact(const CompactParams &p, hipStream_t stream);
+
+}  // namespace reader

@@ -1,0 +1,225 @@
+// C ABI entry points: argument validation on the host, launch planning, dispatch.
+// The operations themselves are defined in include/reader.h with their citations.
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <utility>
+#include <vector>
+
+#include "internal.h"
+
+namespace reader {
+
+static char g_error_detail[256] = "";
+
+hipError_t note_hip_error(const char *where, hipError_t e) {
+    if (e != hipSuccess) snprintf(g_error_detail, sizeof g_error_detail, "%s: %s", where, hipGetErrorName(e));
+    return e;
+}
+
+static bool dims_ok(const reader_dims *d, int *err) {
+    if (!d) { *err = READER_EINVAL; return false; }
+    if (d->B < 0 || d->T < 1 || d->Hq < 1 || d->Hkv < 1 || d->D < 1 || d->max_pages_per_seq < 0 ||
+        d->max_path < 1 || d->num_pages < 0 || d->Hq % d->Hkv != 0 || d->max_path > d->T) {
+        *err = READER_EINVAL;
+        return false;
+    }
+    if (d->T > READER_MAX_T || (d->D != 64 && d->D != 128) || d->page_size != READER_PAGE_SIZE ||
+        d->Hq / d->Hkv > 16 || d->B > kMaxBatchScan) {
+        *err = READER_EUNSUPPORTED;
+        return false;
+    }
+    return true;
+}
+
+int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len) {
+    // One range workgroup streams a contiguous run of 64-key tiles of the flattened
+    // (sequence, kv head, tile) axis.  Two workgroups fit on a compute unit, so at most
+    // 2 * 256 ranges; short problems get fewer so that a range holds a few tiles.
+    static int forced = -1;
+    if (forced < 0) {
+        const char *e = getenv("READER_ATTN_RANGES");
+        forced = e ? atoi(e) : 0;
+    }
+    long long tiles_per_pair = (max_seq_len + kTile - 1) / kTile + (d.T + kTile - 1) / kTile;
+    long long units = (long long)d.B * d.Hkv * tiles_per_pair;
+    long long n = forced > 0 ? forced : units / 4;
+    if (n > 2 * kNumCU) n = 2 * kNumCU;
+    if (n > units) n = units;
+    if (n < 1) n = 1;
+    if (n >= kNumXCD) n -= n % kNumXCD;  // row chunks of one key range then share an XCD's L2
+    return (int)n;
+}
+
+// Measurement hook state: event pairs recorded around the main attention kernel.
+struct ProfileState {
+    bool on = false;
+    size_t used = 0;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs;
+};
+static ProfileState g_profile;
+constexpr size_t kMaxProfilePairs = 65536;
+
+static bool profile_next(hipEvent_t *a, hipEvent_t *b) {
+    *a = nullptr; *b = nullptr;
+    if (!g_profile.on || g_profile.used >= kMaxProfilePairs) return false;
+    if (g_profile.used == g_profile.pairs.size()) {
+        hipEvent_t s, t;
+        if (hipEventCreate(&s) != hipSuccess) return false;
+        if (hipEventCreate(&t) != hipSuccess) { (void)hipEventDestroy(s); return false; }
+        g_profile.pairs.emplace_back(s, t);
+    }
+    *a = g_profile.pairs[g_profile.used].first;
+    *b = g_profile.pairs[g_profile.used].second;
+    ++g_profile.used;
+    return true;
+}
+
+static int row_chunks(const reader_dims &d) {
+    int M = d.T * (d.Hq / d.Hkv);
+    return (M + kRowsPerWG - 1) / kRowsPerWG;
+}
+
+}  // namespace reader
+
+using namespace reader;
+
+extern "C" const char *reader_version(void) { return "reader-hip 0.1 (gfx950)"; }
+
+extern "C" const char *reader_strerror(int code) {
+    switch (code) {
+        case READER_OK: return "ok";
+        case READER_EINVAL: return "invalid argument";
+        case READER_EUNSUPPORTED: return "size not supported by the kernels";
+        case READER_EWORKSPACE: return "workspace missing or too small";
+        case READER_EHIP: return "HIP launch failed";
+        default: return "unknown error";
+    }
+}
+
+extern "C" const char *reader_last_error_detail(void) { return g_error_detail; }
+
+extern "C" int reader_validate_tree(const int32_t *parents_host, int32_t B, int32_t T) {
+    if (!parents_host || B < 0 || T < 1) return READER_EINVAL;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t *p = parents_host + (size_t)b * T;
+        if (p[0] != -1) return READER_EINVAL;
+        for (int32_t i = 1; i < T; ++i)
+            if (p[i] < 0 || p[i] >= i) return READER_EINVAL;
+    }
+    return READER_OK;
+}
+
+extern "C" size_t reader_workspace_bytes(const reader_dims *dims, int32_t max_seq_len) {
+    int err = 0;
+    if (!dims_ok(dims, &err) || max_seq_len < 0) return 0;
+    if (dims->B == 0) return 256;
+    size_t slots = 2 * (size_t)attn_plan_ranges(*dims, max_seq_len) * (size_t)row_chunks(*dims);
+    size_t bytes = slots * attn_slot_floats(dims->D) * sizeof(float);
+    return (bytes + 255) & ~(size_t)255;
+}
+
+extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const void *k_tree,
+                                const void *v_tree, const void *k_cache, const void *v_cache,
+                                const int32_t *page_table, const int32_t *seq_lens,
+                                const int32_t *parents, void *out, float *lse, int32_t max_seq_len,
+                                void *workspace, size_t workspace_bytes, int32_t *status,
+                                void *stream) {
+    int err = 0;
+    if (!dims_ok(dims, &err)) return err;
+    if (max_seq_len < 0) return READER_EINVAL;
+    if (dims->B == 0) return READER_OK;
+    if (!q || !k_tree || !v_tree || !k_cache || !v_cache || !page_table || !seq_lens || !parents || !out)
+        return READER_EINVAL;
+    if ((long long)dims->max_pages_per_seq * dims->page_size < max_seq_len) return READER_EINVAL;
+    if (dims->variant != 0 && dims->variant != 1) return READER_EINVAL;
+
+    AttnParams p;
+    p.q = (const uint16_t *)q; p.k_tree = (const uint16_t *)k_tree; p.v_tree = (const uint16_t *)v_tree;
+    p.k_cache = (const uint16_t *)k_cache; p.v_cache = (const uint16_t *)v_cache;
+    p.page_table = page_table; p.seq_lens = seq_lens; p.parents = parents;
+    p.out = (uint16_t *)out; p.lse = lse; p.workspace = (float *)workspace; p.status = status;
+    p.B = dims->B; p.T = dims->T; p.Hq = dims->Hq; p.Hkv = dims->Hkv; p.D = dims->D;
+    p.G = dims->Hq / dims->Hkv; p.M = p.T * p.G;
+    p.max_pages = dims->max_pages_per_seq; p.max_seq_len = max_seq_len;
+    p.n_tree_tiles = (dims->T + kTile - 1) / kTile;
+    p.n_row_chunks = row_chunks(*dims);
+    p.n_ranges = attn_plan_ranges(*dims, max_seq_len);
+    p.num_pages = dims->num_pages;
+    float scale = dims->sm_scale > 0.f ? dims->sm_scale : 1.0f / sqrtf((float)dims->D);
+    p.scale_log2 = scale * 1.44269504088896340736f;
+
+    hipError_t e;
+    if (dims->variant == 1) {
+        e = launch_tree_attn_scalar(p, (hipStream_t)stream);
+    } else {
+        if (!workspace || ((uintptr_t)workspace & 255) != 0) return READER_EWORKSPACE;
+        if (workspace_bytes < reader_workspace_bytes(dims, max_seq_len)) return READER_EWORKSPACE;
+        hipEvent_t ev_a, ev_b;
+        profile_next(&ev_a, &ev_b);
+        e = launch_tree_attn_mfma(p, (hipStream_t)stream, ev_a, ev_b);
+    }
+    return e == hipSuccess ? READER_OK : READER_EHIP;
+}
+
+extern "C" int reader_profile_enable(int32_t on) {
+    g_profile.on = on != 0;
+    return READER_OK;
+}
+
+extern "C" int reader_profile_collect(double *kernel_ms_sum, int32_t *launches) {
+    if (!kernel_ms_sum || !launches) return READER_EINVAL;
+    double sum = 0.0;
+    int32_t n = 0;
+    int rc = READER_OK;
+    for (size_t i = 0; i < g_profile.used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_profile.pairs[i].second) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_profile.pairs[i].first, g_profile.pairs[i].second) != hipSuccess) {
+            rc = READER_EHIP;
+            continue;
+        }
+        sum += ms;
+        ++n;
+    }
+    g_profile.used = 0;
+    *kernel_ms_sum = sum;
+    *launches = n;
+    return rc;
+}
+
+extern "C" int reader_accept_path(const reader_dims *dims, const int32_t *draft_tokens,
+                                  const int32_t *target_tokens, const int32_t *parents,
+                                  int32_t *accept_len, int32_t *path, int32_t *bonus_token,
+                                  int32_t *status, void *stream) {
+    int err = 0;
+    if (!dims_ok(dims, &err)) return err;
+    if (dims->B == 0) return READER_OK;
+    if (!draft_tokens || !target_tokens || !parents || !accept_len || !path || !bonus_token)
+        return READER_EINVAL;
+    AcceptParams p;
+    p.draft = draft_tokens; p.target = target_tokens; p.parents = parents;
+    p.accept_len = accept_len; p.path = path; p.bonus = bonus_token; p.status = status;
+    p.B = dims->B; p.T = dims->T; p.max_path = dims->max_path;
+    return launch_accept_path(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
+}
+
+extern "C" int reader_kv_compact(const reader_dims *dims, const void *k_tree, const void *v_tree,
+                                 const int32_t *path, const int32_t *accept_len, void *k_cache,
+                                 void *v_cache, const int32_t *page_table, int32_t *seq_lens,
+                                 int32_t *status, void *stream) {
+    int err = 0;
+    if (!dims_ok(dims, &err)) return err;
+    if (dims->B == 0) return READER_OK;
+    if (!k_tree || !v_tree || !path || !accept_len || !k_cache || !v_cache || !page_table || !seq_lens)
+        return READER_EINVAL;
+    CompactParams p;
+    p.k_tree = (const uint16_t *)k_tree; p.v_tree = (const uint16_t *)v_tree;
+    p.path = path; p.accept_len = accept_len; p.page_table = page_table;
+    p.k_cache = (uint16_t *)k_cache; p.v_cache = (uint16_t *)v_cache;
+    p.seq_lens = seq_lens; p.status = status;
+    p.B = dims->B; p.T = dims->T; p.Hkv = dims->Hkv; p.D = dims->D;
+    p.max_pages = dims->max_pages_per_seq; p.max_path = dims->max_path; p.num_pages = dims->num_pages;
+    return launch_kv_compact(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
+}

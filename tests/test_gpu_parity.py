@@ -1,0 +1,275 @@
+"""Parity of the HIP library (through its C ABI) against the CPU oracle, on a real MI355X.
+
+Attention: |gpu - oracle| <= 2e-2 + 2e-2 * |oracle| element by element (bf16 outputs,
+fp32 accumulation).  Acceptance and compaction: bit-exact.
+"""
+import numpy as np
+import pytest
+
+from paper_2508_09072_amd import workloads as W
+from helpers import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def R():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2508_09072_amd import binding
+    binding.load()          # raises if the HIP library was not built: no fallback
+    return binding
+
+
+def bf16_to_np(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def run_attn(R, w, variant=0, want_status=0, sm_scale=0.0):
+    import torch
+    dw = R.to_device(w, variant=variant, sm_scale=sm_scale)
+    dw.out.fill_(float("nan"))
+    dw.lse.fill_(float("nan"))
+    R.reader_tree_attn(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table,
+                       dw.seq_lens, dw.parents, dw.out, dw.lse, dw.max_seq_len, dw.workspace, dw.status)
+    torch.cuda.synchronize()
+    assert int(dw.status.item()) == want_status
+    return bf16_to_np(dw.out), dw.lse.cpu().numpy().astype(np.float64)
+
+
+def check_attn(R, oracle_mod, w, variants=(0, 1), sm_scale=0.0):
+    ref, ref_lse = oracle_mod.tree_attn(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table,
+                                        w.seq_lens, w.parents, sm_scale=sm_scale)
+    for variant in variants:
+        print("attn parity:", w.name, "variant", variant, "B", w.B, "T", w.T, "L", w.seq_lens[:6], flush=True)
+        out, lse = run_attn(R, w, variant=variant, sm_scale=sm_scale)
+        assert_close(out, ref, what="%s variant %d out" % (w.name, variant))
+        assert_close(lse, ref_lse, what="%s variant %d lse" % (w.name, variant))
+
+
+# ------------------------------------------------------------------ attention, whole outputs
+
+@pytest.mark.parametrize("index,scale", [(0, 1.0), (1, 1.0), (2, 0.25), (3, 0.03), (4, 0.04)])
+def test_attn_presets_element_by_element(R, oracle_mod, index, scale):
+    # presets 0 and 1 at full size; 2-4 with shortened prefixes (still several 64-key tiles,
+    # ragged tails, several workgroups per pair) so that the oracle finishes in seconds
+    w = W.make_config(index, length_scale=scale)
+    check_attn(R, oracle_mod, w, variants=(0, 1) if index < 2 else (0,))
+
+
+@pytest.mark.parametrize("L", [0, 1, 15, 16, 63, 64, 65, 127, 129, 500])
+def test_attn_prefix_length_edges(R, oracle_mod, L):
+    w = W.make_custom("edge_L%d" % L, B=2, Hq=8, Hkv=2, D=128, T=20, seq_lens=[L, max(0, L - 1)],
+                      tree="uniform", depth=5, seed=100 + L)
+    check_attn(R, oracle_mod, w)
+
+
+@pytest.mark.parametrize("T,tree", [(1, "chain"), (2, "chain"), (31, "uniform"), (64, "trie"), (65, "uniform"),
+                                    (128, "chain"), (128, "star"), (128, "trie")])
+def test_attn_tree_shapes(R, oracle_mod, T, tree):
+    w = W.make_custom("tree_%s_T%d" % (tree, T), B=2, Hq=4, Hkv=2, D=128, T=T, seq_lens=[70, 200],
+                      tree=tree, depth=12, branch=8, seed=200 + T)
+    check_attn(R, oracle_mod, w)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(8, 8, 64), (8, 2, 64), (16, 2, 64), (4, 4, 128), (16, 2, 128), (32, 2, 128)])
+def test_attn_head_layouts(R, oracle_mod, Hq, Hkv, D):
+    w = W.make_custom("heads_%d_%d_%d" % (Hq, Hkv, D), B=3, Hq=Hq, Hkv=Hkv, D=D, T=24,
+                      seq_lens=[130, 5, 321], tree="trie", depth=6, branch=3, seed=300 + Hq + D)
+    check_attn(R, oracle_mod, w)
+
+
+def test_attn_many_short_sequences(R, oracle_mod):
+    # more pairs than a workgroup range holds tiles: ranges cover several whole pairs
+    rng = np.random.Generator(np.random.PCG64(5))
+    w = W.make_custom("many_short", B=40, Hq=8, Hkv=4, D=128, T=8, seq_lens=rng.integers(0, 90, size=40),
+                      tree="uniform", depth=4, seed=401)
+    check_attn(R, oracle_mod, w)
+
+
+def test_attn_custom_scale_and_peaked_scores(R, oracle_mod):
+    w = W.make_custom("peaked", B=1, Hq=8, Hkv=2, D=128, T=16, seq_lens=[700], tree="trie", depth=5,
+                      k_outlier_frac=0.05, seed=402)
+    check_attn(R, oracle_mod, w)
+    check_attn(R, oracle_mod, w, sm_scale=0.2)
+
+
+def test_attn_max_seq_len_bound_may_be_loose(R, oracle_mod):
+    import torch
+    w = W.make_custom("loose", B=2, Hq=8, Hkv=2, D=128, T=12, seq_lens=[100, 333], seed=403)
+    ref, _ = oracle_mod.tree_attn(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table, w.seq_lens, w.parents)
+    dw = R.to_device(w)
+    bound = w.max_pages * 16
+    ws = torch.empty(R.reader_workspace_bytes(dw.dims, bound), dtype=torch.uint8, device="cuda")
+    R.reader_tree_attn(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table,
+                       dw.seq_lens, dw.parents, dw.out, None, bound, ws, dw.status)
+    torch.cuda.synchronize()
+    assert_close(bf16_to_np(dw.out), ref, what="loose bound")
+
+
+# ------------------------------------------------------------------ attention, full size, sampled rows
+
+@pytest.mark.parametrize("index", [2, 3, 4])
+def test_attn_full_size_sampled_rows(R, oracle_mod, index):
+    # the launch configuration the benchmark times; the oracle checks a sample of output rows
+    w = W.make_config(index)
+    print("full-size attn:", w.name, flush=True)
+    out, lse = run_attn(R, w)
+    rng = np.random.Generator(np.random.PCG64(900 + index))
+    n = 96
+    rows = np.stack([rng.integers(0, w.B, n), rng.integers(0, w.Hq, n), rng.integers(0, w.T, n)], axis=1).astype(np.int32)
+    rows[0] = (0, 0, 0)
+    rows[1] = (w.B - 1, w.Hq - 1, w.T - 1)
+    ref, ref_lse = oracle_mod.tree_attn_rows(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table,
+                                             w.seq_lens, w.parents, rows)
+    got = np.stack([out[b, i, hq] for b, hq, i in rows])
+    got_lse = np.asarray([lse[b, hq, i] for b, hq, i in rows])
+    assert_close(got, ref, what=w.name + " sampled rows")
+    assert_close(got_lse, ref_lse, what=w.name + " sampled lse")
+    assert np.isfinite(out).all()
+
+
+# ------------------------------------------------------------------ device-side input errors
+
+def test_malformed_tree_and_bad_page_set_status_without_faulting(R, oracle_mod):
+    w = W.make_custom("status", B=2, Hq=4, Hkv=2, D=128, T=10, seq_lens=[40, 90], tree="uniform", depth=4, seed=404)
+    w.parents[1, 5] = 7                    # parent after child
+    for variant in (0, 1):
+        run_attn(R, w, variant=variant, want_status=R.STATUS_BAD_TREE)
+    w = W.make_custom("status2", B=2, Hq=4, Hkv=2, D=128, T=10, seq_lens=[40, 90], tree="uniform", depth=4, seed=405)
+    w.page_table[1, 2] = w.num_pages + 5   # outside the pool
+    for variant in (0, 1):
+        out, _ = run_attn(R, w, variant=variant, want_status=R.STATUS_BAD_PAGE)
+        ref, _ = oracle_mod.tree_attn(w.q[:1], w.k_tree[:1], w.v_tree[:1], w.k_cache, w.v_cache,
+                                      w.page_table[:1], w.seq_lens[:1], w.parents[:1])
+        assert_close(out[:1], ref, what="sequence next to the bad one")
+
+
+# ------------------------------------------------------------------ acceptance
+
+def run_accept(R, w):
+    import torch
+    dw = R.to_device(w)
+    dw.path.fill_(-7)
+    R.reader_accept_path(dw.dims, dw.draft_tokens, dw.target_tokens, dw.parents, dw.accept_len, dw.path,
+                         dw.bonus, dw.status)
+    torch.cuda.synchronize()
+    return dw.accept_len.cpu().numpy(), dw.path.cpu().numpy(), dw.bonus.cpu().numpy(), int(dw.status.item())
+
+
+@pytest.mark.parametrize("index", [0, 1, 2, 3, 4])
+def test_accept_presets_bit_exact(R, oracle_mod, index):
+    w = W.make_config(index, length_scale=0.01)          # acceptance does not look at the prefix
+    al, path, bonus, status = run_accept(R, w)
+    ral, rpath, rbonus = oracle_mod.accept_path(w.draft_tokens, w.target_tokens, w.parents, w.max_path)
+    assert status == 0
+    assert np.array_equal(al, ral) and np.array_equal(path, rpath) and np.array_equal(bonus, rbonus)
+
+
+@pytest.mark.parametrize("T", [1, 2, 63, 64, 65, 128])
+def test_accept_random_trees_with_duplicate_siblings(R, oracle_mod, T):
+    rng = np.random.Generator(np.random.PCG64(500 + T))
+    B = 64
+    w = W.make_custom("acc_T%d" % T, B=B, Hq=1, Hkv=1, D=64, T=T, seq_lens=[0] * B, tree="uniform",
+                      depth=min(T - 1, 9) if T > 1 else 0, seed=501 + T, max_path=min(T, 10))
+    w.draft_tokens[:] = rng.integers(0, 3, size=(B, T))     # tiny vocabulary: ties and duplicates
+    w.target_tokens[:] = rng.integers(0, 3, size=(B, T))
+    w.target_tokens[0] = w.draft_tokens[0, 0] = 1            # one sequence where everything matches
+    w.draft_tokens[0] = 1
+    al, path, bonus, status = run_accept(R, w)
+    ral, rpath, rbonus = oracle_mod.accept_path(w.draft_tokens, w.target_tokens, w.parents, w.max_path)
+    assert status == 0 and al.max() >= min(T - 1, 1)
+    assert np.array_equal(al, ral) and np.array_equal(path, rpath) and np.array_equal(bonus, rbonus)
+
+
+def test_accept_path_longer_than_max_path_is_cut_and_flagged(R):
+    w = W.make_custom("cut", B=1, Hq=1, Hkv=1, D=64, T=8, seq_lens=[0], tree="chain", seed=7, max_path=4)
+    w.draft_tokens[:] = 5
+    w.target_tokens[:] = 5
+    w.target_tokens[0, 3] = 9
+    w.draft_tokens[0, 4] = 9                 # still a match: all 7 drafted nodes are acceptable
+    al, path, bonus, status = run_accept(R, w)
+    assert status == R.STATUS_BAD_PATH and al[0] == 3 and path[0].tolist() == [0, 1, 2, 3] and bonus[0] == 9
+
+
+# ------------------------------------------------------------------ compaction and the whole step
+
+def run_step(R, w, with_attn=True):
+    """attention -> acceptance -> compaction on one stream, as the benchmark does."""
+    import torch
+    dw = R.to_device(w)
+    if with_attn:
+        R.reader_tree_attn(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table,
+                           dw.seq_lens, dw.parents, dw.out, dw.lse, dw.max_seq_len, dw.workspace, dw.status)
+    R.reader_accept_path(dw.dims, dw.draft_tokens, dw.target_tokens, dw.parents, dw.accept_len, dw.path,
+                         dw.bonus, dw.status)
+    R.reader_kv_compact(dw.dims, dw.k_tree, dw.v_tree, dw.path, dw.accept_len, dw.k_cache, dw.v_cache,
+                        dw.page_table, dw.seq_lens, dw.status)
+    torch.cuda.synchronize()
+    return dw
+
+
+def oracle_step(oracle_mod, w):
+    kc, vc, sl = w.k_cache.copy(), w.v_cache.copy(), w.seq_lens.copy()
+    al, path, bonus = oracle_mod.accept_path(w.draft_tokens, w.target_tokens, w.parents, w.max_path)
+    oracle_mod.kv_compact(w.k_tree, w.v_tree, path, al, kc, vc, w.page_table, sl)
+    return al, path, bonus, kc, vc, sl
+
+
+def cache_bits(t):
+    import torch
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("index,scale", [(0, 1.0), (1, 0.1), (2, 0.1), (3, 0.01), (4, 0.02)])
+def test_compact_presets_bit_exact(R, oracle_mod, index, scale):
+    w = W.make_config(index, length_scale=scale)
+    dw = run_step(R, w, with_attn=False)
+    al, path, bonus, kc, vc, sl = oracle_step(oracle_mod, w)
+    assert int(dw.status.item()) == 0
+    assert np.array_equal(dw.seq_lens.cpu().numpy(), sl)
+    assert np.array_equal(cache_bits(dw.k_cache), kc) and np.array_equal(cache_bits(dw.v_cache), vc)
+
+
+def test_compact_page_boundaries_and_long_paths(R, oracle_mod):
+    w = W.make_custom("compact_edges", B=8, Hq=4, Hkv=4, D=64, T=40, seq_lens=[0, 1, 15, 16, 17, 31, 32, 200],
+                      tree="chain", vocab=2, p_match=0.97, seed=601)
+    dw = run_step(R, w, with_attn=False)
+    al, path, bonus, kc, vc, sl = oracle_step(oracle_mod, w)
+    assert al.max() >= 17                                   # spans more than one whole page
+    assert int(dw.status.item()) == 0 and np.array_equal(dw.seq_lens.cpu().numpy(), sl)
+    assert np.array_equal(cache_bits(dw.k_cache), kc) and np.array_equal(cache_bits(dw.v_cache), vc)
+
+
+def test_compact_refuses_bad_items_and_leaves_the_sequence_alone(R):
+    import torch
+    w = W.make_custom("compact_bad", B=3, Hq=2, Hkv=2, D=64, T=6, seq_lens=[20, 30, 40], tree="chain", seed=602)
+    dw = R.to_device(w)
+    dw.accept_len.copy_(torch.tensor([1, 9, 1], dtype=torch.int32))           # 9 > max_path - 1
+    dw.path.copy_(torch.tensor([[0, 1, -1, -1, -1, -1], [0, 1, 2, 3, 4, 5], [0, 77, -1, -1, -1, -1]], dtype=torch.int32))
+    R.reader_kv_compact(dw.dims, dw.k_tree, dw.v_tree, dw.path, dw.accept_len, dw.k_cache, dw.v_cache,
+                        dw.page_table, dw.seq_lens, dw.status)
+    torch.cuda.synchronize()
+    assert int(dw.status.item()) == R.STATUS_BAD_PATH
+    assert dw.seq_lens.cpu().tolist() == [22, 30, 40]
+    k = cache_bits(dw.k_cache)
+    changed = (k != w.k_cache).any(axis=(1, 3)).sum()
+    assert changed == 2
+
+
+@pytest.mark.parametrize("index,scale", [(0, 1.0), (2, 0.1)])
+def test_whole_step_then_next_step_attention(R, oracle_mod, index, scale):
+    # One full step, then attention again over the grown cache: what a decoding loop does.
+    import torch
+    w = W.make_config(index, length_scale=scale)
+    dw = run_step(R, w)
+    al, path, bonus, kc, vc, sl = oracle_step(oracle_mod, w)
+    assert np.array_equal(dw.accept_len.cpu().numpy(), al) and np.array_equal(dw.bonus.cpu().numpy(), bonus)
+    assert np.array_equal(dw.seq_lens.cpu().numpy(), sl)
+    assert np.array_equal(cache_bits(dw.k_cache), kc) and np.array_equal(cache_bits(dw.v_cache), vc)
+    # second step: same tree tensors over the grown prefix
+    ref, _ = oracle_mod.tree_attn(w.q, w.k_tree, w.v_tree, kc, vc, w.page_table, sl, w.parents)
+    R.reader_tree_attn(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table,
+                       dw.seq_lens, dw.parents, dw.out, dw.lse, int(sl.max()), dw.workspace, dw.status)
+    torch.cuda.synchronize()
+    assert_close(bf16_to_np(dw.out), ref, what="second step")
