@@ -114,41 +114,53 @@ __device__ inline int range_of_unit(long long x, long long U, int n_ranges) {
     return (int)w;
 }
 
-__device__ inline int pick4(int a0, int a1, int a2, int a3, int idx) {
-    int lo = (idx & 1) ? a1 : a0;
-    int hi = (idx & 1) ? a3 : a2;
-    return (idx & 2) ? hi : lo;
+// 16 bytes as a native vector (selects and copies of it stay in registers)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ inline u32x4 ld16(const void *ptr) { return *reinterpret_cast<const u32x4 *>(ptr); }
+__device__ inline u32x4 keep_if(bool ok, u32x4 v) {
+    v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
+    return v;
 }
-
-__device__ inline uint4 ld16(const uint16_t *ptr) { return *reinterpret_cast<const uint4 *>(ptr); }
 
 template <int D>
 struct Geometry {
-    static constexpr int kChunks = D / 8;                          // 16-byte chunks per K/V row
-    static constexpr int kKLoads = kTile * kChunks / kThreads;     // K chunks per thread per tile
-    static constexpr int kVLoads = (kTile / 2) * kChunks / kThreads;  // key pairs x chunks per thread
-    static constexpr int kKBytes = kTile * D * 2;
-    static constexpr int kVBytes = D * kTile * 2;
-    static constexpr int kBufBytes = kKBytes + kVBytes;
-    static constexpr int kKSteps = D / 16;                         // MFMA k-steps of the QK product
-    static constexpr int kOBlocks = D / 32;                        // 32-wide blocks of the output dim
+    static constexpr int kChunks = D / 8;                       // 16-byte chunks per K/V row
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kTileBytes = kTile * kRowBytes;        // one K (or V) tile in LDS
+    static constexpr int kBufBytes = 2 * kTileBytes;            // K tile then V tile
+    static constexpr int kKeysPerPass = kThreads / kChunks;     // keys one load instruction of the workgroup covers
+    static constexpr int kLoads = kTile / kKeysPerPass;         // loads per thread per tile, for K and for V each
+    static constexpr int kKSteps = D / 16;                      // MFMA k-steps of the QK product
+    static constexpr int kOBlocks = D / 32;                     // 32-wide blocks of the output dim
 };
+
+// 16-byte chunks of a row are XOR-swizzled by the row index so that the matrix-core
+// operand reads below touch every LDS bank once.  K is read 16 bytes per lane from 8
+// consecutive rows; V is read through the transposing 8-byte load from 4 consecutive
+// rows, two adjacent chunks each, hence the different bit order.
+__device__ inline int swizzle_k(int row) { return row & 7; }
+__device__ inline int swizzle_v(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
 
 // Registers a thread holds for the tile that is in flight from HBM.
 template <int D>
 struct Staged {
-    uint4 k[Geometry<D>::kKLoads];
-    uint4 va[Geometry<D>::kVLoads], vb[Geometry<D>::kVLoads];
+    u32x4 k[Geometry<D>::kLoads];
+    u32x4 v[Geometry<D>::kLoads];
+    unsigned real;   // bit i: load i fetched an existing row (others are written to LDS as zeros)
 };
 
-// Issue the global loads of one unit.  Rows that do not exist (past the sequence end, past
-// the last tree node, behind an invalid page id) are staged as zeros: a zero K row is
-// masked later, a zero V row contributes nothing.
+// Issue the global loads of one unit: a wave-uniform base address per load instruction
+// plus one 32-bit lane offset.  Rows that do not exist (past the sequence end, past the
+// last tree node, behind an invalid page id) read a harmless valid address and are
+// replaced by zeros when they are written to LDS: a zero K row is masked later, a zero V
+// row contributes nothing.
 template <int D>
 __device__ inline void issue_loads(const AttnParams &p, const Cursor &c, Staged<D> &st, int &bad) {
     using G = Geometry<D>;
     const int tid = threadIdx.x;
-    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int key0 = tid / G::kChunks, chunk = tid % G::kChunks;   // this thread's key in pass 0
+    st.real = 0u;
     if (c.idx < c.n_pre) {
         const int base = c.idx * kTile;
         const int n_valid = min(kTile, c.L - base);
@@ -162,82 +174,51 @@ __device__ inline void issue_loads(const AttnParams &p, const Cursor &c, Staged<
                 if (v >= 0 && v < p.num_pages) pg[j] = v; else bad |= READER_STATUS_BAD_PAGE;
             }
         }
+        const size_t page_stride = (size_t)p.Hkv * 16 * D;           // elements
+        const size_t head_off = (size_t)c.hkv * 16 * D;
+        const unsigned voff = ((key0 & 15) * D + chunk * 8) * 2;      // bytes inside the (page, head) block
 #pragma unroll
-        for (int i = 0; i < G::kKLoads; ++i) {
-            const int id = tid + kThreads * i;
-            const int key = id / G::kChunks, chunk = id % G::kChunks;
-            const int page = pick4(pg[0], pg[1], pg[2], pg[3], key >> 4);
-            const bool ok = key < n_valid && page >= 0;
-            const size_t off = (((size_t)(ok ? page : 0) * p.Hkv + c.hkv) * 16 + (key & 15)) * D + chunk * 8;
-            st.k[i] = ok ? ld16(p.k_cache + off) : zero;
-        }
-#pragma unroll
-        for (int i = 0; i < G::kVLoads; ++i) {
-            const int id = tid + kThreads * i;
-            const int key = 2 * (id / G::kChunks), chunk = id % G::kChunks;
-            const int page = pick4(pg[0], pg[1], pg[2], pg[3], key >> 4);
-            const bool ok0 = key < n_valid && page >= 0, ok1 = key + 1 < n_valid && page >= 0;
-            const size_t off = (((size_t)(ok0 ? page : 0) * p.Hkv + c.hkv) * 16 + (key & 15)) * D + chunk * 8;
-            st.va[i] = ok0 ? ld16(p.v_cache + off) : zero;
-            st.vb[i] = ok1 ? ld16(p.v_cache + off + D) : zero;
+        for (int i = 0; i < G::kLoads; ++i) {
+            const int pj = i * (G::kKeysPerPass / 16) + (wave_s * 64 / G::kChunks) / 16;   // wave-uniform
+            const int page = pj == 0 ? pg[0] : pj == 1 ? pg[1] : pj == 2 ? pg[2] : pg[3];
+            const bool ok = page >= 0 && key0 + i * G::kKeysPerPass < n_valid;
+            const size_t eoff = (size_t)(page >= 0 ? page : 0) * page_stride + head_off;
+            const unsigned vo = ok ? voff : 0u;
+            st.k[i] = ld16(reinterpret_cast<const char *>(p.k_cache + eoff) + vo);
+            st.v[i] = ld16(reinterpret_cast<const char *>(p.v_cache + eoff) + vo);
+            st.real |= ok ? (1u << i) : 0u;
         }
     } else {
         const int base = (c.idx - c.n_pre) * kTile;
         const int n_valid = min(kTile, p.T - base);
-        const size_t row_stride = (size_t)p.Hkv * D;
+        const unsigned row_bytes = (unsigned)p.Hkv * D * 2;
         const size_t origin = (((size_t)c.b * p.T + base) * p.Hkv + c.hkv) * D;
 #pragma unroll
-        for (int i = 0; i < G::kKLoads; ++i) {
-            const int id = tid + kThreads * i;
-            const int key = id / G::kChunks, chunk = id % G::kChunks;
+        for (int i = 0; i < G::kLoads; ++i) {
+            const int key = key0 + i * G::kKeysPerPass;
             const bool ok = key < n_valid;
-            st.k[i] = ok ? ld16(p.k_tree + origin + (size_t)key * row_stride + chunk * 8) : zero;
-        }
-#pragma unroll
-        for (int i = 0; i < G::kVLoads; ++i) {
-            const int id = tid + kThreads * i;
-            const int key = 2 * (id / G::kChunks), chunk = id % G::kChunks;
-            const size_t off = origin + (size_t)key * row_stride + chunk * 8;
-            st.va[i] = key < n_valid ? ld16(p.v_tree + off) : zero;
-            st.vb[i] = key + 1 < n_valid ? ld16(p.v_tree + off + row_stride) : zero;
+            const unsigned vo = ok ? (unsigned)key * row_bytes + chunk * 16 : 0u;
+            st.k[i] = ld16(reinterpret_cast<const char *>(p.k_tree + origin) + vo);
+            st.v[i] = ld16(reinterpret_cast<const char *>(p.v_tree + origin) + vo);
+            st.real |= ok ? (1u << i) : 0u;
         }
     }
 }
 
-// Where key `key` of a tile sits along the key axis of the transposed V tile: the order
-// in which the S^T accumulator registers of a lane enumerate the keys.
-__device__ inline int vt_column(int key) {
-    const int r = key & 31;
-    return (key & 32) + ((r >> 4) << 4) + (((r >> 2) & 1) << 3) + (((r >> 3) & 1) << 2) + (r & 3);
-}
-
-// Staged registers -> LDS.  K keeps its row-major form; V is written transposed,
-// two keys (one 32-bit word) at a time.  Both use 16-byte chunks XOR-swizzled by row.
+// Staged registers -> LDS, both tiles row-major with swizzled 16-byte chunks.
 template <int D>
-__device__ inline void write_stage(const Staged<D> &st, char *k_lds, char *vt_lds) {
+__device__ inline void write_stage(const Staged<D> &st, char *k_lds, char *v_lds) {
     using G = Geometry<D>;
     const int tid = threadIdx.x;
+    const int key0 = tid / G::kChunks, chunk = tid % G::kChunks;
+    // kKeysPerPass is a multiple of 8, so the swizzle of a thread's row is the same in every pass
+    const int koff = key0 * G::kRowBytes + ((chunk ^ swizzle_k(key0)) << 4);
+    const int voff = key0 * G::kRowBytes + ((chunk ^ swizzle_v(key0)) << 4);
 #pragma unroll
-    for (int i = 0; i < G::kKLoads; ++i) {
-        const int id = tid + kThreads * i;
-        const int key = id / G::kChunks, chunk = id % G::kChunks;
-        *reinterpret_cast<uint4 *>(k_lds + key * (D * 2) + ((chunk ^ (key & 7)) << 4)) = st.k[i];
-    }
-#pragma unroll
-    for (int i = 0; i < G::kVLoads; ++i) {
-        const int id = tid + kThreads * i;
-        const int key = 2 * (id / G::kChunks), chunk = id % G::kChunks;
-        const int col = vt_column(key);           // even; key + 1 sits at col + 1
-        const uint32_t a[4] = {st.va[i].x, st.va[i].y, st.va[i].z, st.va[i].w};
-        const uint32_t b[4] = {st.vb[i].x, st.vb[i].y, st.vb[i].z, st.vb[i].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t lo = (e & 1) ? (a[e >> 1] >> 16) : (a[e >> 1] & 0xffffu);
-            const uint32_t hi = (e & 1) ? (b[e >> 1] & 0xffff0000u) : (b[e >> 1] << 16);
-            const int d = chunk * 8 + e;
-            const int swz = (e ^ chunk) & 7;      // (d ^ (d >> 3)) & 7
-            *reinterpret_cast<uint32_t *>(vt_lds + d * (kTile * 2) + (((col >> 3) ^ swz) << 4) + (col & 7) * 2) = lo | hi;
-        }
+    for (int i = 0; i < G::kLoads; ++i) {
+        const bool real = (st.real >> i) & 1u;
+        *reinterpret_cast<u32x4 *>(k_lds + koff + i * G::kKeysPerPass * G::kRowBytes) = keep_if(real, st.k[i]);
+        *reinterpret_cast<u32x4 *>(v_lds + voff + i * G::kKeysPerPass * G::kRowBytes) = keep_if(real, st.v[i]);
     }
 }
 
@@ -247,6 +228,16 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
     v[0] = (__bf16)lo;
     v[1] = (__bf16)hi;
     return __builtin_bit_cast(uint32_t, v);
+}
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// Transposing LDS load of gfx950: within each group of 16 lanes the 16 x 4 block of
+// 16-bit elements the lanes point at (lane k supplies 4 consecutive elements) is read
+// as 4 rows of 16, and lane i receives element i of each row.
+__device__ inline s16x4 lds_read_tr16(const char *ptr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(ptr));
 }
 
 }  // namespace
@@ -259,8 +250,8 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     char *buf1 = smem + G::kBufBytes;
     uint32_t *s_anc = reinterpret_cast<uint32_t *>(smem + 2 * G::kBufBytes);   // [READER_MAX_T][4]
     int *s_par = reinterpret_cast<int *>(s_anc + READER_MAX_T * 4);            // [READER_MAX_T]
-    int *s_pref = s_par + READER_MAX_T;                                        // [B + 1]
-    __shared__ int s_wsum[4];
+    int *s_wsum = s_par + READER_MAX_T;                                        // [4]
+    int *s_pref = s_wsum + 4;                                                  // [B + 1]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, h = lane >> 5;
@@ -277,23 +268,39 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     const long long lo = range_begin(blockIdx.x, U, p.n_ranges);
     const long long hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
     if (lo >= hi) return;
+    const int n_iter = (int)(hi - lo);
 
-    Cursor cc;   // unit being computed
-    cc.b = find_seq(s_pref, p.B, p.Hkv, lo);
+    Cursor cc;   // unit being computed; every field is wave-uniform and kept in scalar registers
+    cc.b = __builtin_amdgcn_readfirstlane(find_seq(s_pref, p.B, p.Hkv, lo));
     cursor_enter_seq(cc, p);
     {
         const long long rel = lo - (long long)p.Hkv * s_pref[cc.b];
-        cc.hkv = (int)(rel / cc.n_units);
-        cc.idx = (int)(rel - (long long)cc.hkv * cc.n_units);
+        const int hkv = (int)(rel / cc.n_units);
+        cc.hkv = __builtin_amdgcn_readfirstlane(hkv);
+        cc.idx = __builtin_amdgcn_readfirstlane((int)(rel - (long long)hkv * cc.n_units));
     }
     Cursor lc = cc;   // unit being loaded (one ahead)
 
     int bad = 0;
     Staged<D> st;
     issue_loads<D>(p, lc, st, bad);
-    write_stage<D>(st, buf0, buf0 + G::kKBytes);
+    write_stage<D>(st, buf0, buf0 + G::kTileBytes);
     cursor_advance(lc, p);
     __syncthreads();
+
+    // per-lane LDS offsets of the matrix-core operand reads
+    int k_rd[4];   // K fragment of k-step kk: k_rd[kk & 3] + (kk >> 2) * 128 (+ 32 rows for the second key block)
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) k_rd[kk] = n * G::kRowBytes + (((2 * kk + h) ^ swizzle_k(n)) << 4);
+    int v_rd[2];   // V fragment of output block db: v_rd[db & 1] + (db >> 1) * 128 (+ key rows)
+    {
+        const int i16 = lane & 15, g16 = (lane >> 4) & 1;
+        const int key_lo = 4 * h + (i16 >> 2);                       // key row inside an 8-key group
+        const int c_lo = 2 * g16 + ((i16 & 3) >> 1);                 // 16-byte chunk inside the 32-wide d block
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+            v_rd[db] = key_lo * G::kRowBytes + ((((db * 4) | c_lo) ^ swizzle_v(key_lo)) << 4) + (i16 & 1) * 8;
+    }
 
     bf16x8 qf[G::kKSteps];
     f32x16 o[G::kOBlocks];
@@ -302,12 +309,10 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     bool seg_from_pair_start = false;
     const float c2 = p.scale_log2;
 
-    for (long long x = lo; x < hi; ++x) {
-        const int cur = (int)((x - lo) & 1);
-        char *k_lds = (cur ? buf1 : buf0);
-        char *vt_lds = k_lds + G::kKBytes;
-        const bool more = x + 1 < hi;
-        if (more) issue_loads<D>(p, lc, st, bad);
+    for (int it = 0; it < n_iter; ++it) {
+        char *k_lds = (it & 1) ? buf1 : buf0;
+        char *v_lds = k_lds + G::kTileBytes;
+        const bool more = it + 1 < n_iter;
 
         if (fresh) {
             fresh = false;
@@ -322,12 +327,10 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             const uint16_t *qrow = p.q + (((size_t)cc.b * p.T + node) * p.Hq + cc.hkv * p.G + group) * D;
 #pragma unroll
             for (int kk = 0; kk < G::kKSteps; ++kk) {
-                uint4 v = row_real ? ld16(qrow + kk * 16 + h * 8) : make_uint4(0u, 0u, 0u, 0u);
-                qf[kk] = __builtin_bit_cast(bf16x8, v);
+                qf[kk] = __builtin_bit_cast(bf16x8, keep_if(row_real, ld16(qrow + kk * 16 + h * 8)));
             }
             // ancestor-or-self masks of this sequence's tree, if this segment reaches its tree tiles
-            const long long seg_end_idx = (long long)cc.idx + (hi - x);   // exclusive, in pair units
-            if (seg_end_idx > cc.n_pre) {
+            if (cc.idx + (n_iter - it) > cc.n_pre) {
                 __syncthreads();   // previous users of s_anc / s_par are done
                 if (tid < p.T) {
                     int pi = p.parents[(size_t)cc.b * p.T + tid];
@@ -350,21 +353,35 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             }
         }
 
+        if (more) issue_loads<D>(p, lc, st, bad);
+
         if (wave_active) {
             // ---- S^T = K . Q^T : two 32-key blocks ----
+            // All fragment reads of a block are issued before its first matrix instruction,
+            // and the second block's reads are interleaved with the first block's products.
             f32x16 s[2];
+            bf16x8 ka[2][G::kKSteps];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int kk = 0; kk < G::kKSteps; ++kk)
+                    ka[kb][kk] = *reinterpret_cast<const bf16x8 *>(
+                        k_lds + k_rd[kk & 3] + (kk >> 2) * 128 + kb * 32 * G::kRowBytes);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
-                const int row = kb * 32 + n;
 #pragma unroll
-                for (int kk = 0; kk < G::kKSteps; ++kk) {
-                    const int chunk = kk * 2 + h;
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(k_lds + row * (D * 2) + ((chunk ^ (row & 7)) << 4));
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s[kb], 0, 0, 0);
-                }
+                for (int kk = 0; kk < G::kKSteps; ++kk)
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kb][kk], qf[kk], s[kb], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_group_barrier(0x100, G::kKSteps, 0);          // LDS reads of block 0
+#pragma unroll
+            for (int kk = 0; kk < G::kKSteps; ++kk) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one product of block 0
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one read of block 1
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);          // products of block 1
             // ---- masks: ragged last prefix tile, tree tiles ----
             const bool is_tree = cc.idx >= cc.n_pre;
             if (is_tree) {
@@ -419,19 +436,22 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
 #pragma unroll
                     for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
             }
-            // ---- O^T += V^T . P^T ----
+            // ---- O^T += V^T . P^T : the S^T registers of a lane are, 8 at a time, the B operand ----
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 const int kb = ks >> 1, m2 = ks & 1;
-                const uint4 pv = make_uint4(pk[kb][4 * m2], pk[kb][4 * m2 + 1], pk[kb][4 * m2 + 2], pk[kb][4 * m2 + 3]);
+                u32x4 pv;
+                pv.x = pk[kb][4 * m2]; pv.y = pk[kb][4 * m2 + 1]; pv.z = pk[kb][4 * m2 + 2]; pv.w = pk[kb][4 * m2 + 3];
                 const bf16x8 pb = __builtin_bit_cast(bf16x8, pv);
-                const int chunk = ks * 2 + h;
+                const int key_base = (kb * 32 + m2 * 16) * G::kRowBytes;
 #pragma unroll
                 for (int db = 0; db < G::kOBlocks; ++db) {
-                    const int d = db * 32 + n;
-                    const int swz = (d ^ (d >> 3)) & 7;
-                    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(vt_lds + d * (kTile * 2) + ((chunk ^ swz) << 4));
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[db], 0, 0, 0);
+                    const char *src = v_lds + v_rd[db & 1] + (db >> 1) * 128 + key_base;
+                    const s16x4 lo4 = lds_read_tr16(src);                         // keys +0..3 (+4h)
+                    const s16x4 hi4 = lds_read_tr16(src + 8 * G::kRowBytes);      // keys +8..11 (+4h)
+                    typedef short s16x8 __attribute__((ext_vector_type(8)));
+                    const s16x8 a8 = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
                 }
             }
         }
@@ -478,8 +498,8 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         }
 
         if (more) {
-            char *nk = (cur ? buf0 : buf1);
-            write_stage<D>(st, nk, nk + G::kKBytes);
+            char *nk = (it & 1) ? buf0 : buf1;
+            write_stage<D>(st, nk, nk + G::kTileBytes);
             cursor_advance(lc, p);
         }
         cursor_advance(cc, p);
@@ -565,7 +585,7 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
     using G = Geometry<D>;
     const size_t pref_bytes = ((size_t)(p.B + 1) * sizeof(int) + 15) & ~(size_t)15;
     const size_t main_lds = 2 * (size_t)G::kBufBytes + READER_MAX_T * 4 * sizeof(uint32_t) +
-                            READER_MAX_T * sizeof(int) + pref_bytes;
+                            READER_MAX_T * sizeof(int) + 4 * sizeof(int) + pref_bytes;
     // More than 64 KB of LDS per workgroup has to be asked for; the limit counts the
     // kernel's static LDS too, so ask for exactly what this launch needs.
     static size_t lds_allowed = 0;
