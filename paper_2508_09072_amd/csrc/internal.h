@@ -18,9 +18,12 @@ constexpr int kNumCU = 256;
 constexpr int kNumXCD = 8;
 
 constexpr int kTile = 64;          // keys per tile of the attention main loop
-constexpr int kRowsPerWG = 128;    // query rows (node, grouped head) one workgroup carries
-constexpr int kThreads = 256;      // 4 wavefronts
+constexpr int kThreads = 512;      // 8 wavefronts per attention workgroup, one workgroup per compute unit
 constexpr int kMaxBatchScan = 4096;  // sequences the in-kernel prefix scan is sized for
+
+// Query rows (tree node, grouped head) one attention workgroup carries: 4 row blocks of 32
+// with the tile's keys split between two wave groups, or 8 row blocks when T*G > 128.
+__host__ __device__ inline int attn_rows_per_wg(int M) { return M <= 128 ? 128 : 256; }
 
 // Everything the attention kernels need, passed by value as the kernel argument.
 struct AttnParams {
@@ -33,14 +36,15 @@ struct AttnParams {
     int32_t B, T, Hq, Hkv, D, G, M;       // G = Hq/Hkv, M = T*G query rows per (sequence, kv head)
     int32_t max_pages, max_seq_len;
     int32_t n_tree_tiles;                  // ceil(T / kTile)
-    int32_t n_row_chunks;                  // ceil(M / kRowsPerWG)
+    int32_t rows_per_wg;                   // attn_rows_per_wg(M)
+    int32_t n_row_chunks;                  // ceil(M / rows_per_wg)
     int32_t n_ranges;                      // workgroups along the flattened (pair, tile) axis
     int64_t num_pages;
     float scale_log2;                      // sm_scale * log2(e)
 };
 
-// Floats in one partial record: kRowsPerWG rows of D outputs, then running max, then running sum.
-__host__ __device__ inline size_t attn_slot_floats(int D) { return (size_t)kRowsPerWG * (size_t)(D + 2); }
+// Floats in one partial record: `rows` rows of D outputs, then running max, then running sum.
+__host__ __device__ inline size_t attn_slot_floats(int D, int rows) { return (size_t)rows * (size_t)(D + 2); }
 
 // Number of range workgroups the planner picks; a pure function of the dims so that
 // reader_workspace_bytes and the launch agree.

@@ -35,8 +35,9 @@ static bool dims_ok(const reader_dims *d, int *err) {
 
 int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len) {
     // One range workgroup streams a contiguous run of 64-key tiles of the flattened
-    // (sequence, kv head, tile) axis.  Two workgroups fit on a compute unit, so at most
-    // 2 * 256 ranges; short problems get fewer so that a range holds a few tiles.
+    // (sequence, kv head, tile) axis.  One workgroup (8 waves, ~100 KB of LDS) occupies a
+    // compute unit, so at most 256 ranges; short problems get fewer so that a range holds
+    // a few tiles.
     static int forced = -1;
     if (forced < 0) {
         const char *e = getenv("READER_ATTN_RANGES");
@@ -45,7 +46,7 @@ int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len) {
     long long tiles_per_pair = (max_seq_len + kTile - 1) / kTile + (d.T + kTile - 1) / kTile;
     long long units = (long long)d.B * d.Hkv * tiles_per_pair;
     long long n = forced > 0 ? forced : units / 4;
-    if (n > 2 * kNumCU) n = 2 * kNumCU;
+    if (n > kNumCU) n = kNumCU;
     if (n > units) n = units;
     if (n < 1) n = 1;
     if (n >= kNumXCD) n -= n % kNumXCD;  // row chunks of one key range then share an XCD's L2
@@ -78,7 +79,8 @@ static bool profile_next(hipEvent_t *a, hipEvent_t *b) {
 
 static int row_chunks(const reader_dims &d) {
     int M = d.T * (d.Hq / d.Hkv);
-    return (M + kRowsPerWG - 1) / kRowsPerWG;
+    int rows = attn_rows_per_wg(M);
+    return (M + rows - 1) / rows;
 }
 
 }  // namespace reader
@@ -116,7 +118,7 @@ extern "C" size_t reader_workspace_bytes(const reader_dims *dims, int32_t max_se
     if (!dims_ok(dims, &err) || max_seq_len < 0) return 0;
     if (dims->B == 0) return 256;
     size_t slots = 2 * (size_t)attn_plan_ranges(*dims, max_seq_len) * (size_t)row_chunks(*dims);
-    size_t bytes = slots * attn_slot_floats(dims->D) * sizeof(float);
+    size_t bytes = slots * attn_slot_floats(dims->D, attn_rows_per_wg(dims->T * (dims->Hq / dims->Hkv))) * sizeof(float);
     return (bytes + 255) & ~(size_t)255;
 }
 
@@ -133,6 +135,7 @@ extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const vo
     if (!q || !k_tree || !v_tree || !k_cache || !v_cache || !page_table || !seq_lens || !parents || !out)
         return READER_EINVAL;
     if ((long long)dims->max_pages_per_seq * dims->page_size < max_seq_len) return READER_EINVAL;
+    if (max_seq_len > 0 && (dims->num_pages < 1 || dims->max_pages_per_seq < 1)) return READER_EINVAL;
     if (dims->variant != 0 && dims->variant != 1) return READER_EINVAL;
 
     AttnParams p;
@@ -144,6 +147,7 @@ extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const vo
     p.G = dims->Hq / dims->Hkv; p.M = p.T * p.G;
     p.max_pages = dims->max_pages_per_seq; p.max_seq_len = max_seq_len;
     p.n_tree_tiles = (dims->T + kTile - 1) / kTile;
+    p.rows_per_wg = attn_rows_per_wg(p.M);
     p.n_row_chunks = row_chunks(*dims);
     p.n_ranges = attn_plan_ranges(*dims, max_seq_len);
     p.num_pages = dims->num_pages;

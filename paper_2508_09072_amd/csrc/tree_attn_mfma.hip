@@ -5,78 +5,101 @@
 //   prefix tiles (paged cache, mask-free except for the ragged last one), then the
 //   tree tiles (the T tree rows, masked by ancestor-or-self bit masks held in LDS).
 //   All tiles of all pairs form one flat axis of U units.  The grid has n_ranges
-//   workgroups along x; workgroup w streams the contiguous unit range
-//   [w*U/n_ranges, (w+1)*U/n_ranges), so every workgroup moves the same number of
+//   workgroups along x, one per compute unit; workgroup w streams the contiguous unit
+//   range [w*U/n_ranges, (w+1)*U/n_ranges), so every workgroup moves the same number of
 //   K/V bytes whatever the ragged sequence lengths are.  A range may cover several
 //   whole pairs and at most one pair at each end in part.  Whole pairs are finished
 //   in place; a pair cut between workgroups leaves one partial record (unnormalised
 //   output, running max, running sum) per workgroup and a second kernel merges them.
-//   blockIdx.y selects a chunk of 128 query rows when T*G > 128.
+//   blockIdx.y selects a chunk of query rows when T*G exceeds what a workgroup carries.
 //
-// One workgroup = 4 wavefronts; wavefront w owns 32 query rows (a row is a
-// (tree node, grouped query head) pair, so one K/V tile serves all heads of the
-// group and all tree nodes).  Per tile, per wavefront:
-//     S^T[64 keys][32 rows] = K_tile . Q^T        16 x v_mfma_f32_32x32x16_bf16 (D = 128)
-//     online softmax down the key axis: the 32 scores a lane holds all belong to
-//     one query row, so the row max is 31 in-lane max ops and one cross-lane swap
-//     O^T[D][32 rows] += V_tile^T . P^T           16 x v_mfma_f32_32x32x16_bf16
-//   The S^T accumulator layout of the first product is exactly the B-operand
-//   layout the second one needs, up to a fixed permutation of the 64 keys of the
-//   tile; V is stored transposed in LDS under that same permutation, so the
-//   softmax weights never leave the registers.
+// One workgroup = 8 wavefronts.  A query row is a (tree node, grouped query head) pair, so
+// one K/V tile serves all heads of the group and all tree nodes.
+//   T*G <= 128: 4 row blocks of 32 rows x 2 key groups; a wavefront takes one row block
+//               and one 32-key half of every tile, and the two key groups of a row block
+//               merge their softmax states through LDS when a pair (or the range) ends;
+//   T*G  > 128: 8 row blocks of 32 rows, every wavefront takes whole tiles.
+// Per tile and 32-key block a wavefront computes
+//     S^T[32 keys][32 rows] = K_block . Q^T        8 x v_mfma_f32_32x32x16_bf16 (D = 128)
+//     online softmax down the key axis: the scores a lane holds all belong to one
+//     query row, so the row max is in-lane max ops plus one cross-lane swap
+//     O^T[D][32 rows] += V_block^T . P^T           8 x v_mfma_f32_32x32x16_bf16
+//   The S^T accumulator registers of a lane are, eight at a time, exactly the B
+//   operand of the second product, so the softmax weights never leave the registers.
+//   V^T fragments come out of the row-major V tile through the transposing LDS load
+//   (ds_read_b64_tr_b16), K fragments through plain 128-bit LDS loads.
 //
-// K/V tiles go HBM -> registers (128-bit loads, issued one tile ahead) -> LDS
-// (double buffered, XOR-swizzled 16-byte chunks, one barrier per tile).
+// K/V tiles go HBM -> LDS directly (global_load_lds_dwordx4: each wavefront instruction
+// moves 1 KB, no staging registers) into a ring of three tile buffers, so two tiles are
+// in flight while one is consumed; one barrier per tile.  Page ids are fetched with
+// scalar loads one more tile ahead.  16-byte chunks are XOR-swizzled inside a tile row
+// (applied on the global-address side of the copy) so that operand reads hit every LDS
+// bank once.
 #include "internal.h"
 
 namespace reader {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// 16 bytes as a native vector (selects and copies of it stay in registers)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) char lds_char;
+
+// 256 bytes of zeros: the copy source of tile rows that do not exist.
+__device__ __attribute__((aligned(256))) const unsigned int kZeroRow[64] = {0u};
 
 namespace {
 
 constexpr float kLn2 = 0.69314718055994530942f;
+constexpr int kWaves = kThreads / 64;
+constexpr int kStages = 3;
 
-// Position along the flat unit axis: which pair, which tile of it.
+// Position along the flat unit axis: which pair, which tile of it.  Every field is
+// wave-uniform and lives in scalar registers.
 struct Cursor {
     int b, hkv, idx;      // idx: unit index inside the pair
     int n_pre, n_units;   // prefix tiles / all tiles of this pair
     int L;                // clamped prefix length of sequence b
 };
 
-__device__ inline int clamp_len(const AttnParams &p, int b) {
-    int L = p.seq_lens[b];
+__device__ inline int clamp_len(const AttnParams &p, const int32_t *__restrict__ seq_lens, int b) {
+    int L = seq_lens[b];
     L = L < 0 ? 0 : L;
     return L > p.max_seq_len ? p.max_seq_len : L;
 }
 
-__device__ inline void cursor_enter_seq(Cursor &c, const AttnParams &p) {
-    c.L = clamp_len(p, c.b);
+__device__ inline void cursor_enter_seq(Cursor &c, const AttnParams &p, const int32_t *__restrict__ seq_lens) {
+    c.L = clamp_len(p, seq_lens, c.b);
     c.n_pre = (c.L + kTile - 1) / kTile;
     c.n_units = c.n_pre + p.n_tree_tiles;
 }
 
-__device__ inline void cursor_advance(Cursor &c, const AttnParams &p) {
+__device__ inline void cursor_advance(Cursor &c, const AttnParams &p, const int32_t *__restrict__ seq_lens) {
     if (++c.idx == c.n_units) {
         c.idx = 0;
         if (++c.hkv == p.Hkv) {
             c.hkv = 0;
             ++c.b;
-            if (c.b < p.B) cursor_enter_seq(c, p);
+            if (c.b < p.B) cursor_enter_seq(c, p, seq_lens);
         }
     }
 }
 
 // Exclusive prefix sums of tiles-per-pair over the sequences, into s_pref[0..B].
-__device__ inline void scan_units(const AttnParams &p, int *s_pref, int *s_wsum) {
+// Works for any workgroup size that is a multiple of 64 up to 512; s_wsum has 8 entries.
+__device__ inline void scan_units(const AttnParams &p, const int32_t *__restrict__ seq_lens, int *s_pref,
+                                  int *s_wsum) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_threads = blockDim.x, n_waves = n_threads >> 6;
     int carry = 0;
     if (tid == 0) s_pref[0] = 0;
-    for (int base = 0; base < p.B; base += kThreads) {
+    for (int base = 0; base < p.B; base += n_threads) {
         const int b = base + tid;
         int v = 0;
-        if (b < p.B) v = (clamp_len(p, b) + kTile - 1) / kTile + p.n_tree_tiles;
+        if (b < p.B) v = (clamp_len(p, seq_lens, b) + kTile - 1) / kTile + p.n_tree_tiles;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int t = __shfl_up(v, off);
@@ -84,9 +107,11 @@ __device__ inline void scan_units(const AttnParams &p, int *s_pref, int *s_wsum)
         }
         if (lane == 63) s_wsum[wave] = v;
         __syncthreads();
-        int woff = 0;
-        for (int w = 0; w < wave; ++w) woff += s_wsum[w];
-        const int total = s_wsum[0] + s_wsum[1] + s_wsum[2] + s_wsum[3];
+        int woff = 0, total = 0;
+        for (int w = 0; w < n_waves; ++w) {
+            if (w < wave) woff += s_wsum[w];
+            total += s_wsum[w];
+        }
         if (b < p.B) s_pref[b + 1] = carry + woff + v;
         carry += total;
         __syncthreads();
@@ -114,8 +139,6 @@ __device__ inline int range_of_unit(long long x, long long U, int n_ranges) {
     return (int)w;
 }
 
-// 16 bytes as a native vector (selects and copies of it stay in registers)
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 __device__ inline u32x4 ld16(const void *ptr) { return *reinterpret_cast<const u32x4 *>(ptr); }
 __device__ inline u32x4 keep_if(bool ok, u32x4 v) {
     v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
@@ -127,99 +150,150 @@ struct Geometry {
     static constexpr int kChunks = D / 8;                       // 16-byte chunks per K/V row
     static constexpr int kRowBytes = D * 2;
     static constexpr int kTileBytes = kTile * kRowBytes;        // one K (or V) tile in LDS
-    static constexpr int kBufBytes = 2 * kTileBytes;            // K tile then V tile
-    static constexpr int kKeysPerPass = kThreads / kChunks;     // keys one load instruction of the workgroup covers
-    static constexpr int kLoads = kTile / kKeysPerPass;         // loads per thread per tile, for K and for V each
+    static constexpr int kStageBytes = 2 * kTileBytes;          // K tile then V tile
+    static constexpr int kRowsPerCopy = 1024 / kRowBytes;       // tile rows one wavefront copy instruction moves
+    static constexpr int kRowsPerWave = kTile / kWaves;         // tile rows a wavefront copies per tile (8)
+    static constexpr int kCopies = kRowsPerWave / kRowsPerCopy; // copy instructions per wavefront, per tile, for K and for V each
     static constexpr int kKSteps = D / 16;                      // MFMA k-steps of the QK product
     static constexpr int kOBlocks = D / 32;                     // 32-wide blocks of the output dim
 };
 
-// 16-byte chunks of a row are XOR-swizzled by the row index so that the matrix-core
-// operand reads below touch every LDS bank once.  K is read 16 bytes per lane from 8
-// consecutive rows; V is read through the transposing 8-byte load from 4 consecutive
-// rows, two adjacent chunks each, hence the different bit order.
-__device__ inline int swizzle_k(int row) { return row & 7; }
-__device__ inline int swizzle_v(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// LDS has 64 four-byte banks.  The 16-byte chunks of a tile row are XOR-swizzled by the
+// row index so that each pass of an operand read touches every bank once:
+//  - a K fragment read (ds_read_b128) serves 16 lanes = 16 consecutive rows, same chunk;
+//  - a V fragment read (ds_read_b64_tr_b16) serves 32 lanes = 4 consecutive rows x 4
+//    adjacent chunks x both halves of a chunk.
+// Rows are 256 bytes (D = 128, all banks) or 128 bytes (D = 64, half of the banks, so
+// the row's parity already separates two rows).
+template <int D> __device__ inline int swizzle_k(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+template <int D> __device__ inline int swizzle_v(int row) {
+    // only bits 0..2 of the row: fragment reads step through the tile in multiples of 8 rows
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 1)) : (((row >> 1) & 1) << 2);
+}
 
-// Registers a thread holds for the tile that is in flight from HBM.
-template <int D>
-struct Staged {
-    u32x4 k[Geometry<D>::kLoads];
-    u32x4 v[Geometry<D>::kLoads];
-    unsigned real;   // bit i: load i fetched an existing row (others are written to LDS as zeros)
+// Page ids of one 64-key prefix tile (-1: not needed or not valid).
+struct TilePages {
+    int pg[4];
 };
 
-// Issue the global loads of one unit: a wave-uniform base address per load instruction
-// plus one 32-bit lane offset.  Rows that do not exist (past the sequence end, past the
-// last tree node, behind an invalid page id) read a harmless valid address and are
-// replaced by zeros when they are written to LDS: a zero K row is masked later, a zero V
-// row contributes nothing.
-template <int D>
-__device__ inline void issue_loads(const AttnParams &p, const Cursor &c, Staged<D> &st, int &bad) {
-    using G = Geometry<D>;
-    const int tid = threadIdx.x;
-    const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int key0 = tid / G::kChunks, chunk = tid % G::kChunks;   // this thread's key in pass 0
-    st.real = 0u;
-    if (c.idx < c.n_pre) {
-        const int base = c.idx * kTile;
-        const int n_valid = min(kTile, c.L - base);
-        const int32_t *pt = p.page_table + (size_t)c.b * p.max_pages + (base >> 4);
-        int pg[4];
+// Scalar loads of the page ids of the tile the cursor points at.
+__device__ inline TilePages load_pages(const AttnParams &p, const int32_t *__restrict__ page_table, const Cursor &c,
+                                       int &bad) {
+    TilePages t;
+    if (c.b < p.B && c.idx < c.n_pre) {
+        const int n_valid = c.L - c.idx * kTile;   // may exceed 64
+        const int32_t *row = page_table + (size_t)c.b * p.max_pages;
+        const int last = p.max_pages - 1;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            pg[j] = -1;
-            if (16 * j < n_valid) {
-                const int v = pt[j];
-                if (v >= 0 && v < p.num_pages) pg[j] = v; else bad |= READER_STATUS_BAD_PAGE;
-            }
+            const int v = row[min(c.idx * 4 + j, last)];
+            const bool needed = 16 * j < n_valid;
+            const bool valid = v >= 0 && v < p.num_pages;
+            t.pg[j] = (needed && valid) ? v : -1;
+            bad |= (needed && !valid) ? READER_STATUS_BAD_PAGE : 0;
         }
-        const size_t page_stride = (size_t)p.Hkv * 16 * D;           // elements
-        const size_t head_off = (size_t)c.hkv * 16 * D;
-        const unsigned voff = ((key0 & 15) * D + chunk * 8) * 2;      // bytes inside the (page, head) block
+    } else {
+        t.pg[0] = t.pg[1] = t.pg[2] = t.pg[3] = -1;
+    }
+    return t;
+}
+
+// Asynchronous copy HBM -> LDS: lane l moves 16 bytes from its global address to LDS byte
+// lds_base + 16 * l.  The compiler does not track these copies; the caller counts them
+// (every wavefront issues the same number per tile) and waits with s_waitcnt vmcnt.
+__device__ inline void copy16_uniform(const void *sbase, unsigned lane_off, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(lane_off), "s"(sbase), "s"(lds_base) : "memory", "m0");
+}
+__device__ inline void copy16_lane(const void *addr, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                 :: "v"(addr), "s"(lds_base) : "memory", "m0");
+}
+
+// Per-lane constants of the tile copy: byte offsets of this lane's 16 bytes inside a
+// (page, head) block of the cache / inside a 64-row slab of the tree tensors, for each copy
+// instruction, with the LDS swizzle already applied to the chunk index.
+template <int D>
+struct CopyLane {
+    unsigned k_cache_off[Geometry<D>::kCopies], v_cache_off[Geometry<D>::kCopies];
+    unsigned k_tree_off[Geometry<D>::kCopies], v_tree_off[Geometry<D>::kCopies];
+    int row[Geometry<D>::kCopies];   // tile row this lane copies
+};
+
+template <int D>
+__device__ inline CopyLane<D> make_copy_lane(const AttnParams &p, int wave, int lane) {
+    using G = Geometry<D>;
+    CopyLane<D> cl;
+    const int rin = lane / G::kChunks, pchunk = lane % G::kChunks;   // row inside the copy, physical chunk
+    const unsigned tree_row_bytes = (unsigned)p.Hkv * D * 2;
 #pragma unroll
-        for (int i = 0; i < G::kLoads; ++i) {
-            const int pj = i * (G::kKeysPerPass / 16) + (wave_s * 64 / G::kChunks) / 16;   // wave-uniform
-            const int page = pj == 0 ? pg[0] : pj == 1 ? pg[1] : pj == 2 ? pg[2] : pg[3];
-            const bool ok = page >= 0 && key0 + i * G::kKeysPerPass < n_valid;
-            const size_t eoff = (size_t)(page >= 0 ? page : 0) * page_stride + head_off;
-            const unsigned vo = ok ? voff : 0u;
-            st.k[i] = ld16(reinterpret_cast<const char *>(p.k_cache + eoff) + vo);
-            st.v[i] = ld16(reinterpret_cast<const char *>(p.v_cache + eoff) + vo);
-            st.real |= ok ? (1u << i) : 0u;
+    for (int i = 0; i < G::kCopies; ++i) {
+        const int r = wave * G::kRowsPerWave + i * G::kRowsPerCopy + rin;
+        const unsigned kc = (unsigned)(pchunk ^ swizzle_k<D>(r)) << 4;
+        const unsigned vc = (unsigned)(pchunk ^ swizzle_v<D>(r)) << 4;
+        cl.row[i] = r;
+        cl.k_cache_off[i] = (r & 15) * G::kRowBytes + kc;
+        cl.v_cache_off[i] = (r & 15) * G::kRowBytes + vc;
+        cl.k_tree_off[i] = r * tree_row_bytes + kc;
+        cl.v_tree_off[i] = r * tree_row_bytes + vc;
+    }
+    return cl;
+}
+
+// Start the copy of one unit into the LDS stage at byte address `stage`.  Every wavefront
+// issues exactly 2 * kCopies copy instructions, whatever the tile looks like: rows that do
+// not exist (past the sequence end, past the last tree node, behind an invalid page id)
+// are copied from a block of zeros, so a missing K row scores 0 (and is masked later) and
+// a missing V row contributes nothing.
+template <int D>
+__device__ inline void issue_copy(const AttnParams &p, const Cursor &c, const TilePages &tp, const CopyLane<D> &cl,
+                                  unsigned stage, int wave_s) {
+    using G = Geometry<D>;
+    const unsigned k_dst = stage + wave_s * G::kRowsPerWave * G::kRowBytes;
+    const unsigned v_dst = k_dst + G::kTileBytes;
+    const char *zeros = reinterpret_cast<const char *>(kZeroRow) + (threadIdx.x & 15) * 16;
+    if (c.idx < c.n_pre) {
+        const int n_valid = min(kTile, c.L - c.idx * kTile);
+        const size_t page_bytes = (size_t)p.Hkv * 16 * D * 2;
+        const size_t head_bytes = (size_t)c.hkv * 16 * D * 2;
+        const int page = (wave_s >> 1) == 0 ? tp.pg[0] : (wave_s >> 1) == 1 ? tp.pg[1] : (wave_s >> 1) == 2 ? tp.pg[2] : tp.pg[3];
+        const size_t boff = (size_t)(page >= 0 ? page : 0) * page_bytes + head_bytes;
+        const char *kb = reinterpret_cast<const char *>(p.k_cache) + boff;
+        const char *vb = reinterpret_cast<const char *>(p.v_cache) + boff;
+        const bool whole = page >= 0 && (wave_s + 1) * G::kRowsPerWave <= n_valid;   // wave-uniform
+        if (whole) {
+#pragma unroll
+            for (int i = 0; i < G::kCopies; ++i) {
+                copy16_uniform(kb, cl.k_cache_off[i], k_dst + i * 1024);
+                copy16_uniform(vb, cl.v_cache_off[i], v_dst + i * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < G::kCopies; ++i) {
+                const bool ok = page >= 0 && cl.row[i] < n_valid;
+                copy16_lane(ok ? kb + cl.k_cache_off[i] : zeros, k_dst + i * 1024);
+                copy16_lane(ok ? vb + cl.v_cache_off[i] : zeros, v_dst + i * 1024);
+            }
         }
     } else {
         const int base = (c.idx - c.n_pre) * kTile;
         const int n_valid = min(kTile, p.T - base);
-        const unsigned row_bytes = (unsigned)p.Hkv * D * 2;
-        const size_t origin = (((size_t)c.b * p.T + base) * p.Hkv + c.hkv) * D;
+        const size_t origin = (((size_t)c.b * p.T + base) * p.Hkv + c.hkv) * D * 2;
+        const char *kb = reinterpret_cast<const char *>(p.k_tree) + origin;
+        const char *vb = reinterpret_cast<const char *>(p.v_tree) + origin;
 #pragma unroll
-        for (int i = 0; i < G::kLoads; ++i) {
-            const int key = key0 + i * G::kKeysPerPass;
-            const bool ok = key < n_valid;
-            const unsigned vo = ok ? (unsigned)key * row_bytes + chunk * 16 : 0u;
-            st.k[i] = ld16(reinterpret_cast<const char *>(p.k_tree + origin) + vo);
-            st.v[i] = ld16(reinterpret_cast<const char *>(p.v_tree + origin) + vo);
-            st.real |= ok ? (1u << i) : 0u;
+        for (int i = 0; i < G::kCopies; ++i) {
+            const bool ok = cl.row[i] < n_valid;
+            copy16_lane(ok ? kb + cl.k_tree_off[i] : zeros, k_dst + i * 1024);
+            copy16_lane(ok ? vb + cl.v_tree_off[i] : zeros, v_dst + i * 1024);
         }
     }
 }
 
-// Staged registers -> LDS, both tiles row-major with swizzled 16-byte chunks.
-template <int D>
-__device__ inline void write_stage(const Staged<D> &st, char *k_lds, char *v_lds) {
-    using G = Geometry<D>;
-    const int tid = threadIdx.x;
-    const int key0 = tid / G::kChunks, chunk = tid % G::kChunks;
-    // kKeysPerPass is a multiple of 8, so the swizzle of a thread's row is the same in every pass
-    const int koff = key0 * G::kRowBytes + ((chunk ^ swizzle_k(key0)) << 4);
-    const int voff = key0 * G::kRowBytes + ((chunk ^ swizzle_v(key0)) << 4);
-#pragma unroll
-    for (int i = 0; i < G::kLoads; ++i) {
-        const bool real = (st.real >> i) & 1u;
-        *reinterpret_cast<u32x4 *>(k_lds + koff + i * G::kKeysPerPass * G::kRowBytes) = keep_if(real, st.k[i]);
-        *reinterpret_cast<u32x4 *>(v_lds + voff + i * G::kKeysPerPass * G::kRowBytes) = keep_if(real, st.v[i]);
-    }
+// s_waitcnt vmcnt(n) only (expcnt and lgkmcnt left alone), n < 64
+template <int N>
+__device__ inline void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
@@ -230,9 +304,6 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
 // Transposing LDS load of gfx950: within each group of 16 lanes the 16 x 4 block of
 // 16-bit elements the lanes point at (lane k supplies 4 consecutive elements) is read
 // as 4 rows of 16, and lane i receives element i of each row.
@@ -242,64 +313,85 @@ __device__ inline s16x4 lds_read_tr16(const char *ptr) {
 
 }  // namespace
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams p) {
+// NKB: 32-key blocks of a tile one wavefront works on (1: keys are split between two wave
+// groups; 2: every wavefront takes the whole tile).
+template <int D, int NKB>
+__global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams p,
+                                                                       const int32_t *__restrict__ page_table,
+                                                                       const int32_t *__restrict__ seq_lens) {
     using G = Geometry<D>;
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    char *buf0 = smem;
-    char *buf1 = smem + G::kBufBytes;
-    uint32_t *s_anc = reinterpret_cast<uint32_t *>(smem + 2 * G::kBufBytes);   // [READER_MAX_T][4]
-    int *s_par = reinterpret_cast<int *>(s_anc + READER_MAX_T * 4);            // [READER_MAX_T]
-    int *s_wsum = s_par + READER_MAX_T;                                        // [4]
-    int *s_pref = s_wsum + 4;                                                  // [B + 1]
+    constexpr int kRowBlocks = NKB == 2 ? 8 : 4;
+    constexpr int kRowsPerWG = 32 * kRowBlocks;
+    constexpr int kCopiesPerTile = 2 * G::kCopies;   // per wavefront
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    char *ring = smem;                                                               // [kStages][kStageBytes]
+    uint32_t *s_anc = reinterpret_cast<uint32_t *>(smem + kStages * G::kStageBytes); // [READER_MAX_T][4]
+    int *s_par = reinterpret_cast<int *>(s_anc + READER_MAX_T * 4);                  // [READER_MAX_T]
+    float *s_ml = reinterpret_cast<float *>(s_par + READER_MAX_T);                   // key group 1's sums [128][2] then maxima [128]
+    int *s_wsum = reinterpret_cast<int *>(s_ml + 384);                               // [8]
+    int *s_pref = s_wsum + 8;                                                        // [B + 1]
+    const unsigned ring_lds = (unsigned)(size_t)(lds_char *)ring;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rb = NKB == 2 ? wave_s : (wave_s & 3);     // row block of this wavefront
+    const int kg = NKB == 2 ? 0 : (wave_s >> 2);         // key group of this wavefront
     const int n = lane & 31, h = lane >> 5;
     const int chunk_base = blockIdx.y * kRowsPerWG;
-    const int row_local = wave * 32 + n;           // row inside this workgroup's chunk
+    const int row_local = rb * 32 + n;             // row inside this workgroup's chunk
     const int m_row = chunk_base + row_local;      // query row inside the pair
     const bool row_real = m_row < p.M;
     const int node = row_real ? m_row / p.G : 0;   // tree node of this lane's query row
     const int group = row_real ? m_row - node * p.G : 0;
-    const bool wave_active = chunk_base + wave * 32 < p.M;
+    const bool wave_active = chunk_base + rb * 32 < p.M;
 
-    scan_units(p, s_pref, s_wsum);
+    scan_units(p, seq_lens, s_pref, s_wsum);
     const long long U = (long long)p.Hkv * s_pref[p.B];
     const long long lo = range_begin(blockIdx.x, U, p.n_ranges);
     const long long hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
     if (lo >= hi) return;
     const int n_iter = (int)(hi - lo);
 
-    Cursor cc;   // unit being computed; every field is wave-uniform and kept in scalar registers
+    int bad = 0;
+    Cursor cc;   // unit being computed
     cc.b = __builtin_amdgcn_readfirstlane(find_seq(s_pref, p.B, p.Hkv, lo));
-    cursor_enter_seq(cc, p);
+    cursor_enter_seq(cc, p, seq_lens);
     {
         const long long rel = lo - (long long)p.Hkv * s_pref[cc.b];
         const int hkv = (int)(rel / cc.n_units);
         cc.hkv = __builtin_amdgcn_readfirstlane(hkv);
         cc.idx = __builtin_amdgcn_readfirstlane((int)(rel - (long long)hkv * cc.n_units));
     }
-    Cursor lc = cc;   // unit being loaded (one ahead)
+    Cursor dc = cc;   // unit whose copy is issued next (two ahead of cc in steady state)
 
-    int bad = 0;
-    Staged<D> st;
-    issue_loads<D>(p, lc, st, bad);
-    write_stage<D>(st, buf0, buf0 + G::kTileBytes);
-    cursor_advance(lc, p);
-    __syncthreads();
+    const CopyLane<D> cl = make_copy_lane<D>(p, wave_s, lane);
 
-    // per-lane LDS offsets of the matrix-core operand reads
-    int k_rd[4];   // K fragment of k-step kk: k_rd[kk & 3] + (kk >> 2) * 128 (+ 32 rows for the second key block)
+    // prologue: tiles 0 and 1 in flight, page ids of tile 2 on their way
+    TilePages tp = load_pages(p, page_table, dc, bad);
+    issue_copy<D>(p, dc, tp, cl, ring_lds, wave_s);
+    cursor_advance(dc, p, seq_lens);
+    tp = load_pages(p, page_table, dc, bad);
+    if (n_iter > 1) {
+        issue_copy<D>(p, dc, tp, cl, ring_lds + G::kStageBytes, wave_s);
+        cursor_advance(dc, p, seq_lens);
+        tp = load_pages(p, page_table, dc, bad);
+    }
+
+    // per-lane LDS offsets of the matrix-core operand reads (relative to the stage)
+    int k_rd[G::kKSteps];   // K fragment of k-step kk, first key block of this wavefront
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) k_rd[kk] = n * G::kRowBytes + (((2 * kk + h) ^ swizzle_k(n)) << 4);
-    int v_rd[2];   // V fragment of output block db: v_rd[db & 1] + (db >> 1) * 128 (+ key rows)
+    for (int kk = 0; kk < G::kKSteps; ++kk)
+        k_rd[kk] = (kg * 32 + n) * G::kRowBytes + (((2 * kk + h) ^ swizzle_k<D>(n)) << 4);
+    int v_rd[G::kOBlocks];  // V fragment of output block db, keys 0..3 (+4h) of this wavefront's first 16-key group
     {
         const int i16 = lane & 15, g16 = (lane >> 4) & 1;
         const int key_lo = 4 * h + (i16 >> 2);                       // key row inside an 8-key group
         const int c_lo = 2 * g16 + ((i16 & 3) >> 1);                 // 16-byte chunk inside the 32-wide d block
 #pragma unroll
-        for (int db = 0; db < 2; ++db)
-            v_rd[db] = key_lo * G::kRowBytes + ((((db * 4) | c_lo) ^ swizzle_v(key_lo)) << 4) + (i16 & 1) * 8;
+        for (int db = 0; db < G::kOBlocks; ++db)
+            v_rd[db] = G::kTileBytes + (kg * 32 + key_lo) * G::kRowBytes +
+                       ((((db * 4) | c_lo) ^ swizzle_v<D>(key_lo)) << 4) + (i16 & 1) * 8;
     }
 
     bf16x8 qf[G::kKSteps];
@@ -310,9 +402,13 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     const float c2 = p.scale_log2;
 
     for (int it = 0; it < n_iter; ++it) {
-        char *k_lds = (it & 1) ? buf1 : buf0;
-        char *v_lds = k_lds + G::kTileBytes;
-        const bool more = it + 1 < n_iter;
+        const int stage_idx = it % kStages;
+        const char *stage = ring + stage_idx * G::kStageBytes;
+
+        // This wavefront's part of tile `it` has landed once at most the copies of tile
+        // it + 1 are outstanding (copies complete in the order they were issued).
+        if (it + 1 < n_iter) wait_vmcnt<kCopiesPerTile>(); else wait_vmcnt<0>();
+        __syncthreads();   // tile `it` is complete in LDS; every wavefront is done with tile it - 1
 
         if (fresh) {
             fresh = false;
@@ -326,12 +422,10 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             // this lane's query row as the B operand of the QK product
             const uint16_t *qrow = p.q + (((size_t)cc.b * p.T + node) * p.Hq + cc.hkv * p.G + group) * D;
 #pragma unroll
-            for (int kk = 0; kk < G::kKSteps; ++kk) {
+            for (int kk = 0; kk < G::kKSteps; ++kk)
                 qf[kk] = __builtin_bit_cast(bf16x8, keep_if(row_real, ld16(qrow + kk * 16 + h * 8)));
-            }
             // ancestor-or-self masks of this sequence's tree, if this segment reaches its tree tiles
             if (cc.idx + (n_iter - it) > cc.n_pre) {
-                __syncthreads();   // previous users of s_anc / s_par are done
                 if (tid < p.T) {
                     int pi = p.parents[(size_t)cc.b * p.T + tid];
                     const bool valid = tid == 0 ? pi == -1 : (pi >= 0 && pi < tid);
@@ -340,55 +434,65 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
                 }
                 __syncthreads();
                 if (tid < p.T) {
-                    uint32_t a[4] = {0u, 0u, 0u, 0u};
+                    uint32_t a0 = 0u, a1 = 0u, a2 = 0u, a3 = 0u;
                     int t = tid;
                     for (int step = 0; step < p.T && t >= 0; ++step) {
-                        a[t >> 5] |= 1u << (t & 31);
+                        const uint32_t bit = 1u << (t & 31);
+                        const int w = t >> 5;
+                        a0 |= w == 0 ? bit : 0u; a1 |= w == 1 ? bit : 0u;
+                        a2 |= w == 2 ? bit : 0u; a3 |= w == 3 ? bit : 0u;
                         t = s_par[t];
                     }
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) s_anc[tid * 4 + w] = a[w];
+                    s_anc[tid * 4 + 0] = a0; s_anc[tid * 4 + 1] = a1;
+                    s_anc[tid * 4 + 2] = a2; s_anc[tid * 4 + 3] = a3;
                 }
                 __syncthreads();
             }
         }
 
-        if (more) issue_loads<D>(p, lc, st, bad);
+        // start the copy of tile it + 2 into the stage tile it - 1 has just left
+        if (it + 2 < n_iter) {
+            issue_copy<D>(p, dc, tp, cl, ring_lds + ((it + 2) % kStages) * G::kStageBytes, wave_s);
+            cursor_advance(dc, p, seq_lens);
+            tp = load_pages(p, page_table, dc, bad);     // page ids of tile it + 3
+        }
 
         if (wave_active) {
-            // ---- S^T = K . Q^T : two 32-key blocks ----
+            // ---- S^T = K . Q^T for this wavefront's key block(s) ----
             // All fragment reads of a block are issued before its first matrix instruction,
-            // and the second block's reads are interleaved with the first block's products.
-            f32x16 s[2];
-            bf16x8 ka[2][G::kKSteps];
+            // and a second block's reads are interleaved with the first block's products.
+            f32x16 s[NKB];
+            bf16x8 ka[NKB][G::kKSteps];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
                 for (int kk = 0; kk < G::kKSteps; ++kk)
-                    ka[kb][kk] = *reinterpret_cast<const bf16x8 *>(
-                        k_lds + k_rd[kk & 3] + (kk >> 2) * 128 + kb * 32 * G::kRowBytes);
+                    ka[kb][kk] = *reinterpret_cast<const bf16x8 *>(stage + k_rd[kk] + kb * 32 * G::kRowBytes);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int kb = 0; kb < NKB; ++kb) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
 #pragma unroll
                 for (int kk = 0; kk < G::kKSteps; ++kk)
                     s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kb][kk], qf[kk], s[kb], 0, 0, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x100, G::kKSteps, 0);          // LDS reads of block 0
+            if (NKB == 2) {
+                __builtin_amdgcn_sched_group_barrier(0x100, G::kKSteps, 0);      // LDS reads of block 0
 #pragma unroll
-            for (int kk = 0; kk < G::kKSteps; ++kk) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one product of block 0
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one read of block 1
+                for (int kk = 0; kk < G::kKSteps; ++kk) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           // one product of block 0
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // one read of block 1
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);      // products of block 1
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);          // products of block 1
+
             // ---- masks: ragged last prefix tile, tree tiles ----
             const bool is_tree = cc.idx >= cc.n_pre;
             if (is_tree) {
                 const int tt = cc.idx - cc.n_pre;
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    uint32_t bits = row_real ? s_anc[node * 4 + tt * 2 + kb] : 0u;
+                for (int kb = 0; kb < NKB; ++kb) {
+                    uint32_t bits = row_real ? s_anc[node * 4 + tt * 2 + kg + kb] : 0u;
                     bits >>= 4 * h;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
@@ -399,17 +503,17 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             } else if ((cc.idx + 1) * kTile > cc.L) {
                 const int n_valid = cc.L - cc.idx * kTile;
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const int key = kb * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
+                        const int key = (kg + kb) * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
                         if (key >= n_valid) s[kb][i] = -INFINITY;
                     }
             }
-            // ---- online softmax along the keys (all 32 values of a lane share one query row) ----
+            // ---- online softmax along the keys (all values of a lane share one query row) ----
             float mx = s[0][0];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -419,9 +523,9 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             m_run = m_new;
             const float mc = m_eff * c2;
             float lsum = 0.f;
-            uint32_t pk[2][8];
+            uint32_t pk[NKB][8];
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
                 for (int i = 0; i < 16; i += 2) {
                     const float p0 = __builtin_amdgcn_exp2f(s[kb][i] * c2 - mc);
@@ -438,7 +542,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             }
             // ---- O^T += V^T . P^T : the S^T registers of a lane are, 8 at a time, the B operand ----
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
+            for (int ks = 0; ks < 2 * NKB; ++ks) {
                 const int kb = ks >> 1, m2 = ks & 1;
                 u32x4 pv;
                 pv.x = pk[kb][4 * m2]; pv.y = pk[kb][4 * m2 + 1]; pv.z = pk[kb][4 * m2 + 2]; pv.w = pk[kb][4 * m2 + 3];
@@ -446,10 +550,9 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
                 const int key_base = (kb * 32 + m2 * 16) * G::kRowBytes;
 #pragma unroll
                 for (int db = 0; db < G::kOBlocks; ++db) {
-                    const char *src = v_lds + v_rd[db & 1] + (db >> 1) * 128 + key_base;
+                    const char *src = stage + v_rd[db] + key_base;
                     const s16x4 lo4 = lds_read_tr16(src);                         // keys +0..3 (+4h)
                     const s16x4 hi4 = lds_read_tr16(src + 8 * G::kRowBytes);      // keys +8..11 (+4h)
-                    typedef short s16x8 __attribute__((ext_vector_type(8)));
                     const s16x8 a8 = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
                     o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
                 }
@@ -458,8 +561,50 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
 
         // ---- end of a segment: this pair ends here, or the range does ----
         const bool pair_ends = cc.idx + 1 == cc.n_units;
-        if (pair_ends || !more) {
-            if (wave_active) {
+        const bool last_iter = it + 1 == n_iter;
+        if (pair_ends || last_iter) {
+            if (NKB == 1) {
+                // Key group 1 hands its state to key group 0 of the same row block through the
+                // stage that has just been consumed, half of the output blocks at a time.
+                float *xbuf = reinterpret_cast<float *>(const_cast<char *>(stage)) + (size_t)rb * (G::kOBlocks / 2) * 16 * 64;
+                float m1 = 0.f, a0 = 1.f, a1 = 0.f;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    __syncthreads();   // stage free (first pass) / previous half consumed
+                    if (kg == 1 && wave_active) {
+#pragma unroll
+                        for (int d2 = 0; d2 < G::kOBlocks / 2; ++d2)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i)
+                                xbuf[(d2 * 16 + i) * 64 + lane] = o[half * (G::kOBlocks / 2) + d2][i];
+                        if (half == 0) {
+                            s_ml[row_local * 2 + h] = l_run;          // each lane half holds a partial sum
+                            if (h == 0) s_ml[256 + row_local] = m_run;
+                        }
+                    }
+                    __syncthreads();
+                    if (kg == 0 && wave_active) {
+                        if (half == 0) {
+                            m1 = s_ml[256 + row_local];
+                            const float l1 = s_ml[row_local * 2 + h];
+                            const float m_new = fmaxf(m_run, m1);
+                            const float m_eff = (m_new == -INFINITY) ? 0.f : m_new;
+                            a0 = __builtin_amdgcn_exp2f((m_run - m_eff) * c2);
+                            a1 = __builtin_amdgcn_exp2f((m1 - m_eff) * c2);
+                            l_run = l_run * a0 + l1 * a1;
+                            m_run = m_new;
+                        }
+#pragma unroll
+                        for (int d2 = 0; d2 < G::kOBlocks / 2; ++d2)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) {
+                                const int db = half * (G::kOBlocks / 2) + d2;
+                                o[db][i] = o[db][i] * a0 + xbuf[(d2 * 16 + i) * 64 + lane] * a1;
+                            }
+                    }
+                }
+            }
+            if (wave_active && kg == 0) {
                 const float l_tot = l_run + __shfl_xor(l_run, 32);
                 if (seg_from_pair_start && pair_ends) {
                     if (row_real) {
@@ -480,7 +625,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
                     }
                 } else {
                     const size_t slot = ((size_t)(2 * blockIdx.x + (seg_from_pair_start ? 1 : 0)) * p.n_row_chunks + blockIdx.y);
-                    float *rec = p.workspace + slot * attn_slot_floats(D);
+                    float *rec = p.workspace + slot * attn_slot_floats(D, kRowsPerWG);
                     float *orow = rec + (size_t)row_local * D;
 #pragma unroll
                     for (int db = 0; db < G::kOBlocks; ++db)
@@ -496,27 +641,21 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             }
             fresh = true;
         }
-
-        if (more) {
-            char *nk = (it & 1) ? buf0 : buf1;
-            write_stage<D>(st, nk, nk + G::kTileBytes);
-            cursor_advance(lc, p);
-        }
-        cursor_advance(cc, p);
-        __syncthreads();
+        cursor_advance(cc, p, seq_lens);
     }
 
     if (p.status && bad) atomicOr(p.status, bad);
 }
 
 // Merge the partial records of every pair that was cut between workgroups.
-// grid = (B * Hkv, row chunks); 2 threads per query row, each half of D.
+// grid = (B * Hkv, row chunks * rows_per_wg / 32): one workgroup per 32 query rows of a
+// pair, 8 threads per row, each 1/8 of D.
 template <int D>
-__global__ __launch_bounds__(kThreads) void tree_attn_merge_kernel(AttnParams p) {
+__global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnParams p, const int32_t *__restrict__ seq_lens) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     int *s_pref = reinterpret_cast<int *>(smem);
-    __shared__ int s_wsum[4];
-    scan_units(p, s_pref, s_wsum);
+    __shared__ int s_wsum[8];
+    scan_units(p, seq_lens, s_pref, s_wsum);
 
     const int pair = blockIdx.x, b = pair / p.Hkv, hkv = pair - b * p.Hkv;
     const int n_units = s_pref[b + 1] - s_pref[b];
@@ -527,48 +666,51 @@ __global__ __launch_bounds__(kThreads) void tree_attn_merge_kernel(AttnParams p)
     if (w_first == w_last) return;   // finished in place by one workgroup
 
     const int tid = threadIdx.x;
-    const int row_local = tid >> 1, half = tid & 1;
-    const int m_row = blockIdx.y * kRowsPerWG + row_local;
+    const int blocks_per_chunk = p.rows_per_wg / 32;
+    const int row_chunk = blockIdx.y / blocks_per_chunk;
+    const int row_local = (blockIdx.y - row_chunk * blocks_per_chunk) * 32 + (tid >> 3), part = tid & 7;
+    const int m_row = row_chunk * p.rows_per_wg + row_local;
     if (m_row >= p.M) return;
     const int node = m_row / p.G, group = m_row - node * p.G;
-    const size_t rec_floats = attn_slot_floats(D);
+    const size_t rows = p.rows_per_wg;
+    const size_t rec_floats = attn_slot_floats(D, p.rows_per_wg);
 
     // Ranges that hold no unit (more workgroups than units) wrote no record.
     auto empty = [&](int w) { return range_begin(w, U, p.n_ranges) >= range_begin(w + 1, U, p.n_ranges); };
     auto record = [&](int w) -> const float * {
-        const size_t slot = ((size_t)(2 * w + (w == w_first ? 1 : 0)) * p.n_row_chunks + blockIdx.y);
+        const size_t slot = ((size_t)(2 * w + (w == w_first ? 1 : 0)) * p.n_row_chunks + row_chunk);
         return p.workspace + slot * rec_floats;
     };
 
     float m_all = -INFINITY;
     for (int w = w_first; w <= w_last; ++w)
-        if (!empty(w)) m_all = fmaxf(m_all, record(w)[(size_t)kRowsPerWG * D + row_local]);
+        if (!empty(w)) m_all = fmaxf(m_all, record(w)[rows * D + row_local]);
     // m_all is finite: every query row sees at least its own tree node
 
-    constexpr int kHalf = D / 2;
-    float acc[kHalf];
+    constexpr int kPart = D / 8;
+    float acc[kPart];
 #pragma unroll
-    for (int d = 0; d < kHalf; ++d) acc[d] = 0.f;
+    for (int d = 0; d < kPart; ++d) acc[d] = 0.f;
     float l_all = 0.f;
     for (int w = w_first; w <= w_last; ++w) {
         if (empty(w)) continue;
         const float *rec = record(w);
-        const float mw = rec[(size_t)kRowsPerWG * D + row_local];
+        const float mw = rec[rows * D + row_local];
         if (mw == -INFINITY) continue;
         const float f = __builtin_amdgcn_exp2f(mw - m_all);
-        l_all += f * rec[(size_t)kRowsPerWG * (D + 1) + row_local];
-        const float4 *src = reinterpret_cast<const float4 *>(rec + (size_t)row_local * D + half * kHalf);
+        l_all += f * rec[rows * (D + 1) + row_local];
+        const float4 *src = reinterpret_cast<const float4 *>(rec + (size_t)row_local * D + part * kPart);
 #pragma unroll
-        for (int d4 = 0; d4 < kHalf / 4; ++d4) {
+        for (int d4 = 0; d4 < kPart / 4; ++d4) {
             const float4 v = src[d4];
             acc[4 * d4] += f * v.x; acc[4 * d4 + 1] += f * v.y;
             acc[4 * d4 + 2] += f * v.z; acc[4 * d4 + 3] += f * v.w;
         }
     }
     const float inv = 1.f / l_all;
-    uint16_t *orow = p.out + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D + half * kHalf;
+    uint16_t *orow = p.out + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D + part * kPart;
 #pragma unroll
-    for (int d8 = 0; d8 < kHalf / 8; ++d8) {
+    for (int d8 = 0; d8 < kPart / 8; ++d8) {
         uint4 w;
         w.x = pack_bf16x2(acc[8 * d8] * inv, acc[8 * d8 + 1] * inv);
         w.y = pack_bf16x2(acc[8 * d8 + 2] * inv, acc[8 * d8 + 3] * inv);
@@ -576,38 +718,40 @@ __global__ __launch_bounds__(kThreads) void tree_attn_merge_kernel(AttnParams p)
         w.w = pack_bf16x2(acc[8 * d8 + 6] * inv, acc[8 * d8 + 7] * inv);
         *reinterpret_cast<uint4 *>(orow + 8 * d8) = w;
     }
-    if (p.lse && half == 0)
+    if (p.lse && part == 0)
         p.lse[((size_t)b * p.Hq + hkv * p.G + group) * p.T + node] = (m_all + __builtin_amdgcn_logf(l_all)) * kLn2;
 }
 
-template <int D>
+template <int D, int NKB>
 static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
     using G = Geometry<D>;
     const size_t pref_bytes = ((size_t)(p.B + 1) * sizeof(int) + 15) & ~(size_t)15;
-    const size_t main_lds = 2 * (size_t)G::kBufBytes + READER_MAX_T * 4 * sizeof(uint32_t) +
-                            READER_MAX_T * sizeof(int) + 4 * sizeof(int) + pref_bytes;
+    const size_t main_lds = (size_t)kStages * G::kStageBytes + READER_MAX_T * 4 * sizeof(uint32_t) +
+                            READER_MAX_T * sizeof(int) + 384 * sizeof(float) + 8 * sizeof(int) + pref_bytes;
     // More than 64 KB of LDS per workgroup has to be asked for; the limit counts the
     // kernel's static LDS too, so ask for exactly what this launch needs.
     static size_t lds_allowed = 0;
     if (main_lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_mfma_kernel<D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_mfma_kernel<D, NKB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)main_lds);
         if (e != hipSuccess) { (void)hipGetLastError(); return note_hip_error("hipFuncSetAttribute(attention LDS size)", e); }
         lds_allowed = main_lds;
     }
     if (ev_start) (void)hipEventRecord(ev_start, stream);
-    hipLaunchKernelGGL(tree_attn_mfma_kernel<D>, dim3(p.n_ranges, p.n_row_chunks), dim3(kThreads),
-                       main_lds, stream, p);
+    hipLaunchKernelGGL((tree_attn_mfma_kernel<D, NKB>), dim3(p.n_ranges, p.n_row_chunks), dim3(kThreads),
+                       main_lds, stream, p, p.page_table, p.seq_lens);
     hipError_t e = hipGetLastError();
     if (ev_stop) (void)hipEventRecord(ev_stop, stream);
     if (e != hipSuccess) return note_hip_error("launch tree_attn_mfma_kernel", e);
-    hipLaunchKernelGGL(tree_attn_merge_kernel<D>, dim3(p.B * p.Hkv, p.n_row_chunks), dim3(kThreads),
-                       pref_bytes, stream, p);
+    hipLaunchKernelGGL(tree_attn_merge_kernel<D>, dim3(p.B * p.Hkv, p.n_row_chunks * (p.rows_per_wg / 32)), dim3(256),
+                       pref_bytes, stream, p, p.seq_lens);
     return note_hip_error("launch tree_attn_merge_kernel", hipGetLastError());
 }
 
 hipError_t launch_tree_attn_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    return p.D == 64 ? launch_mfma<64>(p, stream, ev_start, ev_stop) : launch_mfma<128>(p, stream, ev_start, ev_stop);
+    if (p.rows_per_wg == 128)
+        return p.D == 64 ? launch_mfma<64, 1>(p, stream, ev_start, ev_stop) : launch_mfma<128, 1>(p, stream, ev_start, ev_stop);
+    return p.D == 64 ? launch_mfma<64, 2>(p, stream, ev_start, ev_stop) : launch_mfma<128, 2>(p, stream, ev_start, ev_stop);
 }
 
 }  // namespace reader
