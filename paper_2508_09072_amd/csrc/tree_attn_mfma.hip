@@ -55,7 +55,7 @@ namespace {
 
 constexpr float kLn2 = 0.69314718055994530942f;
 constexpr int kWaves = kThreads / 64;
-constexpr int kStages = 3;
+constexpr int kStages = 4;
 
 // Position along the flat unit axis: which pair, which tile of it.  Every field is
 // wave-uniform and lives in scalar registers.
@@ -171,27 +171,19 @@ template <int D> __device__ inline int swizzle_v(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 1)) : (((row >> 1) & 1) << 2);
 }
 
-// Page ids of one 64-key prefix tile (-1: not needed or not valid).
+// Page-table entries of one 64-key prefix tile, as loaded (validated where they are used, one
+// iteration later, so that the scalar loads have a whole tile of time to come back).
 struct TilePages {
     int pg[4];
 };
 
-// Scalar loads of the page ids of the tile the cursor points at.
-__device__ inline TilePages load_pages(const AttnParams &p, const int32_t *__restrict__ page_table, const Cursor &c,
-                                       int &bad) {
+__device__ inline TilePages load_pages(const AttnParams &p, const int32_t *__restrict__ page_table, const Cursor &c) {
     TilePages t;
     if (c.b < p.B && c.idx < c.n_pre) {
-        const int n_valid = c.L - c.idx * kTile;   // may exceed 64
         const int32_t *row = page_table + (size_t)c.b * p.max_pages;
         const int last = p.max_pages - 1;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int v = row[min(c.idx * 4 + j, last)];
-            const bool needed = 16 * j < n_valid;
-            const bool valid = v >= 0 && v < p.num_pages;
-            t.pg[j] = (needed && valid) ? v : -1;
-            bad |= (needed && !valid) ? READER_STATUS_BAD_PAGE : 0;
-        }
+        for (int j = 0; j < 4; ++j) t.pg[j] = row[min(c.idx * 4 + j, last)];
     } else {
         t.pg[0] = t.pg[1] = t.pg[2] = t.pg[3] = -1;
     }
@@ -247,7 +239,7 @@ __device__ inline CopyLane<D> make_copy_lane(const AttnParams &p, int wave, int 
 // a missing V row contributes nothing.
 template <int D>
 __device__ inline void issue_copy(const AttnParams &p, const Cursor &c, const TilePages &tp, const CopyLane<D> &cl,
-                                  unsigned stage, int wave_s) {
+                                  unsigned stage, int wave_s, int &bad) {
     using G = Geometry<D>;
     const unsigned k_dst = stage + wave_s * G::kRowsPerWave * G::kRowBytes;
     const unsigned v_dst = k_dst + G::kTileBytes;
@@ -256,7 +248,11 @@ __device__ inline void issue_copy(const AttnParams &p, const Cursor &c, const Ti
         const int n_valid = min(kTile, c.L - c.idx * kTile);
         const size_t page_bytes = (size_t)p.Hkv * 16 * D * 2;
         const size_t head_bytes = (size_t)c.hkv * 16 * D * 2;
-        const int page = (wave_s >> 1) == 0 ? tp.pg[0] : (wave_s >> 1) == 1 ? tp.pg[1] : (wave_s >> 1) == 2 ? tp.pg[2] : tp.pg[3];
+        int page = (wave_s >> 1) == 0 ? tp.pg[0] : (wave_s >> 1) == 1 ? tp.pg[1] : (wave_s >> 1) == 2 ? tp.pg[2] : tp.pg[3];
+        if (page < 0 || page >= p.num_pages) {
+            if (wave_s * G::kRowsPerWave < n_valid) bad |= READER_STATUS_BAD_PAGE;   // this wavefront needed it
+            page = -1;
+        }
         const size_t boff = (size_t)(page >= 0 ? page : 0) * page_bytes + head_bytes;
         const char *kb = reinterpret_cast<const char *>(p.k_cache) + boff;
         const char *vb = reinterpret_cast<const char *>(p.v_cache) + boff;
@@ -368,14 +364,14 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     const CopyLane<D> cl = make_copy_lane<D>(p, wave_s, lane);
 
     // prologue: tiles 0 and 1 in flight, page ids of tile 2 on their way
-    TilePages tp = load_pages(p, page_table, dc, bad);
-    issue_copy<D>(p, dc, tp, cl, ring_lds, wave_s);
+    TilePages tp = load_pages(p, page_table, dc);
+    issue_copy<D>(p, dc, tp, cl, ring_lds, wave_s, bad);
     cursor_advance(dc, p, seq_lens);
-    tp = load_pages(p, page_table, dc, bad);
+    tp = load_pages(p, page_table, dc);
     if (n_iter > 1) {
-        issue_copy<D>(p, dc, tp, cl, ring_lds + G::kStageBytes, wave_s);
+        issue_copy<D>(p, dc, tp, cl, ring_lds + G::kStageBytes, wave_s, bad);
         cursor_advance(dc, p, seq_lens);
-        tp = load_pages(p, page_table, dc, bad);
+        tp = load_pages(p, page_table, dc);
     }
 
     // per-lane LDS offsets of the matrix-core operand reads (relative to the stage)
@@ -400,6 +396,117 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     bool fresh = true;                 // the next unit starts a segment (new pair or range start)
     bool seg_from_pair_start = false;
     const float c2 = p.scale_log2;
+
+    const bool rotated = (wave_s & 4) != 0;
+    bool pv_pending = false;
+    uint32_t pk[NKB][8];   // softmax weights of the current tile, bf16 pairs, in B-operand order
+    // The running reference m_run is only raised when a row's maximum outgrows it by more
+    // than 2^8 (in the exp2 domain), so the accumulator rescale is rare; weights stay <= 256.
+    const float grow_margin = 8.f / c2;
+
+    // S^T = K . Q^T for this wavefront's key block(s), masks, online softmax -> pk
+    auto qk_softmax = [&](const char *stage) {
+        // All fragment reads of a block are issued before its first matrix instruction,
+        // and a second block's reads are interleaved with the first block's products.
+        f32x16 s[NKB];
+        bf16x8 ka[NKB][G::kKSteps];
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int kk = 0; kk < G::kKSteps; ++kk)
+                ka[kb][kk] = *reinterpret_cast<const bf16x8 *>(stage + k_rd[kk] + kb * 32 * G::kRowBytes);
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < G::kKSteps; ++kk)
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kb][kk], qf[kk], s[kb], 0, 0, 0);
+        }
+        if (NKB == 2) {
+            __builtin_amdgcn_sched_group_barrier(0x100, G::kKSteps, 0);      // LDS reads of block 0
+#pragma unroll
+            for (int kk = 0; kk < G::kKSteps; ++kk) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           // one product of block 0
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // one read of block 1
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);      // products of block 1
+        }
+
+        // ---- masks: ragged last prefix tile, tree tiles ----
+        const bool is_tree = cc.idx >= cc.n_pre;
+        if (is_tree) {
+            const int tt = cc.idx - cc.n_pre;
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb) {
+                uint32_t bits = row_real ? s_anc[node * 4 + tt * 2 + kg + kb] : 0u;
+                bits >>= 4 * h;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int r = (i >> 2) * 8 + (i & 3);    // + 4h, already shifted out
+                    if (!((bits >> r) & 1u)) s[kb][i] = -INFINITY;
+                }
+            }
+        } else if ((cc.idx + 1) * kTile > cc.L) {
+            const int n_valid = cc.L - cc.idx * kTile;
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int key = (kg + kb) * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
+                    if (key >= n_valid) s[kb][i] = -INFINITY;
+                }
+        }
+        // ---- online softmax along the keys (all values of a lane share one query row) ----
+        float mx = s[0][0];
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const bool grow = mx > m_run + grow_margin;     // also the first finite maximum (m_run = -inf)
+        if (__any(grow)) {
+            const float alpha = grow ? __builtin_amdgcn_exp2f((m_run - mx) * c2) : 1.f;   // m_run = -inf gives 0
+            m_run = grow ? mx : m_run;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < G::kOBlocks; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        }
+        const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
+        float lsum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(s[kb][i] * c2 - mc);
+                const float p1 = __builtin_amdgcn_exp2f(s[kb][i + 1] * c2 - mc);
+                lsum += p0 + p1;
+                pk[kb][i >> 1] = pack_bf16x2(p0, p1);
+            }
+        l_run += lsum;
+    };
+
+    // O^T += V^T . P^T : the S^T registers of a lane are, 8 at a time, the B operand
+    auto pv_product = [&](const char *stage) {
+#pragma unroll
+        for (int ks = 0; ks < 2 * NKB; ++ks) {
+            const int kb = ks >> 1, m2 = ks & 1;
+            u32x4 pv;
+            pv.x = pk[kb][4 * m2]; pv.y = pk[kb][4 * m2 + 1]; pv.z = pk[kb][4 * m2 + 2]; pv.w = pk[kb][4 * m2 + 3];
+            const bf16x8 pb = __builtin_bit_cast(bf16x8, pv);
+            const int key_base = (kb * 32 + m2 * 16) * G::kRowBytes;
+#pragma unroll
+            for (int db = 0; db < G::kOBlocks; ++db) {
+                const char *src = stage + v_rd[db] + key_base;
+                const s16x4 lo4 = lds_read_tr16(src);                         // keys +0..3 (+4h)
+                const s16x4 hi4 = lds_read_tr16(src + 8 * G::kRowBytes);      // keys +8..11 (+4h)
+                const s16x8 a8 = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
+            }
+        }
+    };
 
     for (int it = 0; it < n_iter; ++it) {
         const int stage_idx = it % kStages;
@@ -452,116 +559,28 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
 
         // start the copy of tile it + 2 into the stage tile it - 1 has just left
         if (it + 2 < n_iter) {
-            issue_copy<D>(p, dc, tp, cl, ring_lds + ((it + 2) % kStages) * G::kStageBytes, wave_s);
+            issue_copy<D>(p, dc, tp, cl, ring_lds + ((it + 2) % kStages) * G::kStageBytes, wave_s, bad);
             cursor_advance(dc, p, seq_lens);
-            tp = load_pages(p, page_table, dc, bad);     // page ids of tile it + 3
+            tp = load_pages(p, page_table, dc);     // page ids of tile it + 3
         }
 
+        const bool pair_ends = cc.idx + 1 == cc.n_units;
+        const bool last_iter = it + 1 == n_iter;
         if (wave_active) {
-            // ---- S^T = K . Q^T for this wavefront's key block(s) ----
-            // All fragment reads of a block are issued before its first matrix instruction,
-            // and a second block's reads are interleaved with the first block's products.
-            f32x16 s[NKB];
-            bf16x8 ka[NKB][G::kKSteps];
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                for (int kk = 0; kk < G::kKSteps; ++kk)
-                    ka[kb][kk] = *reinterpret_cast<const bf16x8 *>(stage + k_rd[kk] + kb * 32 * G::kRowBytes);
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
-#pragma unroll
-                for (int kk = 0; kk < G::kKSteps; ++kk)
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kb][kk], qf[kk], s[kb], 0, 0, 0);
+            // Wavefronts 4..7 share their SIMDs with wavefronts 0..3.  They run the three
+            // phases of a tile in a rotated order - the PV product of the previous tile first,
+            // then QK and softmax of this one - so that one wavefront's softmax (vector ALU)
+            // runs against the other's matrix products instead of both queueing for the same
+            // unit.  A tile's V rows therefore stay in the ring one iteration longer.
+            if (rotated && pv_pending) {
+                pv_product(ring + ((it + kStages - 1) % kStages) * G::kStageBytes);
+                pv_pending = false;
             }
-            if (NKB == 2) {
-                __builtin_amdgcn_sched_group_barrier(0x100, G::kKSteps, 0);      // LDS reads of block 0
-#pragma unroll
-                for (int kk = 0; kk < G::kKSteps; ++kk) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           // one product of block 0
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // one read of block 1
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);      // products of block 1
-            }
-
-            // ---- masks: ragged last prefix tile, tree tiles ----
-            const bool is_tree = cc.idx >= cc.n_pre;
-            if (is_tree) {
-                const int tt = cc.idx - cc.n_pre;
-#pragma unroll
-                for (int kb = 0; kb < NKB; ++kb) {
-                    uint32_t bits = row_real ? s_anc[node * 4 + tt * 2 + kg + kb] : 0u;
-                    bits >>= 4 * h;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int r = (i >> 2) * 8 + (i & 3);    // + 4h, already shifted out
-                        if (!((bits >> r) & 1u)) s[kb][i] = -INFINITY;
-                    }
-                }
-            } else if ((cc.idx + 1) * kTile > cc.L) {
-                const int n_valid = cc.L - cc.idx * kTile;
-#pragma unroll
-                for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int key = (kg + kb) * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
-                        if (key >= n_valid) s[kb][i] = -INFINITY;
-                    }
-            }
-            // ---- online softmax along the keys (all values of a lane share one query row) ----
-            float mx = s[0][0];
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_eff = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_eff) * c2);
-            m_run = m_new;
-            const float mc = m_eff * c2;
-            float lsum = 0.f;
-            uint32_t pk[NKB][8];
-#pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; i += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(s[kb][i] * c2 - mc);
-                    const float p1 = __builtin_amdgcn_exp2f(s[kb][i + 1] * c2 - mc);
-                    lsum += p0 + p1;
-                    pk[kb][i >> 1] = pack_bf16x2(p0, p1);
-                }
-            l_run = l_run * alpha + lsum;
-            if (__any(alpha != 1.f)) {
-#pragma unroll
-                for (int db = 0; db < G::kOBlocks; ++db)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-            }
-            // ---- O^T += V^T . P^T : the S^T registers of a lane are, 8 at a time, the B operand ----
-#pragma unroll
-            for (int ks = 0; ks < 2 * NKB; ++ks) {
-                const int kb = ks >> 1, m2 = ks & 1;
-                u32x4 pv;
-                pv.x = pk[kb][4 * m2]; pv.y = pk[kb][4 * m2 + 1]; pv.z = pk[kb][4 * m2 + 2]; pv.w = pk[kb][4 * m2 + 3];
-                const bf16x8 pb = __builtin_bit_cast(bf16x8, pv);
-                const int key_base = (kb * 32 + m2 * 16) * G::kRowBytes;
-#pragma unroll
-                for (int db = 0; db < G::kOBlocks; ++db) {
-                    const char *src = stage + v_rd[db] + key_base;
-                    const s16x4 lo4 = lds_read_tr16(src);                         // keys +0..3 (+4h)
-                    const s16x4 hi4 = lds_read_tr16(src + 8 * G::kRowBytes);      // keys +8..11 (+4h)
-                    const s16x8 a8 = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
-                }
-            }
+            qk_softmax(stage);
+            if (!rotated || pair_ends || last_iter) pv_product(stage); else pv_pending = true;
         }
 
         // ---- end of a segment: this pair ends here, or the range does ----
-        const bool pair_ends = cc.idx + 1 == cc.n_units;
-        const bool last_iter = it + 1 == n_iter;
         if (pair_ends || last_iter) {
             if (NKB == 1) {
                 // Key group 1 hands its state to key group 0 of the same row block through the
