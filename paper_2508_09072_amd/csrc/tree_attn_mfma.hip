@@ -55,7 +55,7 @@ namespace {
 
 constexpr float kLn2 = 0.69314718055994530942f;
 constexpr int kWaves = kThreads / 64;
-constexpr int kStages = 4;
+constexpr int kStages = 3;
 
 // Position along the flat unit axis: which pair, which tile of it.  Every field is
 // wave-uniform and lives in scalar registers.
@@ -397,18 +397,16 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     bool seg_from_pair_start = false;
     const float c2 = p.scale_log2;
 
-    const bool rotated = (wave_s & 4) != 0;
-    bool pv_pending = false;
     uint32_t pk[NKB][8];   // softmax weights of the current tile, bf16 pairs, in B-operand order
     // The running reference m_run is only raised when a row's maximum outgrows it by more
     // than 2^8 (in the exp2 domain), so the accumulator rescale is rare; weights stay <= 256.
     const float grow_margin = 8.f / c2;
 
-    // S^T = K . Q^T for this wavefront's key block(s), masks, online softmax -> pk
-    auto qk_softmax = [&](const char *stage) {
+    f32x16 s[NKB];         // S^T of the current tile
+    // S^T = K . Q^T for this wavefront's key block(s)
+    auto qk_product = [&](const char *stage) {
         // All fragment reads of a block are issued before its first matrix instruction,
         // and a second block's reads are interleaved with the first block's products.
-        f32x16 s[NKB];
         bf16x8 ka[NKB][G::kKSteps];
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb)
@@ -423,17 +421,20 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             for (int kk = 0; kk < G::kKSteps; ++kk)
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kb][kk], qf[kk], s[kb], 0, 0, 0);
         }
+        // instruction order handed to the scheduler: it serialises read/product pairs otherwise
+        __builtin_amdgcn_sched_group_barrier(0x100, G::kKSteps, 0);          // LDS reads of block 0
         if (NKB == 2) {
-            __builtin_amdgcn_sched_group_barrier(0x100, G::kKSteps, 0);      // LDS reads of block 0
 #pragma unroll
             for (int kk = 0; kk < G::kKSteps; ++kk) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           // one product of block 0
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // one read of block 1
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);      // products of block 1
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);          // products of the last block
+    };
 
-        // ---- masks: ragged last prefix tile, tree tiles ----
+    // masks (ragged last prefix tile, tree tiles) and online softmax of s -> pk
+    auto softmax = [&]() {
         const bool is_tree = cc.idx >= cc.n_pre;
         if (is_tree) {
             const int tt = cc.idx - cc.n_pre;
@@ -506,7 +507,18 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
             }
         }
+        // the V fragments of a 16-key step are read while the previous step's products run
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * G::kOBlocks, 0);
+#pragma unroll
+        for (int ks = 0; ks + 1 < 2 * NKB; ++ks)
+#pragma unroll
+            for (int db = 0; db < G::kOBlocks; ++db) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+        __builtin_amdgcn_sched_group_barrier(0x008, G::kOBlocks, 0);
     };
+
 
     for (int it = 0; it < n_iter; ++it) {
         const int stage_idx = it % kStages;
@@ -557,27 +569,28 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             }
         }
 
-        // start the copy of tile it + 2 into the stage tile it - 1 has just left
-        if (it + 2 < n_iter) {
-            issue_copy<D>(p, dc, tp, cl, ring_lds + ((it + 2) % kStages) * G::kStageBytes, wave_s, bad);
-            cursor_advance(dc, p, seq_lens);
-            tp = load_pages(p, page_table, dc);     // page ids of tile it + 3
-        }
+        // Start the copy of tile it + 2 into the stage that tile it - 2 has left.  The copy
+        // instructions queue up behind each other in the memory pipeline, so each wavefront
+        // issues them right after a batch of matrix instructions, which keep running meanwhile.
+        auto copy_ahead = [&]() {
+            if (it + 2 < n_iter)
+                issue_copy<D>(p, dc, tp, cl, ring_lds + ((it + 2) % kStages) * G::kStageBytes, wave_s, bad);
+        };
 
         const bool pair_ends = cc.idx + 1 == cc.n_units;
         const bool last_iter = it + 1 == n_iter;
         if (wave_active) {
-            // Wavefronts 4..7 share their SIMDs with wavefronts 0..3.  They run the three
-            // phases of a tile in a rotated order - the PV product of the previous tile first,
-            // then QK and softmax of this one - so that one wavefront's softmax (vector ALU)
-            // runs against the other's matrix products instead of both queueing for the same
-            // unit.  A tile's V rows therefore stay in the ring one iteration longer.
-            if (rotated && pv_pending) {
-                pv_product(ring + ((it + kStages - 1) % kStages) * G::kStageBytes);
-                pv_pending = false;
-            }
-            qk_softmax(stage);
-            if (!rotated || pair_ends || last_iter) pv_product(stage); else pv_pending = true;
+            qk_product(stage);
+            copy_ahead();
+            softmax();
+            pv_product(stage);
+        } else {
+            copy_ahead();
+        }
+        // page ids of tile it + 3: asked for last, so that they travel during the barrier wait
+        if (it + 2 < n_iter) {
+            cursor_advance(dc, p, seq_lens);
+            tp = load_pages(p, page_table, dc);
         }
 
         // ---- end of a segment: this pair ends here, or the range does ----
