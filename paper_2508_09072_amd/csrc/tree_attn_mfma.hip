@@ -232,57 +232,68 @@ __device__ inline CopyLane<D> make_copy_lane(const AttnParams &p, int wave, int 
     return cl;
 }
 
-// Start the copy of one unit into the LDS stage at byte address `stage`.  Every wavefront
-// issues exactly 2 * kCopies copy instructions, whatever the tile looks like: rows that do
-// not exist (past the sequence end, past the last tree node, behind an invalid page id)
-// are copied from a block of zeros, so a missing K row scores 0 (and is masked later) and
-// a missing V row contributes nothing.
+// What one wavefront needs to copy its 8 rows of a unit: wave-uniform base addresses and
+// which kind of source it is.  Every wavefront issues exactly 2 * kCopies copy instructions
+// per unit, whatever the tile looks like: rows that do not exist (past the sequence end, past
+// the last tree node, behind an invalid page id) are copied from a block of zeros, so a
+// missing K row scores 0 (and is masked later) and a missing V row contributes nothing.
+struct CopyPlan {
+    const char *kb, *vb;   // base of this wavefront's (page, head) block, or of the tree slab
+    int n_valid;           // rows of the tile that exist
+    bool whole;            // all 8 rows of this wavefront exist in the paged cache: uniform fast path
+    bool tree;
+    bool page_ok;
+};
+
 template <int D>
-__device__ inline void issue_copy(const AttnParams &p, const Cursor &c, const TilePages &tp, const CopyLane<D> &cl,
-                                  unsigned stage, int wave_s, int &bad) {
+__device__ inline CopyPlan plan_copy(const AttnParams &p, const Cursor &c, const TilePages &tp, int wave_s, int &bad) {
     using G = Geometry<D>;
-    const unsigned k_dst = stage + wave_s * G::kRowsPerWave * G::kRowBytes;
-    const unsigned v_dst = k_dst + G::kTileBytes;
-    const char *zeros = reinterpret_cast<const char *>(kZeroRow) + (threadIdx.x & 15) * 16;
+    CopyPlan cp;
     if (c.idx < c.n_pre) {
-        const int n_valid = min(kTile, c.L - c.idx * kTile);
+        cp.tree = false;
+        cp.n_valid = min(kTile, c.L - c.idx * kTile);
         const size_t page_bytes = (size_t)p.Hkv * 16 * D * 2;
         const size_t head_bytes = (size_t)c.hkv * 16 * D * 2;
         int page = (wave_s >> 1) == 0 ? tp.pg[0] : (wave_s >> 1) == 1 ? tp.pg[1] : (wave_s >> 1) == 2 ? tp.pg[2] : tp.pg[3];
-        if (page < 0 || page >= p.num_pages) {
-            if (wave_s * G::kRowsPerWave < n_valid) bad |= READER_STATUS_BAD_PAGE;   // this wavefront needed it
-            page = -1;
+        cp.page_ok = page >= 0 && page < p.num_pages;
+        if (!cp.page_ok) {
+            if (wave_s * G::kRowsPerWave < cp.n_valid) bad |= READER_STATUS_BAD_PAGE;   // this wavefront needed it
+            page = 0;
         }
-        const size_t boff = (size_t)(page >= 0 ? page : 0) * page_bytes + head_bytes;
-        const char *kb = reinterpret_cast<const char *>(p.k_cache) + boff;
-        const char *vb = reinterpret_cast<const char *>(p.v_cache) + boff;
-        const bool whole = page >= 0 && (wave_s + 1) * G::kRowsPerWave <= n_valid;   // wave-uniform
-        if (whole) {
-#pragma unroll
-            for (int i = 0; i < G::kCopies; ++i) {
-                copy16_uniform(kb, cl.k_cache_off[i], k_dst + i * 1024);
-                copy16_uniform(vb, cl.v_cache_off[i], v_dst + i * 1024);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < G::kCopies; ++i) {
-                const bool ok = page >= 0 && cl.row[i] < n_valid;
-                copy16_lane(ok ? kb + cl.k_cache_off[i] : zeros, k_dst + i * 1024);
-                copy16_lane(ok ? vb + cl.v_cache_off[i] : zeros, v_dst + i * 1024);
-            }
-        }
+        const size_t boff = (size_t)page * page_bytes + head_bytes;
+        cp.kb = reinterpret_cast<const char *>(p.k_cache) + boff;
+        cp.vb = reinterpret_cast<const char *>(p.v_cache) + boff;
+        cp.whole = cp.page_ok && (wave_s + 1) * G::kRowsPerWave <= cp.n_valid;
     } else {
         const int base = (c.idx - c.n_pre) * kTile;
-        const int n_valid = min(kTile, p.T - base);
+        cp.tree = true;
+        cp.page_ok = true;
+        cp.whole = false;
+        cp.n_valid = min(kTile, p.T - base);
         const size_t origin = (((size_t)c.b * p.T + base) * p.Hkv + c.hkv) * D * 2;
-        const char *kb = reinterpret_cast<const char *>(p.k_tree) + origin;
-        const char *vb = reinterpret_cast<const char *>(p.v_tree) + origin;
-#pragma unroll
-        for (int i = 0; i < G::kCopies; ++i) {
-            const bool ok = cl.row[i] < n_valid;
-            copy16_lane(ok ? kb + cl.k_tree_off[i] : zeros, k_dst + i * 1024);
-            copy16_lane(ok ? vb + cl.v_tree_off[i] : zeros, v_dst + i * 1024);
-        }
+        cp.kb = reinterpret_cast<const char *>(p.k_tree) + origin;
+        cp.vb = reinterpret_cast<const char *>(p.v_tree) + origin;
+    }
+    return cp;
+}
+
+// Copy instruction j of the unit (j < kCopies: K rows, else V rows) into the stage at LDS
+// byte address `stage`.
+template <int D>
+__device__ inline void emit_copy(const CopyPlan &cp, const CopyLane<D> &cl, unsigned stage, int wave_s, int j) {
+    using G = Geometry<D>;
+    const bool is_v = j >= G::kCopies;
+    const int i = is_v ? j - G::kCopies : j;
+    const unsigned dst = stage + (is_v ? G::kTileBytes : 0) + wave_s * G::kRowsPerWave * G::kRowBytes + i * 1024;
+    const char *base = is_v ? cp.vb : cp.kb;
+    if (cp.whole) {
+        copy16_uniform(base, is_v ? cl.v_cache_off[i] : cl.k_cache_off[i], dst);
+    } else {
+        const char *zeros = reinterpret_cast<const char *>(kZeroRow) + (threadIdx.x & 15) * 16;
+        const bool ok = cp.page_ok && cl.row[i] < cp.n_valid;
+        const unsigned off = cp.tree ? (is_v ? cl.v_tree_off[i] : cl.k_tree_off[i])
+                                     : (is_v ? cl.v_cache_off[i] : cl.k_cache_off[i]);
+        copy16_lane(ok ? base + off : zeros, dst);
     }
 }
 
@@ -325,9 +336,11 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     uint32_t *s_anc = reinterpret_cast<uint32_t *>(smem + kStages * G::kStageBytes); // [READER_MAX_T][4]
     int *s_par = reinterpret_cast<int *>(s_anc + READER_MAX_T * 4);                  // [READER_MAX_T]
     float *s_ml = reinterpret_cast<float *>(s_par + READER_MAX_T);                   // key group 1's sums [128][2] then maxima [128]
-    int *s_wsum = reinterpret_cast<int *>(s_ml + 384);                               // [8]
+    float *s_sink = s_ml + 384;                                                      // [64] landing zone of cache-warming copies
+    int *s_wsum = reinterpret_cast<int *>(s_sink + 64);                              // [8]
     int *s_pref = s_wsum + 8;                                                        // [B + 1]
     const unsigned ring_lds = (unsigned)(size_t)(lds_char *)ring;
+    const unsigned prefetch_lds = (unsigned)(size_t)(lds_char *)reinterpret_cast<char *>(s_sink);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -342,37 +355,87 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     const int group = row_real ? m_row - node * p.G : 0;
     const bool wave_active = chunk_base + rb * 32 < p.M;
 
-    scan_units(p, seq_lens, s_pref, s_wsum);
-    const long long U = (long long)p.Hkv * s_pref[p.B];
-    const long long lo = range_begin(blockIdx.x, U, p.n_ranges);
-    const long long hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
+    // Where this workgroup's range starts.  With at most 64 sequences every wavefront finds
+    // it on its own with a shuffle scan (no LDS, no barrier); larger batches scan through LDS.
+    long long U, lo, hi;
+    int first_b, first_pref;
+    if (p.B <= 64) {
+        int v = 0;
+        if (lane < p.B) v = (clamp_len(p, seq_lens, lane) + kTile - 1) / kTile + p.n_tree_tiles;
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t = __shfl_up(incl, off);
+            if (lane >= off) incl += t;
+        }
+        U = (long long)p.Hkv * __builtin_amdgcn_readfirstlane(__shfl(incl, 63));
+        lo = range_begin(blockIdx.x, U, p.n_ranges);
+        hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
+        const unsigned long long before = __ballot(lane < p.B && (long long)p.Hkv * (incl - v) <= lo);
+        first_b = __popcll(before) - 1;               // largest b whose first unit is <= lo
+        first_pref = __shfl(incl - v, first_b < 0 ? 0 : first_b);
+    } else {
+        scan_units(p, seq_lens, s_pref, s_wsum);
+        U = (long long)p.Hkv * __builtin_amdgcn_readfirstlane(s_pref[p.B]);
+        lo = range_begin(blockIdx.x, U, p.n_ranges);
+        hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
+        first_b = lo < hi ? find_seq(s_pref, p.B, p.Hkv, lo) : 0;
+        first_pref = s_pref[first_b];
+    }
     if (lo >= hi) return;
     const int n_iter = (int)(hi - lo);
 
     int bad = 0;
     Cursor cc;   // unit being computed
-    cc.b = __builtin_amdgcn_readfirstlane(find_seq(s_pref, p.B, p.Hkv, lo));
+    cc.b = __builtin_amdgcn_readfirstlane(first_b);
     cursor_enter_seq(cc, p, seq_lens);
     {
-        const long long rel = lo - (long long)p.Hkv * s_pref[cc.b];
+        const long long rel = lo - (long long)p.Hkv * __builtin_amdgcn_readfirstlane(first_pref);
         const int hkv = (int)(rel / cc.n_units);
         cc.hkv = __builtin_amdgcn_readfirstlane(hkv);
         cc.idx = __builtin_amdgcn_readfirstlane((int)(rel - (long long)hkv * cc.n_units));
     }
+
+    // This lane's query row as the B operand of the QK product.  The first segment's rows are
+    // asked for before anything else so that they travel together with the first tiles.
+    bf16x8 qf[G::kKSteps];
+    auto load_q = [&](int b, int hkv) {
+        const uint16_t *qrow = p.q + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D;
+#pragma unroll
+        for (int kk = 0; kk < G::kKSteps; ++kk)
+            qf[kk] = __builtin_bit_cast(bf16x8, keep_if(row_real, ld16(qrow + kk * 16 + h * 8)));
+    };
+    // Touch the next pair's query rows one tile before they are needed, so that they wait in
+    // the cache: an LDS copy of 4 bytes per lane into a scratch area nobody reads (a plain load
+    // would need a destination register that stays reserved until the data arrives).
+    auto prefetch_q = [&](int b, int hkv) {
+        const uint16_t *qrow = p.q + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D;
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off"
+                     :: "v"(qrow + (h * 64) % D), "s"(prefetch_lds) : "memory", "m0");
+    };
+    load_q(cc.b, cc.hkv);
+
     Cursor dc = cc;   // unit whose copy is issued next (two ahead of cc in steady state)
 
     const CopyLane<D> cl = make_copy_lane<D>(p, wave_s, lane);
 
     // prologue: tiles 0 and 1 in flight, page ids of tile 2 on their way
     TilePages tp = load_pages(p, page_table, dc);
-    issue_copy<D>(p, dc, tp, cl, ring_lds, wave_s, bad);
+    {
+        const CopyPlan cp = plan_copy<D>(p, dc, tp, wave_s, bad);
+#pragma unroll
+        for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D>(cp, cl, ring_lds, wave_s, j);
+    }
     cursor_advance(dc, p, seq_lens);
     tp = load_pages(p, page_table, dc);
     if (n_iter > 1) {
-        issue_copy<D>(p, dc, tp, cl, ring_lds + G::kStageBytes, wave_s, bad);
+        const CopyPlan cp = plan_copy<D>(p, dc, tp, wave_s, bad);
+#pragma unroll
+        for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D>(cp, cl, ring_lds + G::kStageBytes, wave_s, j);
         cursor_advance(dc, p, seq_lens);
         tp = load_pages(p, page_table, dc);
     }
+    Cursor pc = dc;   // unit whose page ids are fetched next (one ahead of dc in steady state)
 
     // per-lane LDS offsets of the matrix-core operand reads (relative to the stage)
     int k_rd[G::kKSteps];   // K fragment of k-step kk, first key block of this wavefront
@@ -390,7 +453,6 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
                        ((((db * 4) | c_lo) ^ swizzle_v<D>(key_lo)) << 4) + (i16 & 1) * 8;
     }
 
-    bf16x8 qf[G::kKSteps];
     f32x16 o[G::kOBlocks];
     float m_run = -INFINITY, l_run = 0.f;
     bool fresh = true;                 // the next unit starts a segment (new pair or range start)
@@ -433,8 +495,8 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);          // products of the last block
     };
 
-    // masks (ragged last prefix tile, tree tiles) and online softmax of s -> pk
-    auto softmax = [&]() {
+    // masks (ragged last prefix tile, tree tiles), row maximum, rare accumulator rescale
+    auto softmax_max = [&]() {
         const bool is_tree = cc.idx >= cc.n_pre;
         if (is_tree) {
             const int tt = cc.idx - cc.n_pre;
@@ -475,6 +537,10 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
         }
+    };
+
+    // softmax weights of s relative to the running reference -> pk, running sum
+    auto softmax_exp = [&]() {
         const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
         float lsum = 0.f;
 #pragma unroll
@@ -489,36 +555,35 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         l_run += lsum;
     };
 
-    // O^T += V^T . P^T : the S^T registers of a lane are, 8 at a time, the B operand
+    // O^T += V^T . P^T : the S^T registers of a lane are, 8 at a time, the B operand.
+    // Written in the order it should run: the V fragments of a 16-key step are read while
+    // the previous step's products execute.
     auto pv_product = [&](const char *stage) {
-#pragma unroll
-        for (int ks = 0; ks < 2 * NKB; ++ks) {
-            const int kb = ks >> 1, m2 = ks & 1;
-            u32x4 pv;
-            pv.x = pk[kb][4 * m2]; pv.y = pk[kb][4 * m2 + 1]; pv.z = pk[kb][4 * m2 + 2]; pv.w = pk[kb][4 * m2 + 3];
-            const bf16x8 pb = __builtin_bit_cast(bf16x8, pv);
-            const int key_base = (kb * 32 + m2 * 16) * G::kRowBytes;
+        auto read_step = [&](int ks, bf16x8 (&frag)[G::kOBlocks]) {
+            const int key_base = ((ks >> 1) * 32 + (ks & 1) * 16) * G::kRowBytes;
 #pragma unroll
             for (int db = 0; db < G::kOBlocks; ++db) {
                 const char *src = stage + v_rd[db] + key_base;
                 const s16x4 lo4 = lds_read_tr16(src);                         // keys +0..3 (+4h)
                 const s16x4 hi4 = lds_read_tr16(src + 8 * G::kRowBytes);      // keys +8..11 (+4h)
                 const s16x8 a8 = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
+                frag[db] = __builtin_bit_cast(bf16x8, a8);
             }
+        };
+        bf16x8 va[2][G::kOBlocks];
+        read_step(0, va[0]);
+#pragma unroll
+        for (int ks = 0; ks < 2 * NKB; ++ks) {
+            if (ks + 1 < 2 * NKB) read_step(ks + 1, va[(ks + 1) & 1]);
+            const int kb = ks >> 1, m2 = ks & 1;
+            u32x4 pv;
+            pv.x = pk[kb][4 * m2]; pv.y = pk[kb][4 * m2 + 1]; pv.z = pk[kb][4 * m2 + 2]; pv.w = pk[kb][4 * m2 + 3];
+            const bf16x8 pb = __builtin_bit_cast(bf16x8, pv);
+#pragma unroll
+            for (int db = 0; db < G::kOBlocks; ++db)
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks & 1][db], pb, o[db], 0, 0, 0);
         }
-        // the V fragments of a 16-key step are read while the previous step's products run
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * G::kOBlocks, 0);
-#pragma unroll
-        for (int ks = 0; ks + 1 < 2 * NKB; ++ks)
-#pragma unroll
-            for (int db = 0; db < G::kOBlocks; ++db) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            }
-        __builtin_amdgcn_sched_group_barrier(0x008, G::kOBlocks, 0);
     };
-
 
     for (int it = 0; it < n_iter; ++it) {
         const int stage_idx = it % kStages;
@@ -538,11 +603,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             for (int db = 0; db < G::kOBlocks; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-            // this lane's query row as the B operand of the QK product
-            const uint16_t *qrow = p.q + (((size_t)cc.b * p.T + node) * p.Hq + cc.hkv * p.G + group) * D;
-#pragma unroll
-            for (int kk = 0; kk < G::kKSteps; ++kk)
-                qf[kk] = __builtin_bit_cast(bf16x8, keep_if(row_real, ld16(qrow + kk * 16 + h * 8)));
+            if (it != 0) load_q(cc.b, cc.hkv);
             // ancestor-or-self masks of this sequence's tree, if this segment reaches its tree tiles
             if (cc.idx + (n_iter - it) > cc.n_pre) {
                 if (tid < p.T) {
@@ -569,28 +630,47 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             }
         }
 
-        // Start the copy of tile it + 2 into the stage that tile it - 2 has left.  The copy
-        // instructions queue up behind each other in the memory pipeline, so each wavefront
-        // issues them right after a batch of matrix instructions, which keep running meanwhile.
-        auto copy_ahead = [&]() {
-            if (it + 2 < n_iter)
-                issue_copy<D>(p, dc, tp, cl, ring_lds + ((it + 2) % kStages) * G::kStageBytes, wave_s, bad);
+        // Tile it + 2 is copied into the stage that tile it - 1 has left.  A wavefront stalls on
+        // a copy instruction while the memory pipeline is full, so the copies are spread over
+        // the iteration, each behind a batch of matrix or vector work.  The page ids of tile
+        // it + 3 are asked for first: they then travel while this tile is being computed.
+        const bool copy_next = it + 2 < n_iter;
+        CopyPlan cp;
+        TilePages tp_next = tp;
+        if (copy_next) {
+            cp = plan_copy<D>(p, dc, tp, wave_s, bad);
+            cursor_advance(pc, p, seq_lens);
+            tp_next = load_pages(p, page_table, pc);
+        }
+        const unsigned next_stage = ring_lds + ((it + 2) % kStages) * G::kStageBytes;
+        auto copy_part = [&](int part) {   // part 0..3
+            if (copy_next) {
+                if (kCopiesPerTile == 4) emit_copy<D>(cp, cl, next_stage, wave_s, part);
+                else if ((part & 1) == 0) emit_copy<D>(cp, cl, next_stage, wave_s, part >> 1);
+            }
         };
 
         const bool pair_ends = cc.idx + 1 == cc.n_units;
         const bool last_iter = it + 1 == n_iter;
+        if (pair_ends && !last_iter) {
+            const bool wrap = cc.hkv + 1 == p.Hkv;
+            prefetch_q(wrap ? cc.b + 1 : cc.b, wrap ? 0 : cc.hkv + 1);
+        }
         if (wave_active) {
             qk_product(stage);
-            copy_ahead();
-            softmax();
+            copy_part(0);
+            softmax_max();
+            copy_part(1);
+            softmax_exp();
+            copy_part(2);
             pv_product(stage);
+            copy_part(3);
         } else {
-            copy_ahead();
+            copy_part(0); copy_part(1); copy_part(2); copy_part(3);
         }
-        // page ids of tile it + 3: asked for last, so that they travel during the barrier wait
-        if (it + 2 < n_iter) {
+        if (copy_next) {
             cursor_advance(dc, p, seq_lens);
-            tp = load_pages(p, page_table, dc);
+            tp = tp_next;
         }
 
         // ---- end of a segment: this pair ends here, or the range does ----
@@ -759,7 +839,7 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
     using G = Geometry<D>;
     const size_t pref_bytes = ((size_t)(p.B + 1) * sizeof(int) + 15) & ~(size_t)15;
     const size_t main_lds = (size_t)kStages * G::kStageBytes + READER_MAX_T * 4 * sizeof(uint32_t) +
-                            READER_MAX_T * sizeof(int) + 384 * sizeof(float) + 8 * sizeof(int) + pref_bytes;
+                            READER_MAX_T * sizeof(int) + (384 + 64) * sizeof(float) + 8 * sizeof(int) + pref_bytes;
     // More than 64 KB of LDS per workgroup has to be asked for; the limit counts the
     // kernel's static LDS too, so ask for exactly what this launch needs.
     static size_t lds_allowed = 0;
