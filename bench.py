@@ -31,6 +31,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 ROTATE_BYTES = 512 << 20       # K/V copies cycled per step so the 256 MB Infinity Cache cannot serve the stream
+CALIBRATION_BYTES = 256 << 20  # size of the plain elementwise pass the counter runs are scaled by
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "tree_attn_mfma_kernel_hbm_traffic.txt")
 
 
 def log(*a):
@@ -151,9 +153,41 @@ def time_workload(R, torch, w, steps, warmup, use_graph=True):
                 "frac": tflops / MFMA_BF16_PEAK_TFLOPS}
     roof.update({"kernel": "tree_attn_mfma_kernel", "kernel_ms": kernel_ms, "launches_timed": n,
                  "algorithmic_bytes": alg_bytes, "algorithmic_flops": flops, "hbm_gbs": gbs,
-                 "hbm_frac": gbs / HBM_PEAK_GBS, "mfma_tflops": tflops, "traffic": None})
+                 "hbm_frac": gbs / HBM_PEAK_GBS, "mfma_tflops": tflops, "traffic": measured_traffic(w.name)})
     res["roofline"] = roof
     return res
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the attention kernel from the committed counter runs, or None.
+
+    bench.py cannot run the counter collector around itself; the figure is taken from the
+    summary of the two counter runs of this same command (one line per workload,
+    `traffic <workload> <bytes>`), which is re-made whenever the kernel changes.
+    """
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for ln in f:
+                tok = ln.split()
+                if len(tok) == 3 and tok[0] == "traffic" and tok[1] == workload_name:
+                    return float(tok[2])
+    except OSError:
+        pass
+    return None
+
+
+def calibration_pass(torch):
+    """One elementwise pass that reads and writes CALIBRATION_BYTES: the known-size kernel
+    the FETCH_SIZE / WRITE_SIZE readings of a counter run are scaled by."""
+    n = CALIBRATION_BYTES // 4
+    x = torch.ones(n, dtype=torch.int32, device="cuda")
+    y = torch.empty_like(x)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        torch.add(x, 1, out=y)
+    torch.cuda.synchronize()
+    assert int(y[-1].item()) == 2
+    del x, y
 
 
 def cpu_baseline(w, budget_s=12.0):
@@ -185,6 +219,8 @@ def main():
     ap.add_argument("--other-steps", type=int, default=30)
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-pass", action="store_true",
+                    help="also run a plain elementwise pass of known size (for counter runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported", file=sys.stderr)
@@ -200,6 +236,8 @@ def main():
     R.load()   # raises if the HIP library is missing: there is no fallback path
     torch.cuda.set_device(0)
 
+    if args.calibration_pass:
+        calibration_pass(torch)
     log("generating", W.CONFIG_NAMES[args.config])
     w = W.make_config(args.config)
     head = time_workload(R, torch, w, args.steps, args.warmup, use_graph=not args.no_graph)
