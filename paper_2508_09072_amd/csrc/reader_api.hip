@@ -26,7 +26,7 @@ static bool dims_ok(const reader_dims *d, int *err) {
         return false;
     }
     if (d->T > READER_MAX_T || (d->D != 64 && d->D != 128) || d->page_size != READER_PAGE_SIZE ||
-        d->Hq / d->Hkv > 16 || d->B > kMaxBatchScan) {
+        d->Hq / d->Hkv > 16 || d->B > kMaxBatchScan || d->num_pages * d->Hkv > 0x7fffffffLL) {
         *err = READER_EUNSUPPORTED;
         return false;
     }

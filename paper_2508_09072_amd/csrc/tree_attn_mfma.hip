@@ -57,41 +57,17 @@ constexpr float kLn2 = 0.69314718055994530942f;
 constexpr int kWaves = kThreads / 64;
 constexpr int kStages = 3;
 
-// Position along the flat unit axis: which pair, which tile of it.  Every field is
-// wave-uniform and lives in scalar registers.
-struct Cursor {
-    int b, hkv, idx;      // idx: unit index inside the pair
-    int n_pre, n_units;   // prefix tiles / all tiles of this pair
-    int L;                // clamped prefix length of sequence b
-};
-
 __device__ inline int clamp_len(const AttnParams &p, const int32_t *__restrict__ seq_lens, int b) {
     int L = seq_lens[b];
     L = L < 0 ? 0 : L;
     return L > p.max_seq_len ? p.max_seq_len : L;
 }
 
-__device__ inline void cursor_enter_seq(Cursor &c, const AttnParams &p, const int32_t *__restrict__ seq_lens) {
-    c.L = clamp_len(p, seq_lens, c.b);
-    c.n_pre = (c.L + kTile - 1) / kTile;
-    c.n_units = c.n_pre + p.n_tree_tiles;
-}
-
-__device__ inline void cursor_advance(Cursor &c, const AttnParams &p, const int32_t *__restrict__ seq_lens) {
-    if (++c.idx == c.n_units) {
-        c.idx = 0;
-        if (++c.hkv == p.Hkv) {
-            c.hkv = 0;
-            ++c.b;
-            if (c.b < p.B) cursor_enter_seq(c, p, seq_lens);
-        }
-    }
-}
-
 // Exclusive prefix sums of tiles-per-pair over the sequences, into s_pref[0..B].
 // Works for any workgroup size that is a multiple of 64 up to 512; s_wsum has 8 entries.
+// s_len (optional) receives the clamped prefix lengths.
 __device__ inline void scan_units(const AttnParams &p, const int32_t *__restrict__ seq_lens, int *s_pref,
-                                  int *s_wsum) {
+                                  int *s_wsum, int *s_len = nullptr) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n_threads = blockDim.x, n_waves = n_threads >> 6;
     int carry = 0;
@@ -99,7 +75,11 @@ __device__ inline void scan_units(const AttnParams &p, const int32_t *__restrict
     for (int base = 0; base < p.B; base += n_threads) {
         const int b = base + tid;
         int v = 0;
-        if (b < p.B) v = (clamp_len(p, seq_lens, b) + kTile - 1) / kTile + p.n_tree_tiles;
+        if (b < p.B) {
+            const int L = clamp_len(p, seq_lens, b);
+            if (s_len) s_len[b] = L;
+            v = (L + kTile - 1) / kTile + p.n_tree_tiles;
+        }
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int t = __shfl_up(v, off);
@@ -171,23 +151,63 @@ template <int D> __device__ inline int swizzle_v(int row) {
     return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 1)) : (((row >> 1) & 1) << 2);
 }
 
-// Page-table entries of one 64-key prefix tile, as loaded (validated where they are used, one
-// iteration later, so that the scalar loads have a whole tile of time to come back).
-struct TilePages {
-    int pg[4];
+// One entry of a workgroup's tile list, kept in LDS.  The workgroup writes the list itself,
+// up to kDescSlots tiles ahead of the tile being computed, so the main loop reads neither the
+// sequence lengths nor the page table and spends no scalar work on finding its place.
+struct TileDesc {
+    int blk[4];    // prefix tile: page * Hkv + kv head of each 16-key quarter, -1 where the quarter
+                   // reads as zeros; tree tile: all four = ((b * T + first node) * Hkv + kv head)
+    int n_valid;   // rows of the tile that exist (1..64)
+    int flags;     // kDesc* bits, number of the tree tile from bit 8 up
+    int b;         // sequence
+    int hkv;       // kv head
 };
+enum {
+    kDescTree = 1,        // keys are tree nodes (masked by ancestor sets), else prefix positions
+    kDescFresh = 2,       // first tile of a segment: new pair, or start of the workgroup's range
+    kDescPairEnd = 4,     // last tile of its pair
+    kDescMasks = 8,       // (on a fresh tile) the segment reaches the pair's tree tiles
+    kDescPairStart = 16,  // first tile of its pair
+};
+constexpr int kDescSlots = 256;
 
-__device__ inline TilePages load_pages(const AttnParams &p, const int32_t *__restrict__ page_table, const Cursor &c) {
-    TilePages t;
-    if (c.b < p.B && c.idx < c.n_pre) {
-        const int32_t *row = page_table + (size_t)c.b * p.max_pages;
-        const int last = p.max_pages - 1;
+// Descriptor of tile i of the range that starts at unit lo and holds n_iter tiles.
+__device__ inline void build_desc(const AttnParams &p, const int32_t *__restrict__ page_table, const int *s_pref,
+                                  const int *s_len, long long lo, int n_iter, int i, TileDesc *slot, int &bad) {
+    const long long x = lo + i;
+    const int b = find_seq(s_pref, p.B, p.Hkv, x);
+    const int L = s_len[b];
+    const int n_pre = (L + kTile - 1) / kTile, n_units = n_pre + p.n_tree_tiles;
+    const int rel = (int)(x - (long long)p.Hkv * s_pref[b]);
+    const int hkv = rel / n_units, idx = rel - hkv * n_units;
+    int blk[4], n_valid, flags = 0;
+    if (idx < n_pre) {
+        n_valid = min(kTile, L - idx * kTile);
+        const int32_t *row = page_table + (size_t)b * p.max_pages + idx * 4;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) t.pg[j] = row[min(c.idx * 4 + j, last)];
+        for (int j = 0; j < 4; ++j) {
+            blk[j] = -1;
+            if (j * 16 < n_valid) {   // position idx*64 + j*16 < L <= 16 * max_pages: inside the row
+                const int page = row[j];
+                if (page >= 0 && page < p.num_pages) blk[j] = page * p.Hkv + hkv;
+                else bad |= READER_STATUS_BAD_PAGE;
+            }
+        }
     } else {
-        t.pg[0] = t.pg[1] = t.pg[2] = t.pg[3] = -1;
+        const int tt = idx - n_pre;
+        n_valid = min(kTile, p.T - tt * kTile);
+        flags = kDescTree | (tt << 8);
+        blk[0] = blk[1] = blk[2] = blk[3] = (b * p.T + tt * kTile) * p.Hkv + hkv;
     }
-    return t;
+    if (idx == 0) flags |= kDescPairStart;
+    if (idx + 1 == n_units) flags |= kDescPairEnd;
+    if (idx == 0 || i == 0) {
+        flags |= kDescFresh;
+        if (idx + (n_iter - i) > n_pre) flags |= kDescMasks;
+    }
+    int4 *dst = reinterpret_cast<int4 *>(slot);
+    dst[0] = make_int4(blk[0], blk[1], blk[2], blk[3]);
+    dst[1] = make_int4(n_valid, flags, b, hkv);
 }
 
 // Asynchronous copy HBM -> LDS: lane l moves 16 bytes from its global address to LDS byte
@@ -246,33 +266,22 @@ struct CopyPlan {
 };
 
 template <int D>
-__device__ inline CopyPlan plan_copy(const AttnParams &p, const Cursor &c, const TilePages &tp, int wave_s, int &bad) {
+__device__ inline CopyPlan plan_copy(const AttnParams &p, int blk, int n_valid, int flags, int wave_s) {
     using G = Geometry<D>;
     CopyPlan cp;
-    if (c.idx < c.n_pre) {
-        cp.tree = false;
-        cp.n_valid = min(kTile, c.L - c.idx * kTile);
-        const size_t page_bytes = (size_t)p.Hkv * 16 * D * 2;
-        const size_t head_bytes = (size_t)c.hkv * 16 * D * 2;
-        int page = (wave_s >> 1) == 0 ? tp.pg[0] : (wave_s >> 1) == 1 ? tp.pg[1] : (wave_s >> 1) == 2 ? tp.pg[2] : tp.pg[3];
-        cp.page_ok = page >= 0 && page < p.num_pages;
-        if (!cp.page_ok) {
-            if (wave_s * G::kRowsPerWave < cp.n_valid) bad |= READER_STATUS_BAD_PAGE;   // this wavefront needed it
-            page = 0;
-        }
-        const size_t boff = (size_t)page * page_bytes + head_bytes;
+    cp.n_valid = n_valid;
+    cp.tree = (flags & kDescTree) != 0;
+    cp.page_ok = blk >= 0;
+    if (!cp.tree) {
+        const size_t boff = (size_t)(cp.page_ok ? blk : 0) * (16 * G::kRowBytes);
         cp.kb = reinterpret_cast<const char *>(p.k_cache) + boff;
         cp.vb = reinterpret_cast<const char *>(p.v_cache) + boff;
-        cp.whole = cp.page_ok && (wave_s + 1) * G::kRowsPerWave <= cp.n_valid;
+        cp.whole = cp.page_ok && (wave_s + 1) * G::kRowsPerWave <= n_valid;
     } else {
-        const int base = (c.idx - c.n_pre) * kTile;
-        cp.tree = true;
-        cp.page_ok = true;
-        cp.whole = false;
-        cp.n_valid = min(kTile, p.T - base);
-        const size_t origin = (((size_t)c.b * p.T + base) * p.Hkv + c.hkv) * D * 2;
+        const size_t origin = (size_t)blk * G::kRowBytes;
         cp.kb = reinterpret_cast<const char *>(p.k_tree) + origin;
         cp.vb = reinterpret_cast<const char *>(p.v_tree) + origin;
+        cp.whole = false;
     }
     return cp;
 }
@@ -338,7 +347,9 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     float *s_ml = reinterpret_cast<float *>(s_par + READER_MAX_T);                   // key group 1's sums [128][2] then maxima [128]
     float *s_sink = s_ml + 384;                                                      // [64] landing zone of cache-warming copies
     int *s_wsum = reinterpret_cast<int *>(s_sink + 64);                              // [8]
-    int *s_pref = s_wsum + 8;                                                        // [B + 1]
+    TileDesc *s_desc = reinterpret_cast<TileDesc *>(s_wsum + 8);                     // [kDescSlots]
+    int *s_pref = reinterpret_cast<int *>(s_desc + kDescSlots);                      // [B + 1]
+    int *s_len = s_pref + p.B + 1;                                                   // [B]
     const unsigned ring_lds = (unsigned)(size_t)(lds_char *)ring;
     const unsigned prefetch_lds = (unsigned)(size_t)(lds_char *)reinterpret_cast<char *>(s_sink);
 
@@ -355,49 +366,40 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     const int group = row_real ? m_row - node * p.G : 0;
     const bool wave_active = chunk_base + rb * 32 < p.M;
 
-    // Where this workgroup's range starts.  With at most 64 sequences every wavefront finds
-    // it on its own with a shuffle scan (no LDS, no barrier); larger batches scan through LDS.
-    long long U, lo, hi;
-    int first_b, first_pref;
+    // Tiles per sequence (prefix sums) and clamped lengths go to LDS.  With at most 64 sequences
+    // every wavefront scans on its own and all of them write the same values, so a wavefront
+    // may read them back without a barrier (its own LDS accesses execute in order).
     if (p.B <= 64) {
-        int v = 0;
-        if (lane < p.B) v = (clamp_len(p, seq_lens, lane) + kTile - 1) / kTile + p.n_tree_tiles;
+        int L = 0, v = 0;
+        if (lane < p.B) {
+            L = clamp_len(p, seq_lens, lane);
+            v = (L + kTile - 1) / kTile + p.n_tree_tiles;
+        }
         int incl = v;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int t = __shfl_up(incl, off);
             if (lane >= off) incl += t;
         }
-        U = (long long)p.Hkv * __builtin_amdgcn_readfirstlane(__shfl(incl, 63));
-        lo = range_begin(blockIdx.x, U, p.n_ranges);
-        hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
-        const unsigned long long before = __ballot(lane < p.B && (long long)p.Hkv * (incl - v) <= lo);
-        first_b = __popcll(before) - 1;               // largest b whose first unit is <= lo
-        first_pref = __shfl(incl - v, first_b < 0 ? 0 : first_b);
+        if (lane < p.B) {
+            s_pref[lane + 1] = incl;
+            s_len[lane] = L;
+        }
+        if (lane == 0) s_pref[0] = 0;
     } else {
-        scan_units(p, seq_lens, s_pref, s_wsum);
-        U = (long long)p.Hkv * __builtin_amdgcn_readfirstlane(s_pref[p.B]);
-        lo = range_begin(blockIdx.x, U, p.n_ranges);
-        hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
-        first_b = lo < hi ? find_seq(s_pref, p.B, p.Hkv, lo) : 0;
-        first_pref = s_pref[first_b];
+        scan_units(p, seq_lens, s_pref, s_wsum, s_len);
     }
+    const long long U = (long long)p.Hkv * __builtin_amdgcn_readfirstlane(s_pref[p.B]);
+    const long long lo = range_begin(blockIdx.x, U, p.n_ranges);
+    const long long hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
     if (lo >= hi) return;
     const int n_iter = (int)(hi - lo);
 
     int bad = 0;
-    Cursor cc;   // unit being computed
-    cc.b = __builtin_amdgcn_readfirstlane(first_b);
-    cursor_enter_seq(cc, p, seq_lens);
-    {
-        const long long rel = lo - (long long)p.Hkv * __builtin_amdgcn_readfirstlane(first_pref);
-        const int hkv = (int)(rel / cc.n_units);
-        cc.hkv = __builtin_amdgcn_readfirstlane(hkv);
-        cc.idx = __builtin_amdgcn_readfirstlane((int)(rel - (long long)hkv * cc.n_units));
-    }
+    for (int i = tid; i < min(n_iter, kDescSlots); i += kThreads)
+        build_desc(p, page_table, s_pref, s_len, lo, n_iter, i, s_desc + i, bad);
 
-    // This lane's query row as the B operand of the QK product.  The first segment's rows are
-    // asked for before anything else so that they travel together with the first tiles.
+    // This lane's query row as the B operand of the QK product.
     bf16x8 qf[G::kKSteps];
     auto load_q = [&](int b, int hkv) {
         const uint16_t *qrow = p.q + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D;
@@ -413,29 +415,26 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off"
                      :: "v"(qrow + (h * 64) % D), "s"(prefetch_lds) : "memory", "m0");
     };
-    load_q(cc.b, cc.hkv);
-
-    Cursor dc = cc;   // unit whose copy is issued next (two ahead of cc in steady state)
 
     const CopyLane<D> cl = make_copy_lane<D>(p, wave_s, lane);
+    __syncthreads();   // the tile list is written
 
-    // prologue: tiles 0 and 1 in flight, page ids of tile 2 on their way
-    TilePages tp = load_pages(p, page_table, dc);
-    {
-        const CopyPlan cp = plan_copy<D>(p, dc, tp, wave_s, bad);
+    // Descriptor words a wavefront needs of a tile: for computing it (rows, flags) and for
+    // copying it (this wavefront's quarter).  Uniform values, moved to scalar registers.
+    auto desc_of = [&](int i) -> const TileDesc * { return s_desc + (i & (kDescSlots - 1)); };
+    auto issue_tile = [&](int i, unsigned stage_lds) {
+        const TileDesc *d = desc_of(i);
+        const int blk = __builtin_amdgcn_readfirstlane(d->blk[wave_s >> 1]);
+        const int nv = __builtin_amdgcn_readfirstlane(d->n_valid);
+        const int fl = __builtin_amdgcn_readfirstlane(d->flags);
+        const CopyPlan cp = plan_copy<D>(p, blk, nv, fl, wave_s);
 #pragma unroll
-        for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D>(cp, cl, ring_lds, wave_s, j);
-    }
-    cursor_advance(dc, p, seq_lens);
-    tp = load_pages(p, page_table, dc);
-    if (n_iter > 1) {
-        const CopyPlan cp = plan_copy<D>(p, dc, tp, wave_s, bad);
-#pragma unroll
-        for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D>(cp, cl, ring_lds + G::kStageBytes, wave_s, j);
-        cursor_advance(dc, p, seq_lens);
-        tp = load_pages(p, page_table, dc);
-    }
-    Cursor pc = dc;   // unit whose page ids are fetched next (one ahead of dc in steady state)
+        for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D>(cp, cl, stage_lds, wave_s, j);
+    };
+    // prologue: the first segment's query rows, then tiles 0 and 1
+    load_q(__builtin_amdgcn_readfirstlane(s_desc[0].b), __builtin_amdgcn_readfirstlane(s_desc[0].hkv));
+    issue_tile(0, ring_lds);
+    if (n_iter > 1) issue_tile(1, ring_lds + G::kStageBytes);
 
     // per-lane LDS offsets of the matrix-core operand reads (relative to the stage)
     int k_rd[G::kKSteps];   // K fragment of k-step kk, first key block of this wavefront
@@ -455,7 +454,6 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
 
     f32x16 o[G::kOBlocks];
     float m_run = -INFINITY, l_run = 0.f;
-    bool fresh = true;                 // the next unit starts a segment (new pair or range start)
     bool seg_from_pair_start = false;
     const float c2 = p.scale_log2;
 
@@ -496,10 +494,8 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     };
 
     // masks (ragged last prefix tile, tree tiles), row maximum, rare accumulator rescale
-    auto softmax_max = [&]() {
-        const bool is_tree = cc.idx >= cc.n_pre;
+    auto softmax_max = [&](bool is_tree, int tt, int n_valid) {
         if (is_tree) {
-            const int tt = cc.idx - cc.n_pre;
 #pragma unroll
             for (int kb = 0; kb < NKB; ++kb) {
                 uint32_t bits = row_real ? s_anc[node * 4 + tt * 2 + kg + kb] : 0u;
@@ -510,8 +506,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
                     if (!((bits >> r) & 1u)) s[kb][i] = -INFINITY;
                 }
             }
-        } else if ((cc.idx + 1) * kTile > cc.L) {
-            const int n_valid = cc.L - cc.idx * kTile;
+        } else if (n_valid < kTile) {
 #pragma unroll
             for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
@@ -585,29 +580,55 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         }
     };
 
+    // LDS byte offsets of the ring stages: tile being computed, next tile, tile being copied
+    int st_cur = 0, st_nxt = G::kStageBytes, st_cpy = 2 * G::kStageBytes;
+    // descriptor words of the tile to compute (rows, flags) and of the tile to copy, read one
+    // iteration ahead so that the LDS latency hides behind the barrier
+    int2 d_cur = *reinterpret_cast<const int2 *>(&desc_of(0)->n_valid);
+    int2 d_cpy = *reinterpret_cast<const int2 *>(&desc_of(2)->n_valid);
+    int d_blk = desc_of(2)->blk[wave_s >> 1];
+
     for (int it = 0; it < n_iter; ++it) {
-        const int stage_idx = it % kStages;
-        const char *stage = ring + stage_idx * G::kStageBytes;
+        const char *stage = ring + st_cur;
+        const int t_valid = __builtin_amdgcn_readfirstlane(d_cur.x);
+        const int t_flags = __builtin_amdgcn_readfirstlane(d_cur.y);
+        const int c_valid = __builtin_amdgcn_readfirstlane(d_cpy.x);
+        const int c_flags = __builtin_amdgcn_readfirstlane(d_cpy.y);
+        const int c_blk = __builtin_amdgcn_readfirstlane(d_blk);
+        const bool last_iter = it + 1 == n_iter;
+        const bool copy_next = it + 2 < n_iter;
 
         // This wavefront's part of tile `it` has landed once at most the copies of tile
         // it + 1 are outstanding (copies complete in the order they were issued).
-        if (it + 1 < n_iter) wait_vmcnt<kCopiesPerTile>(); else wait_vmcnt<0>();
+        if (!last_iter) wait_vmcnt<kCopiesPerTile>(); else wait_vmcnt<0>();
         __syncthreads();   // tile `it` is complete in LDS; every wavefront is done with tile it - 1
 
-        if (fresh) {
-            fresh = false;
-            seg_from_pair_start = (cc.idx == 0);
+        // next iteration's descriptor words
+        d_cur = *reinterpret_cast<const int2 *>(&desc_of(it + 1)->n_valid);
+        d_cpy = *reinterpret_cast<const int2 *>(&desc_of(it + 3)->n_valid);
+        d_blk = desc_of(it + 3)->blk[wave_s >> 1];
+
+        // The tile list is extended half a list at a time, by the first two wavefronts, while
+        // the half it replaces is no longer read and long before the new half is.
+        if ((it & (kDescSlots / 2 - 1)) == 0 && it > 0 && tid < kDescSlots / 2) {
+            const int i = it + kDescSlots / 2 + tid;
+            if (i < n_iter) build_desc(p, page_table, s_pref, s_len, lo, n_iter, i, s_desc + (i & (kDescSlots - 1)), bad);
+        }
+
+        if (t_flags & kDescFresh) {
+            seg_from_pair_start = (t_flags & kDescPairStart) != 0;
             m_run = -INFINITY;
             l_run = 0.f;
 #pragma unroll
             for (int db = 0; db < G::kOBlocks; ++db)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-            if (it != 0) load_q(cc.b, cc.hkv);
+            const int sb = __builtin_amdgcn_readfirstlane(desc_of(it)->b);
+            if (it != 0) load_q(sb, __builtin_amdgcn_readfirstlane(desc_of(it)->hkv));
             // ancestor-or-self masks of this sequence's tree, if this segment reaches its tree tiles
-            if (cc.idx + (n_iter - it) > cc.n_pre) {
+            if (t_flags & kDescMasks) {
                 if (tid < p.T) {
-                    int pi = p.parents[(size_t)cc.b * p.T + tid];
+                    int pi = p.parents[(size_t)sb * p.T + tid];
                     const bool valid = tid == 0 ? pi == -1 : (pi >= 0 && pi < tid);
                     if (!valid) { bad |= READER_STATUS_BAD_TREE; pi = -1; }
                     s_par[tid] = pi;
@@ -630,36 +651,28 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             }
         }
 
+        const bool pair_ends = (t_flags & kDescPairEnd) != 0;
+        if (pair_ends && !last_iter) {
+            const TileDesc *dn = desc_of(it + 1);
+            prefetch_q(__builtin_amdgcn_readfirstlane(dn->b), __builtin_amdgcn_readfirstlane(dn->hkv));
+        }
+
         // Tile it + 2 is copied into the stage that tile it - 1 has left.  A wavefront stalls on
         // a copy instruction while the memory pipeline is full, so the copies are spread over
-        // the iteration, each behind a batch of matrix or vector work.  The page ids of tile
-        // it + 3 are asked for first: they then travel while this tile is being computed.
-        const bool copy_next = it + 2 < n_iter;
+        // the iteration, each behind a batch of matrix or vector work.
+        const unsigned next_stage = ring_lds + st_cpy;
         CopyPlan cp;
-        TilePages tp_next = tp;
-        if (copy_next) {
-            cp = plan_copy<D>(p, dc, tp, wave_s, bad);
-            cursor_advance(pc, p, seq_lens);
-            tp_next = load_pages(p, page_table, pc);
-        }
-        const unsigned next_stage = ring_lds + ((it + 2) % kStages) * G::kStageBytes;
+        if (copy_next) cp = plan_copy<D>(p, c_blk, c_valid, c_flags, wave_s);
         auto copy_part = [&](int part) {   // part 0..3
             if (copy_next) {
                 if (kCopiesPerTile == 4) emit_copy<D>(cp, cl, next_stage, wave_s, part);
                 else if ((part & 1) == 0) emit_copy<D>(cp, cl, next_stage, wave_s, part >> 1);
             }
         };
-
-        const bool pair_ends = cc.idx + 1 == cc.n_units;
-        const bool last_iter = it + 1 == n_iter;
-        if (pair_ends && !last_iter) {
-            const bool wrap = cc.hkv + 1 == p.Hkv;
-            prefetch_q(wrap ? cc.b + 1 : cc.b, wrap ? 0 : cc.hkv + 1);
-        }
         if (wave_active) {
             qk_product(stage);
             copy_part(0);
-            softmax_max();
+            softmax_max((t_flags & kDescTree) != 0, t_flags >> 8, t_valid);
             copy_part(1);
             softmax_exp();
             copy_part(2);
@@ -668,13 +681,15 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         } else {
             copy_part(0); copy_part(1); copy_part(2); copy_part(3);
         }
-        if (copy_next) {
-            cursor_advance(dc, p, seq_lens);
-            tp = tp_next;
+        {
+            const int t = st_cur;
+            st_cur = st_nxt; st_nxt = st_cpy; st_cpy = t;
         }
 
         // ---- end of a segment: this pair ends here, or the range does ----
         if (pair_ends || last_iter) {
+            const int e_b = __builtin_amdgcn_readfirstlane(desc_of(it)->b);
+            const int e_hkv = __builtin_amdgcn_readfirstlane(desc_of(it)->hkv);
             if (NKB == 1) {
                 // Key group 1 hands its state to key group 0 of the same row block through the
                 // stage that has just been consumed, half of the output blocks at a time.
@@ -721,7 +736,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
                 if (seg_from_pair_start && pair_ends) {
                     if (row_real) {
                         const float inv = 1.f / l_tot;
-                        uint16_t *orow = p.out + (((size_t)cc.b * p.T + node) * p.Hq + cc.hkv * p.G + group) * D;
+                        uint16_t *orow = p.out + (((size_t)e_b * p.T + node) * p.Hq + e_hkv * p.G + group) * D;
 #pragma unroll
                         for (int db = 0; db < G::kOBlocks; ++db)
 #pragma unroll
@@ -732,7 +747,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
                                 *reinterpret_cast<uint2 *>(orow + db * 32 + i4 * 8 + 4 * h) = w;
                             }
                         if (p.lse && h == 0)
-                            p.lse[((size_t)cc.b * p.Hq + cc.hkv * p.G + group) * p.T + node] =
+                            p.lse[((size_t)e_b * p.Hq + e_hkv * p.G + group) * p.T + node] =
                                 (m_run * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
                     }
                 } else {
@@ -751,9 +766,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
                     }
                 }
             }
-            fresh = true;
         }
-        cursor_advance(cc, p, seq_lens);
     }
 
     if (p.status && bad) atomicOr(p.status, bad);
@@ -839,7 +852,8 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
     using G = Geometry<D>;
     const size_t pref_bytes = ((size_t)(p.B + 1) * sizeof(int) + 15) & ~(size_t)15;
     const size_t main_lds = (size_t)kStages * G::kStageBytes + READER_MAX_T * 4 * sizeof(uint32_t) +
-                            READER_MAX_T * sizeof(int) + (384 + 64) * sizeof(float) + 8 * sizeof(int) + pref_bytes;
+                            READER_MAX_T * sizeof(int) + (384 + 64) * sizeof(float) + 8 * sizeof(int) +
+                            kDescSlots * sizeof(TileDesc) + (((size_t)(2 * p.B + 1) * sizeof(int) + 15) & ~(size_t)15);
     // More than 64 KB of LDS per workgroup has to be asked for; the limit counts the
     // kernel's static LDS too, so ask for exactly what this launch needs.
     static size_t lds_allowed = 0;
