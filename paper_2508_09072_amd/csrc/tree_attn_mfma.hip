@@ -12,14 +12,16 @@
 //   in place; a pair cut between workgroups leaves one partial record (unnormalised
 //   output, running max, running sum) per workgroup and a second kernel merges them.
 //   blockIdx.y selects a chunk of query rows when T*G exceeds what a workgroup carries.
+//   Each workgroup first writes the list of its tiles (page ids, row counts, segment
+//   flags) into LDS, so the main loop does no bookkeeping.
 //
 // One workgroup = 8 wavefronts.  A query row is a (tree node, grouped query head) pair, so
 // one K/V tile serves all heads of the group and all tree nodes.
-//   T*G <= 128: 4 row blocks of 32 rows x 2 key groups; a wavefront takes one row block
-//               and one 32-key half of every tile, and the two key groups of a row block
-//               merge their softmax states through LDS when a pair (or the range) ends;
-//   T*G  > 128: 8 row blocks of 32 rows, every wavefront takes whole tiles.
-// Per tile and 32-key block a wavefront computes
+//   T*G <= 128: wavefronts 0..3 compute one block of 32 query rows each, wavefronts 4..7
+//               only move data (tile copies, the next pair's query rows, parent pointers
+//               and ancestor masks, the tile list), always ahead of the computation;
+//   T*G  > 128: 8 row blocks of 32 rows, every wavefront computes and copies.
+// Per tile and 32-key block a computing wavefront runs
 //     S^T[32 keys][32 rows] = K_block . Q^T        8 x v_mfma_f32_32x32x16_bf16 (D = 128)
 //     online softmax down the key axis: the scores a lane holds all belong to one
 //     query row, so the row max is in-lane max ops plus one cross-lane swap
@@ -31,10 +33,9 @@
 //
 // K/V tiles go HBM -> LDS directly (global_load_lds_dwordx4: each wavefront instruction
 // moves 1 KB, no staging registers) into a ring of three tile buffers, so two tiles are
-// in flight while one is consumed; one barrier per tile.  Page ids are fetched with
-// scalar loads one more tile ahead.  16-byte chunks are XOR-swizzled inside a tile row
-// (applied on the global-address side of the copy) so that operand reads hit every LDS
-// bank once.
+// in flight while one is consumed; one barrier per tile.  16-byte chunks are XOR-swizzled
+// inside a tile row (applied on the global-address side of the copy) so that operand reads
+// hit every LDS bank once.
 #include "internal.h"
 
 namespace reader {
@@ -65,9 +66,8 @@ __device__ inline int clamp_len(const AttnParams &p, const int32_t *__restrict__
 
 // Exclusive prefix sums of tiles-per-pair over the sequences, into s_pref[0..B].
 // Works for any workgroup size that is a multiple of 64 up to 512; s_wsum has 8 entries.
-// s_len (optional) receives the clamped prefix lengths.
 __device__ inline void scan_units(const AttnParams &p, const int32_t *__restrict__ seq_lens, int *s_pref,
-                                  int *s_wsum, int *s_len = nullptr) {
+                                  int *s_wsum) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n_threads = blockDim.x, n_waves = n_threads >> 6;
     int carry = 0;
@@ -75,11 +75,7 @@ __device__ inline void scan_units(const AttnParams &p, const int32_t *__restrict
     for (int base = 0; base < p.B; base += n_threads) {
         const int b = base + tid;
         int v = 0;
-        if (b < p.B) {
-            const int L = clamp_len(p, seq_lens, b);
-            if (s_len) s_len[b] = L;
-            v = (L + kTile - 1) / kTile + p.n_tree_tiles;
-        }
+        if (b < p.B) v = (clamp_len(p, seq_lens, b) + kTile - 1) / kTile + p.n_tree_tiles;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int t = __shfl_up(v, off);
@@ -125,15 +121,16 @@ __device__ inline u32x4 keep_if(bool ok, u32x4 v) {
     return v;
 }
 
-template <int D>
+// CW: wavefronts that copy tiles (each takes 64 / CW rows of every tile).
+template <int D, int CW>
 struct Geometry {
     static constexpr int kChunks = D / 8;                       // 16-byte chunks per K/V row
     static constexpr int kRowBytes = D * 2;
     static constexpr int kTileBytes = kTile * kRowBytes;        // one K (or V) tile in LDS
     static constexpr int kStageBytes = 2 * kTileBytes;          // K tile then V tile
     static constexpr int kRowsPerCopy = 1024 / kRowBytes;       // tile rows one wavefront copy instruction moves
-    static constexpr int kRowsPerWave = kTile / kWaves;         // tile rows a wavefront copies per tile (8)
-    static constexpr int kCopies = kRowsPerWave / kRowsPerCopy; // copy instructions per wavefront, per tile, for K and for V each
+    static constexpr int kRowsPerWave = kTile / CW;             // tile rows a copying wavefront moves per tile (8 or 16)
+    static constexpr int kCopies = kRowsPerWave / kRowsPerCopy; // copy instructions per copying wavefront, per tile, for K and for V each
     static constexpr int kKSteps = D / 16;                      // MFMA k-steps of the QK product
     static constexpr int kOBlocks = D / 32;                     // 32-wide blocks of the output dim
 };
@@ -172,11 +169,12 @@ enum {
 constexpr int kDescSlots = 256;
 
 // Descriptor of tile i of the range that starts at unit lo and holds n_iter tiles.
-__device__ inline void build_desc(const AttnParams &p, const int32_t *__restrict__ page_table, const int *s_pref,
-                                  const int *s_len, long long lo, int n_iter, int i, TileDesc *slot, int &bad) {
+__device__ inline void build_desc(const AttnParams &p, const int32_t *__restrict__ page_table,
+                                  const int32_t *__restrict__ seq_lens, const int *s_pref, long long lo, int n_iter,
+                                  int i, TileDesc *slot, int &bad) {
     const long long x = lo + i;
     const int b = find_seq(s_pref, p.B, p.Hkv, x);
-    const int L = s_len[b];
+    const int L = clamp_len(p, seq_lens, b);
     const int n_pre = (L + kTile - 1) / kTile, n_units = n_pre + p.n_tree_tiles;
     const int rel = (int)(x - (long long)p.Hkv * s_pref[b]);
     const int hkv = rel / n_units, idx = rel - hkv * n_units;
@@ -225,22 +223,23 @@ __device__ inline void copy16_lane(const void *addr, unsigned lds_base) {
 // Per-lane constants of the tile copy: byte offsets of this lane's 16 bytes inside a
 // (page, head) block of the cache / inside a 64-row slab of the tree tensors, for each copy
 // instruction, with the LDS swizzle already applied to the chunk index.
-template <int D>
+template <int D, int CW>
 struct CopyLane {
-    unsigned k_cache_off[Geometry<D>::kCopies], v_cache_off[Geometry<D>::kCopies];
-    unsigned k_tree_off[Geometry<D>::kCopies], v_tree_off[Geometry<D>::kCopies];
-    int row[Geometry<D>::kCopies];   // tile row this lane copies
+    unsigned k_cache_off[Geometry<D, CW>::kCopies], v_cache_off[Geometry<D, CW>::kCopies];
+    unsigned k_tree_off[Geometry<D, CW>::kCopies], v_tree_off[Geometry<D, CW>::kCopies];
+    int row[Geometry<D, CW>::kCopies];   // tile row this lane copies
 };
 
-template <int D>
-__device__ inline CopyLane<D> make_copy_lane(const AttnParams &p, int wave, int lane) {
-    using G = Geometry<D>;
-    CopyLane<D> cl;
+// cw: index of the copying wavefront (0 .. CW-1)
+template <int D, int CW>
+__device__ inline CopyLane<D, CW> make_copy_lane(const AttnParams &p, int cw, int lane) {
+    using G = Geometry<D, CW>;
+    CopyLane<D, CW> cl;
     const int rin = lane / G::kChunks, pchunk = lane % G::kChunks;   // row inside the copy, physical chunk
     const unsigned tree_row_bytes = (unsigned)p.Hkv * D * 2;
 #pragma unroll
     for (int i = 0; i < G::kCopies; ++i) {
-        const int r = wave * G::kRowsPerWave + i * G::kRowsPerCopy + rin;
+        const int r = cw * G::kRowsPerWave + i * G::kRowsPerCopy + rin;
         const unsigned kc = (unsigned)(pchunk ^ swizzle_k<D>(r)) << 4;
         const unsigned vc = (unsigned)(pchunk ^ swizzle_v<D>(r)) << 4;
         cl.row[i] = r;
@@ -252,22 +251,22 @@ __device__ inline CopyLane<D> make_copy_lane(const AttnParams &p, int wave, int 
     return cl;
 }
 
-// What one wavefront needs to copy its 8 rows of a unit: wave-uniform base addresses and
-// which kind of source it is.  Every wavefront issues exactly 2 * kCopies copy instructions
-// per unit, whatever the tile looks like: rows that do not exist (past the sequence end, past
-// the last tree node, behind an invalid page id) are copied from a block of zeros, so a
-// missing K row scores 0 (and is masked later) and a missing V row contributes nothing.
+// What one copying wavefront needs for its rows of a tile: wave-uniform base addresses and
+// which kind of source it is.  It issues exactly 2 * kCopies copy instructions per tile,
+// whatever the tile looks like: rows that do not exist (past the sequence end, past the last
+// tree node, behind an invalid page id) are copied from a block of zeros, so a missing K row
+// scores 0 (and is masked later) and a missing V row contributes nothing.
 struct CopyPlan {
     const char *kb, *vb;   // base of this wavefront's (page, head) block, or of the tree slab
     int n_valid;           // rows of the tile that exist
-    bool whole;            // all 8 rows of this wavefront exist in the paged cache: uniform fast path
+    bool whole;            // all rows of this wavefront exist in the paged cache: uniform fast path
     bool tree;
     bool page_ok;
 };
 
-template <int D>
-__device__ inline CopyPlan plan_copy(const AttnParams &p, int blk, int n_valid, int flags, int wave_s) {
-    using G = Geometry<D>;
+template <int D, int CW>
+__device__ inline CopyPlan plan_copy(const AttnParams &p, int blk, int n_valid, int flags, int cw) {
+    using G = Geometry<D, CW>;
     CopyPlan cp;
     cp.n_valid = n_valid;
     cp.tree = (flags & kDescTree) != 0;
@@ -276,7 +275,7 @@ __device__ inline CopyPlan plan_copy(const AttnParams &p, int blk, int n_valid, 
         const size_t boff = (size_t)(cp.page_ok ? blk : 0) * (16 * G::kRowBytes);
         cp.kb = reinterpret_cast<const char *>(p.k_cache) + boff;
         cp.vb = reinterpret_cast<const char *>(p.v_cache) + boff;
-        cp.whole = cp.page_ok && (wave_s + 1) * G::kRowsPerWave <= n_valid;
+        cp.whole = cp.page_ok && (cw + 1) * G::kRowsPerWave <= n_valid;
     } else {
         const size_t origin = (size_t)blk * G::kRowBytes;
         cp.kb = reinterpret_cast<const char *>(p.k_tree) + origin;
@@ -286,14 +285,14 @@ __device__ inline CopyPlan plan_copy(const AttnParams &p, int blk, int n_valid, 
     return cp;
 }
 
-// Copy instruction j of the unit (j < kCopies: K rows, else V rows) into the stage at LDS
+// Copy instruction j of the tile (j < kCopies: K rows, else V rows) into the stage at LDS
 // byte address `stage`.
-template <int D>
-__device__ inline void emit_copy(const CopyPlan &cp, const CopyLane<D> &cl, unsigned stage, int wave_s, int j) {
-    using G = Geometry<D>;
+template <int D, int CW>
+__device__ inline void emit_copy(const CopyPlan &cp, const CopyLane<D, CW> &cl, unsigned stage, int cw, int j) {
+    using G = Geometry<D, CW>;
     const bool is_v = j >= G::kCopies;
     const int i = is_v ? j - G::kCopies : j;
-    const unsigned dst = stage + (is_v ? G::kTileBytes : 0) + wave_s * G::kRowsPerWave * G::kRowBytes + i * 1024;
+    const unsigned dst = stage + (is_v ? G::kTileBytes : 0) + cw * G::kRowsPerWave * G::kRowBytes + i * 1024;
     const char *base = is_v ? cp.vb : cp.kb;
     if (cp.whole) {
         copy16_uniform(base, is_v ? cl.v_cache_off[i] : cl.k_cache_off[i], dst);
@@ -329,34 +328,45 @@ __device__ inline s16x4 lds_read_tr16(const char *ptr) {
 
 }  // namespace
 
-// NKB: 32-key blocks of a tile one wavefront works on (1: keys are split between two wave
-// groups; 2: every wavefront takes the whole tile).
-template <int D, int NKB>
-__global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams p,
-                                                                       const int32_t *__restrict__ page_table,
-                                                                       const int32_t *__restrict__ seq_lens) {
-    using G = Geometry<D>;
-    constexpr int kRowBlocks = NKB == 2 ? 8 : 4;
-    constexpr int kRowsPerWG = 32 * kRowBlocks;
-    constexpr int kCopiesPerTile = 2 * G::kCopies;   // per wavefront
+// RB: row blocks of 32 query rows a workgroup carries = wavefronts that compute.
+//   RB = 4 (T*G <= 128): wavefronts 0..3 compute; wavefronts 4..7 only move data: they copy
+//        the tiles, stage the next pair's query rows in LDS, fetch parent pointers and turn
+//        them into ancestor masks, and extend the tile list, all ahead of the computation,
+//        so that a computing wavefront never waits on a memory counter inside the loop.
+//   RB = 8: every wavefront computes and copies its share of each tile.
+template <int D, int RB>
+__global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
+                                                                    const int32_t *__restrict__ page_table,
+                                                                    const int32_t *__restrict__ seq_lens) {
+    constexpr bool kDma = RB == 4;
+    constexpr int CW = kDma ? 4 : 8;
+    using G = Geometry<D, CW>;
+    constexpr int kRowsPerWG = 32 * RB;
+    constexpr int kCopiesPerTile = 2 * G::kCopies;   // per copying wavefront
+    constexpr int kQStageBytes = kDma ? kRowsPerWG * G::kRowBytes : 0;
+    constexpr int kHelpers = kDma ? 256 : kThreads;  // threads that build the tile list and the masks
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     char *ring = smem;                                                               // [kStages][kStageBytes]
-    uint32_t *s_anc = reinterpret_cast<uint32_t *>(smem + kStages * G::kStageBytes); // [READER_MAX_T][4]
-    int *s_par = reinterpret_cast<int *>(s_anc + READER_MAX_T * 4);                  // [READER_MAX_T]
-    float *s_ml = reinterpret_cast<float *>(s_par + READER_MAX_T);                   // key group 1's sums [128][2] then maxima [128]
-    float *s_sink = s_ml + 384;                                                      // [64] landing zone of cache-warming copies
+    char *s_q = smem + kStages * G::kStageBytes;                                     // staged query rows (RB = 4)
+    uint32_t *s_anc = reinterpret_cast<uint32_t *>(s_q + kQStageBytes);              // [2][READER_MAX_T][4]
+    int *s_par = reinterpret_cast<int *>(s_anc + 2 * READER_MAX_T * 4);              // [2][READER_MAX_T]
+    float *s_sink = reinterpret_cast<float *>(s_par + 2 * READER_MAX_T);             // [64] landing zone of cache-warming copies
     int *s_wsum = reinterpret_cast<int *>(s_sink + 64);                              // [8]
     TileDesc *s_desc = reinterpret_cast<TileDesc *>(s_wsum + 8);                     // [kDescSlots]
     int *s_pref = reinterpret_cast<int *>(s_desc + kDescSlots);                      // [B + 1]
-    int *s_len = s_pref + p.B + 1;                                                   // [B]
     const unsigned ring_lds = (unsigned)(size_t)(lds_char *)ring;
+    const unsigned q_lds = (unsigned)(size_t)(lds_char *)s_q;
+    const unsigned par_lds = (unsigned)(size_t)(lds_char *)reinterpret_cast<char *>(s_par);
     const unsigned prefetch_lds = (unsigned)(size_t)(lds_char *)reinterpret_cast<char *>(s_sink);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int rb = NKB == 2 ? wave_s : (wave_s & 3);     // row block of this wavefront
-    const int kg = NKB == 2 ? 0 : (wave_s >> 2);         // key group of this wavefront
+    const bool is_computer = !kDma || wave_s < 4;
+    const bool is_copier = !kDma || wave_s >= 4;
+    const int cw = kDma ? (wave_s & 3) : wave_s;         // index among the copying wavefronts
+    const int rb = kDma ? (wave_s & 3) : wave_s;         // row block of a computing wavefront
+    const int htid = kDma ? tid - 256 : tid;             // index among the helper threads, negative: none
     const int n = lane & 31, h = lane >> 5;
     const int chunk_base = blockIdx.y * kRowsPerWG;
     const int row_local = rb * 32 + n;             // row inside this workgroup's chunk
@@ -364,30 +374,23 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     const bool row_real = m_row < p.M;
     const int node = row_real ? m_row / p.G : 0;   // tree node of this lane's query row
     const int group = row_real ? m_row - node * p.G : 0;
-    const bool wave_active = chunk_base + rb * 32 < p.M;
+    const bool wave_active = is_computer && chunk_base + rb * 32 < p.M;
 
-    // Tiles per sequence (prefix sums) and clamped lengths go to LDS.  With at most 64 sequences
-    // every wavefront scans on its own and all of them write the same values, so a wavefront
-    // may read them back without a barrier (its own LDS accesses execute in order).
+    // Tiles per sequence as prefix sums in LDS.  With at most 64 sequences every wavefront
+    // scans on its own and all of them write the same values, so a wavefront may read them
+    // back without a barrier (its own LDS accesses execute in order).
     if (p.B <= 64) {
-        int L = 0, v = 0;
-        if (lane < p.B) {
-            L = clamp_len(p, seq_lens, lane);
-            v = (L + kTile - 1) / kTile + p.n_tree_tiles;
-        }
-        int incl = v;
+        int v = 0;
+        if (lane < p.B) v = (clamp_len(p, seq_lens, lane) + kTile - 1) / kTile + p.n_tree_tiles;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            const int t = __shfl_up(incl, off);
-            if (lane >= off) incl += t;
+            const int t = __shfl_up(v, off);
+            if (lane >= off) v += t;
         }
-        if (lane < p.B) {
-            s_pref[lane + 1] = incl;
-            s_len[lane] = L;
-        }
+        if (lane < p.B) s_pref[lane + 1] = v;
         if (lane == 0) s_pref[0] = 0;
     } else {
-        scan_units(p, seq_lens, s_pref, s_wsum, s_len);
+        scan_units(p, seq_lens, s_pref, s_wsum);
     }
     const long long U = (long long)p.Hkv * __builtin_amdgcn_readfirstlane(s_pref[p.B]);
     const long long lo = range_begin(blockIdx.x, U, p.n_ranges);
@@ -396,8 +399,16 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     const int n_iter = (int)(hi - lo);
 
     int bad = 0;
-    for (int i = tid; i < min(n_iter, kDescSlots); i += kThreads)
-        build_desc(p, page_table, s_pref, s_len, lo, n_iter, i, s_desc + i, bad);
+    if (htid >= 0)
+        for (int i = htid; i < min(n_iter, kDescSlots); i += kHelpers)
+            build_desc(p, page_table, seq_lens, s_pref, lo, n_iter, i, s_desc + i, bad);
+    __syncthreads();   // the tile list is written
+
+    auto desc_of = [&](int i) -> const TileDesc * { return s_desc + (i & (kDescSlots - 1)); };
+    auto desc_b = [&](int i) { return __builtin_amdgcn_readfirstlane(desc_of(i)->b); };
+    auto desc_hkv = [&](int i) { return __builtin_amdgcn_readfirstlane(desc_of(i)->hkv); };
+    auto desc_flags = [&](int i) { return __builtin_amdgcn_readfirstlane(desc_of(i)->flags); };
+    constexpr int kQuarterShift = kDma ? 0 : 1;   // copying wavefront -> 16-key quarter of the tile
 
     // This lane's query row as the B operand of the QK product.
     bf16x8 qf[G::kKSteps];
@@ -407,48 +418,115 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         for (int kk = 0; kk < G::kKSteps; ++kk)
             qf[kk] = __builtin_bit_cast(bf16x8, keep_if(row_real, ld16(qrow + kk * 16 + h * 8)));
     };
-    // Touch the next pair's query rows one tile before they are needed, so that they wait in
-    // the cache: an LDS copy of 4 bytes per lane into a scratch area nobody reads (a plain load
-    // would need a destination register that stays reserved until the data arrives).
+    // RB = 8: touch the next pair's query rows one tile before they are needed, so that they
+    // wait in the cache: an LDS copy of 4 bytes per lane into a scratch area nobody reads.
     auto prefetch_q = [&](int b, int hkv) {
         const uint16_t *qrow = p.q + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D;
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off"
                      :: "v"(qrow + (h * 64) % D), "s"(prefetch_lds) : "memory", "m0");
     };
-
-    const CopyLane<D> cl = make_copy_lane<D>(p, wave_s, lane);
-    __syncthreads();   // the tile list is written
-
-    // Descriptor words a wavefront needs of a tile: for computing it (rows, flags) and for
-    // copying it (this wavefront's quarter).  Uniform values, moved to scalar registers.
-    auto desc_of = [&](int i) -> const TileDesc * { return s_desc + (i & (kDescSlots - 1)); };
-    auto issue_tile = [&](int i, unsigned stage_lds) {
-        const TileDesc *d = desc_of(i);
-        const int blk = __builtin_amdgcn_readfirstlane(d->blk[wave_s >> 1]);
-        const int nv = __builtin_amdgcn_readfirstlane(d->n_valid);
-        const int fl = __builtin_amdgcn_readfirstlane(d->flags);
-        const CopyPlan cp = plan_copy<D>(p, blk, nv, fl, wave_s);
+    // RB = 4: the copying wavefronts stage a pair's query rows in LDS (rows swizzled like a K
+    // tile) two tiles before the pair starts; the computing wavefronts read their fragments
+    // from there.  Only done when the previous pair started at least three tiles earlier, so
+    // that the single buffer is never rewritten while it is read; otherwise rows are loaded
+    // straight from memory.
+    auto stage_q = [&](int b, int hkv) {
+        constexpr int kQCopies = kQStageBytes / 1024 / CW;
+        const char *qbase = reinterpret_cast<const char *>(p.q) + ((size_t)b * p.T * p.Hq + hkv * p.G) * (D * 2);
+        const char *zeros = reinterpret_cast<const char *>(kZeroRow) + (lane & 15) * 16;
 #pragma unroll
-        for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D>(cp, cl, stage_lds, wave_s, j);
+        for (int i = 0; i < kQCopies; ++i) {
+            const int r = (cw * kQCopies + i) * G::kRowsPerCopy + lane / G::kChunks;
+            const int c = (lane % G::kChunks) ^ swizzle_k<D>(r);
+            const int nd = r / p.G, gr = r - nd * p.G;
+            const char *src = r < p.M ? qbase + ((size_t)nd * p.Hq + gr) * (D * 2) + c * 16 : zeros;
+            copy16_lane(src, q_lds + (cw * kQCopies + i) * 1024);
+        }
     };
-    // prologue: the first segment's query rows, then tiles 0 and 1
-    load_q(__builtin_amdgcn_readfirstlane(s_desc[0].b), __builtin_amdgcn_readfirstlane(s_desc[0].hkv));
-    issue_tile(0, ring_lds);
-    if (n_iter > 1) issue_tile(1, ring_lds + G::kStageBytes);
+    auto read_q_stage = [&]() {
+#pragma unroll
+        for (int kk = 0; kk < G::kKSteps; ++kk)
+            qf[kk] = *reinterpret_cast<const bf16x8 *>(s_q + row_local * G::kRowBytes +
+                                                       (((2 * kk + h) ^ swizzle_k<D>(row_local)) << 4));
+    };
+
+    // Parent pointers of a sequence into s_par[buf] (asynchronous, copying wavefronts 0 and 1),
+    // and from there the ancestor-or-self masks into s_anc[buf] (helper threads).
+    auto copy_parents = [&](int b, int buf) {
+        if (cw * 64 < p.T) {
+            const int t = min(cw * 64 + lane, p.T - 1);
+            const int32_t *src = p.parents + (size_t)b * p.T + t;
+            const unsigned dst = par_lds + (buf * READER_MAX_T + cw * 64) * 4;
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" :: "v"(src), "s"(dst) : "memory", "m0");
+        }
+    };
+    auto build_masks = [&](int buf) {
+        if (htid >= 0 && htid < p.T) {
+            const int *par = s_par + buf * READER_MAX_T;
+            uint32_t a0 = 0u, a1 = 0u, a2 = 0u, a3 = 0u;
+            int t = htid;
+            for (int step = 0; step < p.T && t >= 0; ++step) {
+                const uint32_t bit = 1u << (t & 31);
+                const int w = t >> 5;
+                a0 |= w == 0 ? bit : 0u; a1 |= w == 1 ? bit : 0u;
+                a2 |= w == 2 ? bit : 0u; a3 |= w == 3 ? bit : 0u;
+                int pi = par[t];
+                const bool valid = t == 0 ? pi == -1 : (pi >= 0 && pi < t);
+                if (!valid) { bad |= READER_STATUS_BAD_TREE; pi = -1; }
+                t = pi;
+            }
+            uint32_t *dst = s_anc + (buf * READER_MAX_T + htid) * 4;
+            dst[0] = a0; dst[1] = a1; dst[2] = a2; dst[3] = a3;
+        }
+    };
+
+    const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
+    auto issue_tile = [&](int blk, int nv, int fl, unsigned stage_lds) {
+        const CopyPlan cp = plan_copy<D, CW>(p, blk, nv, fl, cw);
+#pragma unroll
+        for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D, CW>(cp, cl, stage_lds, cw, j);
+    };
+    auto issue_tile_at = [&](int i, unsigned stage_lds) {
+        const TileDesc *d = desc_of(i);
+        issue_tile(__builtin_amdgcn_readfirstlane(d->blk[cw >> kQuarterShift]),
+                   __builtin_amdgcn_readfirstlane(d->n_valid), __builtin_amdgcn_readfirstlane(d->flags), stage_lds);
+    };
+
+    // Which mask buffer a segment uses: segments that need masks alternate between the two
+    // buffers; the parent copies, the mask builds and the computation each count them.
+    int gen_cpy = 0, gen_bld = 0, gen_use = 0;
+    int prev_fresh_c = 0, prev_fresh_u = 0;   // last segment start seen by the copies / by the computation
+    const uint32_t *anc = s_anc;
+
+    // prologue: tiles 0 and 1 (with the parent pointers their segments need), the first query rows
+    if (is_copier) {
+        const int f0 = desc_flags(0);
+        if (kDma && (f0 & kDescMasks)) { copy_parents(desc_b(0), 0); gen_cpy = 1; }
+        issue_tile_at(0, ring_lds);
+        if (n_iter > 1) {
+            const int f1 = desc_flags(1);
+            if (kDma && (f1 & kDescFresh)) {
+                if (f1 & kDescMasks) { copy_parents(desc_b(1), gen_cpy & 1); ++gen_cpy; }
+                prev_fresh_c = 1;
+            }
+            issue_tile_at(1, ring_lds + G::kStageBytes);
+        }
+    }
+    if (is_computer) load_q(desc_b(0), desc_hkv(0));
 
     // per-lane LDS offsets of the matrix-core operand reads (relative to the stage)
-    int k_rd[G::kKSteps];   // K fragment of k-step kk, first key block of this wavefront
+    int k_rd[G::kKSteps];   // K fragment of k-step kk, key block 0
 #pragma unroll
     for (int kk = 0; kk < G::kKSteps; ++kk)
-        k_rd[kk] = (kg * 32 + n) * G::kRowBytes + (((2 * kk + h) ^ swizzle_k<D>(n)) << 4);
-    int v_rd[G::kOBlocks];  // V fragment of output block db, keys 0..3 (+4h) of this wavefront's first 16-key group
+        k_rd[kk] = n * G::kRowBytes + (((2 * kk + h) ^ swizzle_k<D>(n)) << 4);
+    int v_rd[G::kOBlocks];  // V fragment of output block db, keys 0..3 (+4h) of the first 16-key group
     {
         const int i16 = lane & 15, g16 = (lane >> 4) & 1;
         const int key_lo = 4 * h + (i16 >> 2);                       // key row inside an 8-key group
         const int c_lo = 2 * g16 + ((i16 & 3) >> 1);                 // 16-byte chunk inside the 32-wide d block
 #pragma unroll
         for (int db = 0; db < G::kOBlocks; ++db)
-            v_rd[db] = G::kTileBytes + (kg * 32 + key_lo) * G::kRowBytes +
+            v_rd[db] = G::kTileBytes + key_lo * G::kRowBytes +
                        ((((db * 4) | c_lo) ^ swizzle_v<D>(key_lo)) << 4) + (i16 & 1) * 8;
     }
 
@@ -457,24 +535,24 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
     bool seg_from_pair_start = false;
     const float c2 = p.scale_log2;
 
-    uint32_t pk[NKB][8];   // softmax weights of the current tile, bf16 pairs, in B-operand order
+    uint32_t pk[2][8];     // softmax weights of the current tile, bf16 pairs, in B-operand order
     // The running reference m_run is only raised when a row's maximum outgrows it by more
     // than 2^8 (in the exp2 domain), so the accumulator rescale is rare; weights stay <= 256.
     const float grow_margin = 8.f / c2;
 
-    f32x16 s[NKB];         // S^T of the current tile
-    // S^T = K . Q^T for this wavefront's key block(s)
+    f32x16 s[2];           // S^T of the current tile, one per 32-key block
+    // S^T = K . Q^T
     auto qk_product = [&](const char *stage) {
-        // All fragment reads of a block are issued before its first matrix instruction,
-        // and a second block's reads are interleaved with the first block's products.
-        bf16x8 ka[NKB][G::kKSteps];
+        // All fragment reads of block 0 are issued before its first matrix instruction, and
+        // block 1's reads are interleaved with block 0's products.
+        bf16x8 ka[2][G::kKSteps];
 #pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int kk = 0; kk < G::kKSteps; ++kk)
                 ka[kb][kk] = *reinterpret_cast<const bf16x8 *>(stage + k_rd[kk] + kb * 32 * G::kRowBytes);
 #pragma unroll
-        for (int kb = 0; kb < NKB; ++kb) {
+        for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
 #pragma unroll
@@ -483,22 +561,20 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         }
         // instruction order handed to the scheduler: it serialises read/product pairs otherwise
         __builtin_amdgcn_sched_group_barrier(0x100, G::kKSteps, 0);          // LDS reads of block 0
-        if (NKB == 2) {
 #pragma unroll
-            for (int kk = 0; kk < G::kKSteps; ++kk) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           // one product of block 0
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // one read of block 1
-            }
+        for (int kk = 0; kk < G::kKSteps; ++kk) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one product of block 0
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one read of block 1
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);          // products of the last block
+        __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);          // products of block 1
     };
 
     // masks (ragged last prefix tile, tree tiles), row maximum, rare accumulator rescale
     auto softmax_max = [&](bool is_tree, int tt, int n_valid) {
         if (is_tree) {
 #pragma unroll
-            for (int kb = 0; kb < NKB; ++kb) {
-                uint32_t bits = row_real ? s_anc[node * 4 + tt * 2 + kg + kb] : 0u;
+            for (int kb = 0; kb < 2; ++kb) {
+                uint32_t bits = row_real ? anc[node * 4 + tt * 2 + kb] : 0u;
                 bits >>= 4 * h;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
@@ -508,17 +584,17 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
             }
         } else if (n_valid < kTile) {
 #pragma unroll
-            for (int kb = 0; kb < NKB; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int key = (kg + kb) * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
+                    const int key = kb * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
                     if (key >= n_valid) s[kb][i] = -INFINITY;
                 }
         }
         // ---- online softmax along the keys (all values of a lane share one query row) ----
         float mx = s[0][0];
 #pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
@@ -539,7 +615,7 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
         float lsum = 0.f;
 #pragma unroll
-        for (int kb = 0; kb < NKB; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int i = 0; i < 16; i += 2) {
                 const float p0 = __builtin_amdgcn_exp2f(s[kb][i] * c2 - mc);
@@ -568,8 +644,8 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         bf16x8 va[2][G::kOBlocks];
         read_step(0, va[0]);
 #pragma unroll
-        for (int ks = 0; ks < 2 * NKB; ++ks) {
-            if (ks + 1 < 2 * NKB) read_step(ks + 1, va[(ks + 1) & 1]);
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks + 1 < 4) read_step(ks + 1, va[(ks + 1) & 1]);
             const int kb = ks >> 1, m2 = ks & 1;
             u32x4 pv;
             pv.x = pk[kb][4 * m2]; pv.y = pk[kb][4 * m2 + 1]; pv.z = pk[kb][4 * m2 + 2]; pv.w = pk[kb][4 * m2 + 3];
@@ -580,192 +656,209 @@ __global__ __launch_bounds__(kThreads, 2) void tree_attn_mfma_kernel(AttnParams 
         }
     };
 
-    // LDS byte offsets of the ring stages: tile being computed, next tile, tile being copied
-    int st_cur = 0, st_nxt = G::kStageBytes, st_cpy = 2 * G::kStageBytes;
-    // descriptor words of the tile to compute (rows, flags) and of the tile to copy, read one
-    // iteration ahead so that the LDS latency hides behind the barrier
-    int2 d_cur = *reinterpret_cast<const int2 *>(&desc_of(0)->n_valid);
-    int2 d_cpy = *reinterpret_cast<const int2 *>(&desc_of(2)->n_valid);
-    int d_blk = desc_of(2)->blk[wave_s >> 1];
+    auto reset_state = [&](int flags) {
+        seg_from_pair_start = (flags & kDescPairStart) != 0;
+        m_run = -INFINITY;
+        l_run = 0.f;
+#pragma unroll
+        for (int db = 0; db < G::kOBlocks; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+    };
 
-    for (int it = 0; it < n_iter; ++it) {
-        const char *stage = ring + st_cur;
-        const int t_valid = __builtin_amdgcn_readfirstlane(d_cur.x);
-        const int t_flags = __builtin_amdgcn_readfirstlane(d_cur.y);
-        const int c_valid = __builtin_amdgcn_readfirstlane(d_cpy.x);
-        const int c_flags = __builtin_amdgcn_readfirstlane(d_cpy.y);
-        const int c_blk = __builtin_amdgcn_readfirstlane(d_blk);
-        const bool last_iter = it + 1 == n_iter;
-        const bool copy_next = it + 2 < n_iter;
-
-        // This wavefront's part of tile `it` has landed once at most the copies of tile
-        // it + 1 are outstanding (copies complete in the order they were issued).
-        if (!last_iter) wait_vmcnt<kCopiesPerTile>(); else wait_vmcnt<0>();
-        __syncthreads();   // tile `it` is complete in LDS; every wavefront is done with tile it - 1
-
-        // next iteration's descriptor words
-        d_cur = *reinterpret_cast<const int2 *>(&desc_of(it + 1)->n_valid);
-        d_cpy = *reinterpret_cast<const int2 *>(&desc_of(it + 3)->n_valid);
-        d_blk = desc_of(it + 3)->blk[wave_s >> 1];
-
-        // The tile list is extended half a list at a time, by the first two wavefronts, while
-        // the half it replaces is no longer read and long before the new half is.
-        if ((it & (kDescSlots / 2 - 1)) == 0 && it > 0 && tid < kDescSlots / 2) {
-            const int i = it + kDescSlots / 2 + tid;
-            if (i < n_iter) build_desc(p, page_table, s_pref, s_len, lo, n_iter, i, s_desc + (i & (kDescSlots - 1)), bad);
-        }
-
-        if (t_flags & kDescFresh) {
-            seg_from_pair_start = (t_flags & kDescPairStart) != 0;
-            m_run = -INFINITY;
-            l_run = 0.f;
+    // End of a segment (its pair ends, or the range does): a pair that this workgroup saw
+    // from its first to its last tile is normalised and written out, anything else leaves
+    // a partial record for the merge kernel.
+    auto finish_segment = [&](int it, bool pair_ends) {
+        const int e_b = desc_b(it), e_hkv = desc_hkv(it);
+        const float l_tot = l_run + __shfl_xor(l_run, 32);
+        if (seg_from_pair_start && pair_ends) {
+            if (row_real) {
+                const float inv = 1.f / l_tot;
+                uint16_t *orow = p.out + (((size_t)e_b * p.T + node) * p.Hq + e_hkv * p.G + group) * D;
+#pragma unroll
+                for (int db = 0; db < G::kOBlocks; ++db)
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        uint2 w;
+                        w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
+                        w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
+                        *reinterpret_cast<uint2 *>(orow + db * 32 + i4 * 8 + 4 * h) = w;
+                    }
+                if (p.lse && h == 0)
+                    p.lse[((size_t)e_b * p.Hq + e_hkv * p.G + group) * p.T + node] =
+                        (m_run * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
+            }
+        } else {
+            const size_t slot = ((size_t)(2 * blockIdx.x + (seg_from_pair_start ? 1 : 0)) * p.n_row_chunks + blockIdx.y);
+            float *rec = p.workspace + slot * attn_slot_floats(D, kRowsPerWG);
+            float *orow = rec + (size_t)row_local * D;
 #pragma unroll
             for (int db = 0; db < G::kOBlocks; ++db)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-            const int sb = __builtin_amdgcn_readfirstlane(desc_of(it)->b);
-            if (it != 0) load_q(sb, __builtin_amdgcn_readfirstlane(desc_of(it)->hkv));
-            // ancestor-or-self masks of this sequence's tree, if this segment reaches its tree tiles
-            if (t_flags & kDescMasks) {
-                if (tid < p.T) {
-                    int pi = p.parents[(size_t)sb * p.T + tid];
-                    const bool valid = tid == 0 ? pi == -1 : (pi >= 0 && pi < tid);
-                    if (!valid) { bad |= READER_STATUS_BAD_TREE; pi = -1; }
-                    s_par[tid] = pi;
-                }
-                __syncthreads();
-                if (tid < p.T) {
-                    uint32_t a0 = 0u, a1 = 0u, a2 = 0u, a3 = 0u;
-                    int t = tid;
-                    for (int step = 0; step < p.T && t >= 0; ++step) {
-                        const uint32_t bit = 1u << (t & 31);
-                        const int w = t >> 5;
-                        a0 |= w == 0 ? bit : 0u; a1 |= w == 1 ? bit : 0u;
-                        a2 |= w == 2 ? bit : 0u; a3 |= w == 3 ? bit : 0u;
-                        t = s_par[t];
-                    }
-                    s_anc[tid * 4 + 0] = a0; s_anc[tid * 4 + 1] = a1;
-                    s_anc[tid * 4 + 2] = a2; s_anc[tid * 4 + 3] = a3;
-                }
-                __syncthreads();
+                for (int i4 = 0; i4 < 4; ++i4)
+                    *reinterpret_cast<float4 *>(orow + db * 32 + i4 * 8 + 4 * h) =
+                        make_float4(o[db][4 * i4], o[db][4 * i4 + 1], o[db][4 * i4 + 2], o[db][4 * i4 + 3]);
+            if (h == 0) {
+                rec[(size_t)kRowsPerWG * D + row_local] = m_run * c2;
+                rec[(size_t)kRowsPerWG * (D + 1) + row_local] = l_tot;
             }
         }
+    };
 
-        const bool pair_ends = (t_flags & kDescPairEnd) != 0;
-        if (pair_ends && !last_iter) {
-            const TileDesc *dn = desc_of(it + 1);
-            prefetch_q(__builtin_amdgcn_readfirstlane(dn->b), __builtin_amdgcn_readfirstlane(dn->hkv));
+    // The tile list is extended half a list at a time while the half it replaces is no
+    // longer read and long before the new half is.
+    auto extend_list = [&](int it) {
+        if ((it & (kDescSlots / 2 - 1)) == 0 && it > 0 && htid >= 0 && htid < kDescSlots / 2) {
+            const int i = it + kDescSlots / 2 + htid;
+            if (i < n_iter) build_desc(p, page_table, seq_lens, s_pref, lo, n_iter, i, s_desc + (i & (kDescSlots - 1)), bad);
         }
+    };
 
-        // Tile it + 2 is copied into the stage that tile it - 1 has left.  A wavefront stalls on
-        // a copy instruction while the memory pipeline is full, so the copies are spread over
-        // the iteration, each behind a batch of matrix or vector work.
-        const unsigned next_stage = ring_lds + st_cpy;
-        CopyPlan cp;
-        if (copy_next) cp = plan_copy<D>(p, c_blk, c_valid, c_flags, wave_s);
-        auto copy_part = [&](int part) {   // part 0..3
-            if (copy_next) {
-                if (kCopiesPerTile == 4) emit_copy<D>(cp, cl, next_stage, wave_s, part);
-                else if ((part & 1) == 0) emit_copy<D>(cp, cl, next_stage, wave_s, part >> 1);
+    // LDS byte offsets of the ring stages: tile being computed, next tile, tile being copied
+    int st_cur = 0, st_nxt = G::kStageBytes, st_cpy = 2 * G::kStageBytes;
+    auto rotate_stages = [&]() {
+        const int t = st_cur;
+        st_cur = st_nxt; st_nxt = st_cpy; st_cpy = t;
+    };
+
+    if (kDma && is_copier) {
+        // ---------------- wavefronts that only move data (RB = 4) ----------------
+        // descriptor words of the tile to copy, read one iteration ahead
+        int2 d_cpy = *reinterpret_cast<const int2 *>(&desc_of(2)->n_valid);
+        int d_blk = desc_of(2)->blk[cw >> kQuarterShift];
+        int n_flags = desc_flags(0);   // flags of tile it, then of tile it + 1
+        for (int it = 0; it < n_iter; ++it) {
+            const int c_valid = __builtin_amdgcn_readfirstlane(d_cpy.x);
+            const int c_flags = __builtin_amdgcn_readfirstlane(d_cpy.y);
+            const int c_blk = __builtin_amdgcn_readfirstlane(d_blk);
+            const int t_flags = n_flags;
+            const bool last_iter = it + 1 == n_iter;
+            // This wavefront's part of tile `it` has landed once at most its copies of tile
+            // it + 1 are outstanding (copies complete in the order they were issued).
+            if (!last_iter) wait_vmcnt<kCopiesPerTile>(); else wait_vmcnt<0>();
+            __syncthreads();   // tile `it` is complete in LDS; every wavefront is done with tile it - 1
+
+            d_cpy = *reinterpret_cast<const int2 *>(&desc_of(it + 3)->n_valid);
+            d_blk = desc_of(it + 3)->blk[cw >> kQuarterShift];
+            n_flags = desc_flags(it + 1);
+            extend_list(it);
+
+            // masks of the first segment, and of a segment that starts with the next tile (their
+            // parent pointers were asked for before the copies this wavefront has just waited for)
+            if (it == 0 && (t_flags & kDescMasks)) { build_masks(0); gen_bld = 1; }
+            if (!last_iter && (n_flags & kDescMasks)) { build_masks(gen_bld & 1); ++gen_bld; }
+            // only a range that starts inside a tree needs the first masks at once
+            if (it == 0 && (t_flags & kDescMasks) && (t_flags & kDescTree)) __syncthreads();
+
+            if (it + 2 < n_iter) {
+                if (c_flags & kDescFresh) {
+                    const int x = it + 2, xb = desc_b(x);
+                    if (c_flags & kDescMasks) { copy_parents(xb, gen_cpy & 1); ++gen_cpy; }
+                    if (x - prev_fresh_c >= 3) stage_q(xb, desc_hkv(x));
+                    prev_fresh_c = x;
+                }
+                issue_tile(c_blk, c_valid, c_flags, ring_lds + st_cpy);
             }
-        };
-        if (wave_active) {
-            qk_product(stage);
-            copy_part(0);
-            softmax_max((t_flags & kDescTree) != 0, t_flags >> 8, t_valid);
-            copy_part(1);
-            softmax_exp();
-            copy_part(2);
-            pv_product(stage);
-            copy_part(3);
-        } else {
-            copy_part(0); copy_part(1); copy_part(2); copy_part(3);
+            rotate_stages();
         }
-        {
-            const int t = st_cur;
-            st_cur = st_nxt; st_nxt = st_cpy; st_cpy = t;
-        }
+    } else if (kDma) {
+        // ---------------- wavefronts that only compute (RB = 4) ----------------
+        int2 d_cur = *reinterpret_cast<const int2 *>(&desc_of(0)->n_valid);
+        for (int it = 0; it < n_iter; ++it) {
+            const char *stage = ring + st_cur;
+            const int t_valid = __builtin_amdgcn_readfirstlane(d_cur.x);
+            const int t_flags = __builtin_amdgcn_readfirstlane(d_cur.y);
+            const bool last_iter = it + 1 == n_iter;
+            const bool pair_ends = (t_flags & kDescPairEnd) != 0;
+            __syncthreads();   // tile `it` is complete in LDS
+            d_cur = *reinterpret_cast<const int2 *>(&desc_of(it + 1)->n_valid);
+            if (it == 0 && (t_flags & kDescMasks) && (t_flags & kDescTree)) __syncthreads();
 
-        // ---- end of a segment: this pair ends here, or the range does ----
-        if (pair_ends || last_iter) {
-            const int e_b = __builtin_amdgcn_readfirstlane(desc_of(it)->b);
-            const int e_hkv = __builtin_amdgcn_readfirstlane(desc_of(it)->hkv);
-            if (NKB == 1) {
-                // Key group 1 hands its state to key group 0 of the same row block through the
-                // stage that has just been consumed, half of the output blocks at a time.
-                float *xbuf = reinterpret_cast<float *>(const_cast<char *>(stage)) + (size_t)rb * (G::kOBlocks / 2) * 16 * 64;
-                float m1 = 0.f, a0 = 1.f, a1 = 0.f;
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    __syncthreads();   // stage free (first pass) / previous half consumed
-                    if (kg == 1 && wave_active) {
-#pragma unroll
-                        for (int d2 = 0; d2 < G::kOBlocks / 2; ++d2)
-#pragma unroll
-                            for (int i = 0; i < 16; ++i)
-                                xbuf[(d2 * 16 + i) * 64 + lane] = o[half * (G::kOBlocks / 2) + d2][i];
-                        if (half == 0) {
-                            s_ml[row_local * 2 + h] = l_run;          // each lane half holds a partial sum
-                            if (h == 0) s_ml[256 + row_local] = m_run;
-                        }
-                    }
+            if (t_flags & kDescFresh) {
+                reset_state(t_flags);
+                if (it != 0) {
+                    if (it - prev_fresh_u >= 3) read_q_stage();
+                    else load_q(desc_b(it), desc_hkv(it));
+                }
+                prev_fresh_u = it;
+                if (t_flags & kDescMasks) { anc = s_anc + (gen_use & 1) * READER_MAX_T * 4; ++gen_use; }
+            }
+            if (wave_active) {
+                qk_product(stage);
+                softmax_max((t_flags & kDescTree) != 0, t_flags >> 8, t_valid);
+                softmax_exp();
+                pv_product(stage);
+                if (pair_ends || last_iter) finish_segment(it, pair_ends);
+            }
+            rotate_stages();
+        }
+    } else {
+        // ---------------- every wavefront computes and copies (RB = 8) ----------------
+        // descriptor words of the tile to compute (rows, flags) and of the tile to copy, read one
+        // iteration ahead so that the LDS latency hides behind the barrier
+        int2 d_cur = *reinterpret_cast<const int2 *>(&desc_of(0)->n_valid);
+        int2 d_cpy = *reinterpret_cast<const int2 *>(&desc_of(2)->n_valid);
+        int d_blk = desc_of(2)->blk[cw >> kQuarterShift];
+        for (int it = 0; it < n_iter; ++it) {
+            const char *stage = ring + st_cur;
+            const int t_valid = __builtin_amdgcn_readfirstlane(d_cur.x);
+            const int t_flags = __builtin_amdgcn_readfirstlane(d_cur.y);
+            const int c_valid = __builtin_amdgcn_readfirstlane(d_cpy.x);
+            const int c_flags = __builtin_amdgcn_readfirstlane(d_cpy.y);
+            const int c_blk = __builtin_amdgcn_readfirstlane(d_blk);
+            const bool last_iter = it + 1 == n_iter;
+            const bool copy_next = it + 2 < n_iter;
+            const bool pair_ends = (t_flags & kDescPairEnd) != 0;
+            const unsigned next_stage = ring_lds + st_cpy;
+
+            if (!last_iter) wait_vmcnt<kCopiesPerTile>(); else wait_vmcnt<0>();
+            __syncthreads();   // tile `it` is complete in LDS; every wavefront is done with tile it - 1
+
+            d_cur = *reinterpret_cast<const int2 *>(&desc_of(it + 1)->n_valid);
+            d_cpy = *reinterpret_cast<const int2 *>(&desc_of(it + 3)->n_valid);
+            d_blk = desc_of(it + 3)->blk[cw >> kQuarterShift];
+            extend_list(it);
+
+            if (t_flags & kDescFresh) {
+                reset_state(t_flags);
+                const int sb = desc_b(it);
+                if (it != 0) load_q(sb, desc_hkv(it));
+                // ancestor-or-self masks of this sequence's tree, if this segment reaches its tree tiles
+                if (t_flags & kDescMasks) {
+                    if (tid < p.T) s_par[tid] = p.parents[(size_t)sb * p.T + tid];
                     __syncthreads();
-                    if (kg == 0 && wave_active) {
-                        if (half == 0) {
-                            m1 = s_ml[256 + row_local];
-                            const float l1 = s_ml[row_local * 2 + h];
-                            const float m_new = fmaxf(m_run, m1);
-                            const float m_eff = (m_new == -INFINITY) ? 0.f : m_new;
-                            a0 = __builtin_amdgcn_exp2f((m_run - m_eff) * c2);
-                            a1 = __builtin_amdgcn_exp2f((m1 - m_eff) * c2);
-                            l_run = l_run * a0 + l1 * a1;
-                            m_run = m_new;
-                        }
-#pragma unroll
-                        for (int d2 = 0; d2 < G::kOBlocks / 2; ++d2)
-#pragma unroll
-                            for (int i = 0; i < 16; ++i) {
-                                const int db = half * (G::kOBlocks / 2) + d2;
-                                o[db][i] = o[db][i] * a0 + xbuf[(d2 * 16 + i) * 64 + lane] * a1;
-                            }
-                    }
+                    build_masks(0);
+                    __syncthreads();
                 }
             }
-            if (wave_active && kg == 0) {
-                const float l_tot = l_run + __shfl_xor(l_run, 32);
-                if (seg_from_pair_start && pair_ends) {
-                    if (row_real) {
-                        const float inv = 1.f / l_tot;
-                        uint16_t *orow = p.out + (((size_t)e_b * p.T + node) * p.Hq + e_hkv * p.G + group) * D;
-#pragma unroll
-                        for (int db = 0; db < G::kOBlocks; ++db)
-#pragma unroll
-                            for (int i4 = 0; i4 < 4; ++i4) {
-                                uint2 w;
-                                w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
-                                w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
-                                *reinterpret_cast<uint2 *>(orow + db * 32 + i4 * 8 + 4 * h) = w;
-                            }
-                        if (p.lse && h == 0)
-                            p.lse[((size_t)e_b * p.Hq + e_hkv * p.G + group) * p.T + node] =
-                                (m_run * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
-                    }
-                } else {
-                    const size_t slot = ((size_t)(2 * blockIdx.x + (seg_from_pair_start ? 1 : 0)) * p.n_row_chunks + blockIdx.y);
-                    float *rec = p.workspace + slot * attn_slot_floats(D, kRowsPerWG);
-                    float *orow = rec + (size_t)row_local * D;
-#pragma unroll
-                    for (int db = 0; db < G::kOBlocks; ++db)
-#pragma unroll
-                        for (int i4 = 0; i4 < 4; ++i4)
-                            *reinterpret_cast<float4 *>(orow + db * 32 + i4 * 8 + 4 * h) =
-                                make_float4(o[db][4 * i4], o[db][4 * i4 + 1], o[db][4 * i4 + 2], o[db][4 * i4 + 3]);
-                    if (h == 0) {
-                        rec[(size_t)kRowsPerWG * D + row_local] = m_run * c2;
-                        rec[(size_t)kRowsPerWG * (D + 1) + row_local] = l_tot;
-                    }
+            if (pair_ends && !last_iter) prefetch_q(desc_b(it + 1), desc_hkv(it + 1));
+
+            // Tile it + 2 is copied into the stage that tile it - 1 has left.  A wavefront stalls on
+            // a copy instruction while the memory pipeline is full, so the copies are spread over
+            // the iteration, each behind a batch of matrix or vector work.
+            CopyPlan cp;
+            if (copy_next) cp = plan_copy<D, CW>(p, c_blk, c_valid, c_flags, cw);
+            auto copy_part = [&](int part) {   // part 0..3
+                if (copy_next) {
+                    if (kCopiesPerTile == 4) emit_copy<D, CW>(cp, cl, next_stage, cw, part);
+                    else if ((part & 1) == 0) emit_copy<D, CW>(cp, cl, next_stage, cw, part >> 1);
                 }
+            };
+            if (wave_active) {
+                qk_product(stage);
+                copy_part(0);
+                softmax_max((t_flags & kDescTree) != 0, t_flags >> 8, t_valid);
+                copy_part(1);
+                softmax_exp();
+                copy_part(2);
+                pv_product(stage);
+                copy_part(3);
+                if (pair_ends || last_iter) finish_segment(it, pair_ends);
+            } else {
+                copy_part(0); copy_part(1); copy_part(2); copy_part(3);
             }
+            rotate_stages();
         }
     }
 
@@ -847,24 +940,24 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnParams p, cons
         p.lse[((size_t)b * p.Hq + hkv * p.G + group) * p.T + node] = (m_all + __builtin_amdgcn_logf(l_all)) * kLn2;
 }
 
-template <int D, int NKB>
+template <int D, int RB>
 static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
-    using G = Geometry<D>;
+    using G = Geometry<D, RB == 4 ? 4 : 8>;
     const size_t pref_bytes = ((size_t)(p.B + 1) * sizeof(int) + 15) & ~(size_t)15;
-    const size_t main_lds = (size_t)kStages * G::kStageBytes + READER_MAX_T * 4 * sizeof(uint32_t) +
-                            READER_MAX_T * sizeof(int) + (384 + 64) * sizeof(float) + 8 * sizeof(int) +
-                            kDescSlots * sizeof(TileDesc) + (((size_t)(2 * p.B + 1) * sizeof(int) + 15) & ~(size_t)15);
+    const size_t main_lds = (size_t)kStages * G::kStageBytes + (RB == 4 ? (size_t)32 * RB * G::kRowBytes : 0) +
+                            2 * READER_MAX_T * 4 * sizeof(uint32_t) + 2 * READER_MAX_T * sizeof(int) +
+                            64 * sizeof(float) + 8 * sizeof(int) + kDescSlots * sizeof(TileDesc) + pref_bytes;
     // More than 64 KB of LDS per workgroup has to be asked for; the limit counts the
     // kernel's static LDS too, so ask for exactly what this launch needs.
     static size_t lds_allowed = 0;
     if (main_lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_mfma_kernel<D, NKB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_mfma_kernel<D, RB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)main_lds);
         if (e != hipSuccess) { (void)hipGetLastError(); return note_hip_error("hipFuncSetAttribute(attention LDS size)", e); }
         lds_allowed = main_lds;
     }
     if (ev_start) (void)hipEventRecord(ev_start, stream);
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<D, NKB>), dim3(p.n_ranges, p.n_row_chunks), dim3(kThreads),
+    hipLaunchKernelGGL((tree_attn_mfma_kernel<D, RB>), dim3(p.n_ranges, p.n_row_chunks), dim3(kThreads),
                        main_lds, stream, p, p.page_table, p.seq_lens);
     hipError_t e = hipGetLastError();
     if (ev_stop) (void)hipEventRecord(ev_stop, stream);
@@ -876,8 +969,8 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
 
 hipError_t launch_tree_attn_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
     if (p.rows_per_wg == 128)
-        return p.D == 64 ? launch_mfma<64, 1>(p, stream, ev_start, ev_stop) : launch_mfma<128, 1>(p, stream, ev_start, ev_stop);
-    return p.D == 64 ? launch_mfma<64, 2>(p, stream, ev_start, ev_stop) : launch_mfma<128, 2>(p, stream, ev_start, ev_stop);
+        return p.D == 64 ? launch_mfma<64, 4>(p, stream, ev_start, ev_stop) : launch_mfma<128, 4>(p, stream, ev_start, ev_stop);
+    return p.D == 64 ? launch_mfma<64, 8>(p, stream, ev_start, ev_stop) : launch_mfma<128, 8>(p, stream, ev_start, ev_stop);
 }
 
 }  // namespace reader
