@@ -95,8 +95,8 @@ int reader_validate_tree(const int32_t *parents_host, int32_t B, int32_t T);
 /*
  * Bytes of device workspace reader_tree_attn needs for these dims when no
  * sequence is longer than max_seq_len.  Pure host function.  Returns 0 when the
- * dims are invalid.  The workspace holds the partial (unnormalised output, running
- * max, running sum) records of key ranges that were split across workgroups; its
+ * dims are invalid.  The workspace holds the partial (bf16 output normalised by its
+ * own sum, running max, running sum) records of key ranges that were split across workgroups; its
  * contents are meaningless between calls and it may be shared by calls that are
  * ordered on one stream.
  */

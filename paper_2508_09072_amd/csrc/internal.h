@@ -43,8 +43,9 @@ struct AttnParams {
     float scale_log2;                      // sm_scale * log2(e)
 };
 
-// Floats in one partial record: `rows` rows of D outputs, then running max, then running sum.
-__host__ __device__ inline size_t attn_slot_floats(int D, int rows) { return (size_t)rows * (size_t)(D + 2); }
+// Size of one partial record in 4-byte units: `rows` rows of D bf16 outputs (normalised by the
+// record's own sum), then the rows' running maxima and running sums as fp32.
+__host__ __device__ inline size_t attn_slot_floats(int D, int rows) { return (size_t)rows * (size_t)(D / 2 + 2); }
 
 // Number of range workgroups the planner picks; a pure function of the dims so that
 // reader_workspace_bytes and the launch agree.

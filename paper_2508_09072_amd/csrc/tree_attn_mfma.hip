@@ -57,6 +57,7 @@ namespace {
 constexpr float kLn2 = 0.69314718055994530942f;
 constexpr int kWaves = kThreads / 64;
 constexpr int kStages = 3;
+constexpr int kMaxLensInLds = 1024;   // batches up to this size keep the clamped lengths in LDS
 
 __device__ inline int clamp_len(const AttnParams &p, const int32_t *__restrict__ seq_lens, int b) {
     int L = seq_lens[b];
@@ -66,8 +67,9 @@ __device__ inline int clamp_len(const AttnParams &p, const int32_t *__restrict__
 
 // Exclusive prefix sums of tiles-per-pair over the sequences, into s_pref[0..B].
 // Works for any workgroup size that is a multiple of 64 up to 512; s_wsum has 8 entries.
+// s_len (optional) receives the clamped lengths.
 __device__ inline void scan_units(const AttnParams &p, const int32_t *__restrict__ seq_lens, int *s_pref,
-                                  int *s_wsum) {
+                                  int *s_wsum, int *s_len = nullptr) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n_threads = blockDim.x, n_waves = n_threads >> 6;
     int carry = 0;
@@ -75,7 +77,11 @@ __device__ inline void scan_units(const AttnParams &p, const int32_t *__restrict
     for (int base = 0; base < p.B; base += n_threads) {
         const int b = base + tid;
         int v = 0;
-        if (b < p.B) v = (clamp_len(p, seq_lens, b) + kTile - 1) / kTile + p.n_tree_tiles;
+        if (b < p.B) {
+            const int L = clamp_len(p, seq_lens, b);
+            if (s_len) s_len[b] = L;
+            v = (L + kTile - 1) / kTile + p.n_tree_tiles;
+        }
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int t = __shfl_up(v, off);
@@ -169,19 +175,20 @@ enum {
 constexpr int kDescSlots = 256;
 
 // Descriptor of tile i of the range that starts at unit lo and holds n_iter tiles.
-__device__ inline void build_desc(const AttnParams &p, const int32_t *__restrict__ page_table,
-                                  const int32_t *__restrict__ seq_lens, const int *s_pref, long long lo, int n_iter,
-                                  int i, TileDesc *slot, int &bad) {
+// `table` is the page table or a copy of it; `s_len` the clamped lengths in LDS, or null.
+__device__ inline void build_desc(const AttnParams &p, const int32_t *table, const int32_t *__restrict__ seq_lens,
+                                  const int *s_len, const int *s_pref, long long lo, int n_iter, int i, TileDesc *slot,
+                                  int &bad) {
     const long long x = lo + i;
     const int b = find_seq(s_pref, p.B, p.Hkv, x);
-    const int L = clamp_len(p, seq_lens, b);
+    const int L = s_len ? s_len[b] : clamp_len(p, seq_lens, b);
     const int n_pre = (L + kTile - 1) / kTile, n_units = n_pre + p.n_tree_tiles;
     const int rel = (int)(x - (long long)p.Hkv * s_pref[b]);
     const int hkv = rel / n_units, idx = rel - hkv * n_units;
     int blk[4], n_valid, flags = 0;
     if (idx < n_pre) {
         n_valid = min(kTile, L - idx * kTile);
-        const int32_t *row = page_table + (size_t)b * p.max_pages + idx * 4;
+        const int32_t *row = table + (size_t)b * p.max_pages + idx * 4;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             blk[j] = -1;
@@ -376,12 +383,33 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     const int group = row_real ? m_row - node * p.G : 0;
     const bool wave_active = is_computer && chunk_base + rb * 32 < p.M;
 
-    // Tiles per sequence as prefix sums in LDS.  With at most 64 sequences every wavefront
-    // scans on its own and all of them write the same values, so a wavefront may read them
-    // back without a barrier (its own LDS accesses execute in order).
+    // A small page table is fetched whole into the third ring stage (idle until the main loop
+    // starts) while the sequence lengths are on their way, so that the tile list can be written
+    // without a second trip to memory.
+    const int table_ints = p.B * p.max_pages;
+    const bool table_in_lds = (size_t)table_ints * 4 + 256 <= (size_t)G::kStageBytes;   // copies come in 256-byte pieces
+    const int32_t *table = page_table;
+    if (table_in_lds) {
+        const unsigned table_lds = ring_lds + 2 * G::kStageBytes;
+        for (int base = wave_s * 64; base < table_ints; base += kThreads) {
+            const int32_t *src = page_table + min(base + lane, table_ints - 1);
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" :: "v"(src), "s"(table_lds + base * 4) : "memory", "m0");
+        }
+        table = reinterpret_cast<const int32_t *>(ring + 2 * G::kStageBytes);
+    }
+
+    // Tiles per sequence as prefix sums in LDS (and the clamped lengths, for up to 1024 sequences).
+    // With at most 64 sequences every wavefront scans on its own and all of them write the
+    // same values, so a wavefront may read them back without a barrier (its own LDS accesses
+    // execute in order).
+    int *s_len = p.B <= kMaxLensInLds ? s_pref + p.B + 1 : nullptr;
     if (p.B <= 64) {
         int v = 0;
-        if (lane < p.B) v = (clamp_len(p, seq_lens, lane) + kTile - 1) / kTile + p.n_tree_tiles;
+        if (lane < p.B) {
+            const int L = clamp_len(p, seq_lens, lane);
+            s_len[lane] = L;
+            v = (L + kTile - 1) / kTile + p.n_tree_tiles;
+        }
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int t = __shfl_up(v, off);
@@ -390,18 +418,22 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         if (lane < p.B) s_pref[lane + 1] = v;
         if (lane == 0) s_pref[0] = 0;
     } else {
-        scan_units(p, seq_lens, s_pref, s_wsum);
+        scan_units(p, seq_lens, s_pref, s_wsum, s_len);
     }
     const long long U = (long long)p.Hkv * __builtin_amdgcn_readfirstlane(s_pref[p.B]);
     const long long lo = range_begin(blockIdx.x, U, p.n_ranges);
     const long long hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
+    if (table_in_lds) {
+        wait_vmcnt<0>();
+        __syncthreads();   // the copy of the page table is complete (every wavefront reaches this)
+    }
     if (lo >= hi) return;
     const int n_iter = (int)(hi - lo);
 
     int bad = 0;
     if (htid >= 0)
         for (int i = htid; i < min(n_iter, kDescSlots); i += kHelpers)
-            build_desc(p, page_table, seq_lens, s_pref, lo, n_iter, i, s_desc + i, bad);
+            build_desc(p, table, seq_lens, s_len, s_pref, lo, n_iter, i, s_desc + i, bad);
     __syncthreads();   // the tile list is written
 
     auto desc_of = [&](int i) -> const TileDesc * { return s_desc + (i & (kDescSlots - 1)); };
@@ -480,15 +512,16 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         }
     };
 
-    const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
-    auto issue_tile = [&](int blk, int nv, int fl, unsigned stage_lds) {
+    // (the per-lane copy constants are made where they are used, so that they occupy registers
+    // only in the wavefronts and loops that copy)
+    auto issue_tile = [&](const CopyLane<D, CW> &cl, int blk, int nv, int fl, unsigned stage_lds) {
         const CopyPlan cp = plan_copy<D, CW>(p, blk, nv, fl, cw);
 #pragma unroll
         for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D, CW>(cp, cl, stage_lds, cw, j);
     };
-    auto issue_tile_at = [&](int i, unsigned stage_lds) {
+    auto issue_tile_at = [&](const CopyLane<D, CW> &cl, int i, unsigned stage_lds) {
         const TileDesc *d = desc_of(i);
-        issue_tile(__builtin_amdgcn_readfirstlane(d->blk[cw >> kQuarterShift]),
+        issue_tile(cl, __builtin_amdgcn_readfirstlane(d->blk[cw >> kQuarterShift]),
                    __builtin_amdgcn_readfirstlane(d->n_valid), __builtin_amdgcn_readfirstlane(d->flags), stage_lds);
     };
 
@@ -500,16 +533,17 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
 
     // prologue: tiles 0 and 1 (with the parent pointers their segments need), the first query rows
     if (is_copier) {
+        const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
         const int f0 = desc_flags(0);
         if (kDma && (f0 & kDescMasks)) { copy_parents(desc_b(0), 0); gen_cpy = 1; }
-        issue_tile_at(0, ring_lds);
+        issue_tile_at(cl, 0, ring_lds);
         if (n_iter > 1) {
             const int f1 = desc_flags(1);
             if (kDma && (f1 & kDescFresh)) {
                 if (f1 & kDescMasks) { copy_parents(desc_b(1), gen_cpy & 1); ++gen_cpy; }
                 prev_fresh_c = 1;
             }
-            issue_tile_at(1, ring_lds + G::kStageBytes);
+            issue_tile_at(cl, 1, ring_lds + G::kStageBytes);
         }
     }
     if (is_computer) load_q(desc_b(0), desc_hkv(0));
@@ -541,36 +575,69 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     const float grow_margin = 8.f / c2;
 
     f32x16 s[2];           // S^T of the current tile, one per 32-key block
-    // S^T = K . Q^T
-    auto qk_product = [&](const char *stage) {
-        // All fragment reads of block 0 are issued before its first matrix instruction, and
-        // block 1's reads are interleaved with block 0's products.
-        bf16x8 ka[2][G::kKSteps];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int kk = 0; kk < G::kKSteps; ++kk)
-                ka[kb][kk] = *reinterpret_cast<const bf16x8 *>(stage + k_rd[kk] + kb * 32 * G::kRowBytes);
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < G::kKSteps; ++kk)
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kb][kk], qf[kk], s[kb], 0, 0, 0);
-        }
-        // instruction order handed to the scheduler: it serialises read/product pairs otherwise
-        __builtin_amdgcn_sched_group_barrier(0x100, G::kKSteps, 0);          // LDS reads of block 0
-#pragma unroll
-        for (int kk = 0; kk < G::kKSteps; ++kk) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one product of block 0
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one read of block 1
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, G::kKSteps, 0);          // products of block 1
-    };
 
-    // masks (ragged last prefix tile, tree tiles), row maximum, rare accumulator rescale
-    auto softmax_max = [&](bool is_tree, int tt, int n_valid) {
+    // A wavefront's vector instructions do not run under its own matrix instructions (only
+    // another wavefront's do), so the tile is a plain sequence with as little exposed latency
+    // as possible:
+    //   K fragments of both 32-key blocks; S0, S1 = K.Q^T as two independent accumulation
+    //   chains, alternating; V fragments of the first 32 keys asked for; masks, row maximum
+    //   (one cross-lane swap), weights; V fragments of the other 32 keys asked for while the
+    //   first half of O += V^T.P^T runs.
+    // `between(j)`, j = 0..3, is called at four points of the tile (the wavefronts that also
+    // copy put their copy instructions there).
+    auto compute_tile = [&](const char *stage, int flags, int n_valid, auto &&between) {
+        const bool is_tree = (flags & kDescTree) != 0;
+        const int tt = flags >> 8;
+        {
+            bf16x8 ka0[G::kKSteps], ka1[G::kKSteps];
+#pragma unroll
+            for (int kk = 0; kk < G::kKSteps; ++kk) {
+                ka0[kk] = *reinterpret_cast<const bf16x8 *>(stage + k_rd[kk]);
+                ka1[kk] = *reinterpret_cast<const bf16x8 *>(stage + k_rd[kk] + 32 * G::kRowBytes);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { s[0][i] = 0.f; s[1][i] = 0.f; }
+#pragma unroll
+            for (int kk = 0; kk < G::kKSteps; ++kk) {
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka0[kk], qf[kk], s[0], 0, 0, 0);
+                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka1[kk], qf[kk], s[1], 0, 0, 0);
+            }
+            // order handed to the scheduler: the first two reads, then one read per product
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+            for (int j = 0; j < 2 * G::kKSteps - 2; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
+        between(0);
+
+        // V^T fragments, as the two transposed reads of each (16-key step, output block).  A
+        // wavefront that has a SIMD to itself asks for all of them now, so that they arrive
+        // during the softmax; with two wavefronts per SIMD (and fewer registers to spare) the
+        // reads of a step are issued one step ahead of its products.
+        constexpr int kVSlots = kDma ? 4 : 2;
+        s16x4 vh[kVSlots][G::kOBlocks][2];
+        auto read_v_step = [&](int ks) {
+            const int key_base = ((ks >> 1) * 32 + (ks & 1) * 16) * G::kRowBytes;
+#pragma unroll
+            for (int db = 0; db < G::kOBlocks; ++db) {
+                const char *src = stage + v_rd[db] + key_base;
+                vh[ks % kVSlots][db][0] = lds_read_tr16(src);                         // keys +0..3 (+4h)
+                vh[ks % kVSlots][db][1] = lds_read_tr16(src + 8 * G::kRowBytes);      // keys +8..11 (+4h)
+            }
+        };
+        if (kDma) {
+            __builtin_amdgcn_sched_barrier(0);   // not before the K fragments are consumed: registers
+            read_v_step(0);
+            read_v_step(1);
+            read_v_step(2);
+            read_v_step(3);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // ---- masks (ragged last prefix tile, tree tiles) ----
         if (is_tree) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -592,12 +659,17 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                 }
         }
         // ---- online softmax along the keys (all values of a lane share one query row) ----
-        float mx = s[0][0];
+        float mx0 = fmaxf(s[0][0], s[0][1]), mx1 = fmaxf(s[1][0], s[1][1]);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        for (int i = 2; i < 16; i += 2) {
+            mx0 = fmaxf(fmaxf(mx0, s[0][i]), s[0][i + 1]);
+            mx1 = fmaxf(fmaxf(mx1, s[1][i]), s[1][i + 1]);
+        }
+        float mx = fmaxf(mx0, mx1);
+        {   // the other half of the row's keys sits in lane ^ 32
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+            mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        }
         const bool grow = mx > m_run + grow_margin;     // also the first finite maximum (m_run = -inf)
         if (__any(grow)) {
             const float alpha = grow ? __builtin_amdgcn_exp2f((m_run - mx) * c2) : 1.f;   // m_run = -inf gives 0
@@ -608,52 +680,50 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
 #pragma unroll
                 for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
         }
-    };
+        between(1);
+        {
+            const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
+            float lsum0 = 0.f, lsum1 = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; i += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(s[kb][i] * c2 - mc);
+                    const float p1 = __builtin_amdgcn_exp2f(s[kb][i + 1] * c2 - mc);
+                    lsum0 += p0;
+                    lsum1 += p1;
+                    pk[kb][i >> 1] = pack_bf16x2(p0, p1);
+                }
+            l_run += lsum0 + lsum1;
+        }
+        between(2);
 
-    // softmax weights of s relative to the running reference -> pk, running sum
-    auto softmax_exp = [&]() {
-        const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
-        float lsum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(s[kb][i] * c2 - mc);
-                const float p1 = __builtin_amdgcn_exp2f(s[kb][i + 1] * c2 - mc);
-                lsum += p0 + p1;
-                pk[kb][i >> 1] = pack_bf16x2(p0, p1);
-            }
-        l_run += lsum;
-    };
-
-    // O^T += V^T . P^T : the S^T registers of a lane are, 8 at a time, the B operand.
-    // Written in the order it should run: the V fragments of a 16-key step are read while
-    // the previous step's products execute.
-    auto pv_product = [&](const char *stage) {
-        auto read_step = [&](int ks, bf16x8 (&frag)[G::kOBlocks]) {
-            const int key_base = ((ks >> 1) * 32 + (ks & 1) * 16) * G::kRowBytes;
-#pragma unroll
-            for (int db = 0; db < G::kOBlocks; ++db) {
-                const char *src = stage + v_rd[db] + key_base;
-                const s16x4 lo4 = lds_read_tr16(src);                         // keys +0..3 (+4h)
-                const s16x4 hi4 = lds_read_tr16(src + 8 * G::kRowBytes);      // keys +8..11 (+4h)
-                const s16x8 a8 = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-                frag[db] = __builtin_bit_cast(bf16x8, a8);
-            }
-        };
-        bf16x8 va[2][G::kOBlocks];
-        read_step(0, va[0]);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks + 1 < 4) read_step(ks + 1, va[(ks + 1) & 1]);
+        // ---- O^T += V^T . P^T : the S^T registers of a lane are, 8 at a time, the B operand ----
+        auto pv_step = [&](int ks) {
             const int kb = ks >> 1, m2 = ks & 1;
             u32x4 pv;
             pv.x = pk[kb][4 * m2]; pv.y = pk[kb][4 * m2 + 1]; pv.z = pk[kb][4 * m2 + 2]; pv.w = pk[kb][4 * m2 + 3];
             const bf16x8 pb = __builtin_bit_cast(bf16x8, pv);
 #pragma unroll
-            for (int db = 0; db < G::kOBlocks; ++db)
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks & 1][db], pb, o[db], 0, 0, 0);
+            for (int db = 0; db < G::kOBlocks; ++db) {
+                const s16x8 a8 = __builtin_shufflevector(vh[ks % kVSlots][db][0], vh[ks % kVSlots][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
+            }
+        };
+        if (kDma) {
+            pv_step(0);
+            pv_step(1);
+            pv_step(2);
+            pv_step(3);
+        } else {
+            read_v_step(0);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (ks + 1 < 4) read_v_step(ks + 1);
+                pv_step(ks);
+            }
         }
+        between(3);
     };
 
     auto reset_state = [&](int flags) {
@@ -673,35 +743,54 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         const int e_b = desc_b(it), e_hkv = desc_hkv(it);
         const float l_tot = l_run + __shfl_xor(l_run, 32);
         if (seg_from_pair_start && pair_ends) {
-            if (row_real) {
-                const float inv = 1.f / l_tot;
-                uint16_t *orow = p.out + (((size_t)e_b * p.T + node) * p.Hq + e_hkv * p.G + group) * D;
-#pragma unroll
-                for (int db = 0; db < G::kOBlocks; ++db)
-#pragma unroll
-                    for (int i4 = 0; i4 < 4; ++i4) {
-                        uint2 w;
-                        w.x = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
-                        w.y = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
-                        *reinterpret_cast<uint2 *>(orow + db * 32 + i4 * 8 + 4 * h) = w;
-                    }
-                if (p.lse && h == 0)
-                    p.lse[((size_t)e_b * p.Hq + e_hkv * p.G + group) * p.T + node] =
-                        (m_run * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
-            }
-        } else {
-            const size_t slot = ((size_t)(2 * blockIdx.x + (seg_from_pair_start ? 1 : 0)) * p.n_row_chunks + blockIdx.y);
-            float *rec = p.workspace + slot * attn_slot_floats(D, kRowsPerWG);
-            float *orow = rec + (size_t)row_local * D;
+            // A lane holds, per 8-wide chunk of the output row, 4 values and its partner lane
+            // (lane ^ 32) the other 4.  One half-wave swap per pair of chunks gives every lane
+            // whole 16-byte chunks: lane h of the pair ends up with chunk 2k + h.
+            const float inv = 1.f / l_tot;
+            uint16_t *orow = p.out + (((size_t)e_b * p.T + node) * p.Hq + e_hkv * p.G + group) * D;
 #pragma unroll
             for (int db = 0; db < G::kOBlocks; ++db)
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4)
-                    *reinterpret_cast<float4 *>(orow + db * 32 + i4 * 8 + 4 * h) =
-                        make_float4(o[db][4 * i4], o[db][4 * i4 + 1], o[db][4 * i4 + 2], o[db][4 * i4 + 3]);
+                for (int i4 = 0; i4 < 4; i4 += 2) {
+                    const uint32_t a0 = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
+                    const uint32_t a1 = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
+                    const uint32_t b0 = pack_bf16x2(o[db][4 * i4 + 4] * inv, o[db][4 * i4 + 5] * inv);
+                    const uint32_t b1 = pack_bf16x2(o[db][4 * i4 + 6] * inv, o[db][4 * i4 + 7] * inv);
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+                    u32x4 w;
+                    w.x = s0[0]; w.y = s1[0]; w.z = s0[1]; w.w = s1[1];
+                    if (row_real) *reinterpret_cast<u32x4 *>(orow + db * 32 + (i4 + h) * 8) = w;
+                }
+            if (row_real && p.lse && h == 0)
+                p.lse[((size_t)e_b * p.Hq + e_hkv * p.G + group) * p.T + node] =
+                    (m_run * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
+        } else {
+            // Partial record: the output so far, normalised by its own sum and rounded to bf16,
+            // as [D / 8 chunks][rows][8 values] (the order the swapped registers hold it, so every
+            // store instruction writes whole 512-byte runs), then the maxima and the sums.
+            const size_t slot = ((size_t)(2 * blockIdx.x + (seg_from_pair_start ? 1 : 0)) * p.n_row_chunks + blockIdx.y);
+            float *rec = p.workspace + slot * attn_slot_floats(D, kRowsPerWG);
+            u32x4 *rec16 = reinterpret_cast<u32x4 *>(rec);
+            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;   // a row may see no key of this segment
+#pragma unroll
+            for (int db = 0; db < G::kOBlocks; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; i4 += 2) {
+                    const uint32_t a0 = pack_bf16x2(o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv);
+                    const uint32_t a1 = pack_bf16x2(o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
+                    const uint32_t b0 = pack_bf16x2(o[db][4 * i4 + 4] * inv, o[db][4 * i4 + 5] * inv);
+                    const uint32_t b1 = pack_bf16x2(o[db][4 * i4 + 6] * inv, o[db][4 * i4 + 7] * inv);
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+                    u32x4 w;
+                    w.x = s0[0]; w.y = s1[0]; w.z = s0[1]; w.w = s1[1];
+                    rec16[(size_t)(db * 4 + i4 + h) * kRowsPerWG + row_local] = w;
+                }
             if (h == 0) {
-                rec[(size_t)kRowsPerWG * D + row_local] = m_run * c2;
-                rec[(size_t)kRowsPerWG * (D + 1) + row_local] = l_tot;
+                float *ml = rec + (size_t)kRowsPerWG * (D / 2);
+                ml[row_local] = m_run * c2;
+                ml[kRowsPerWG + row_local] = l_tot;
             }
         }
     };
@@ -711,7 +800,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     auto extend_list = [&](int it) {
         if ((it & (kDescSlots / 2 - 1)) == 0 && it > 0 && htid >= 0 && htid < kDescSlots / 2) {
             const int i = it + kDescSlots / 2 + htid;
-            if (i < n_iter) build_desc(p, page_table, seq_lens, s_pref, lo, n_iter, i, s_desc + (i & (kDescSlots - 1)), bad);
+            if (i < n_iter) build_desc(p, page_table, seq_lens, s_len, s_pref, lo, n_iter, i, s_desc + (i & (kDescSlots - 1)), bad);
         }
     };
 
@@ -724,6 +813,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
 
     if (kDma && is_copier) {
         // ---------------- wavefronts that only move data (RB = 4) ----------------
+        const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
         // descriptor words of the tile to copy, read one iteration ahead
         int2 d_cpy = *reinterpret_cast<const int2 *>(&desc_of(2)->n_valid);
         int d_blk = desc_of(2)->blk[cw >> kQuarterShift];
@@ -758,7 +848,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                     if (x - prev_fresh_c >= 3) stage_q(xb, desc_hkv(x));
                     prev_fresh_c = x;
                 }
-                issue_tile(c_blk, c_valid, c_flags, ring_lds + st_cpy);
+                issue_tile(cl, c_blk, c_valid, c_flags, ring_lds + st_cpy);
             }
             rotate_stages();
         }
@@ -785,16 +875,14 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                 if (t_flags & kDescMasks) { anc = s_anc + (gen_use & 1) * READER_MAX_T * 4; ++gen_use; }
             }
             if (wave_active) {
-                qk_product(stage);
-                softmax_max((t_flags & kDescTree) != 0, t_flags >> 8, t_valid);
-                softmax_exp();
-                pv_product(stage);
+                compute_tile(stage, t_flags, t_valid, [](int) {});
                 if (pair_ends || last_iter) finish_segment(it, pair_ends);
             }
             rotate_stages();
         }
     } else {
         // ---------------- every wavefront computes and copies (RB = 8) ----------------
+        const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
         // descriptor words of the tile to compute (rows, flags) and of the tile to copy, read one
         // iteration ahead so that the LDS latency hides behind the barrier
         int2 d_cur = *reinterpret_cast<const int2 *>(&desc_of(0)->n_valid);
@@ -846,14 +934,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                 }
             };
             if (wave_active) {
-                qk_product(stage);
-                copy_part(0);
-                softmax_max((t_flags & kDescTree) != 0, t_flags >> 8, t_valid);
-                copy_part(1);
-                softmax_exp();
-                copy_part(2);
-                pv_product(stage);
-                copy_part(3);
+                compute_tile(stage, t_flags, t_valid, copy_part);
                 if (pair_ends || last_iter) finish_segment(it, pair_ends);
             } else {
                 copy_part(0); copy_part(1); copy_part(2); copy_part(3);
@@ -866,8 +947,9 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
 }
 
 // Merge the partial records of every pair that was cut between workgroups.
-// grid = (B * Hkv, row chunks * rows_per_wg / 32): one workgroup per 32 query rows of a
-// pair, 8 threads per row, each 1/8 of D.
+// A record holds [D / 8 chunks][rows][8 bf16] of output normalised by the record's own sum, then
+// the rows' running maxima, then their running sums.  One thread takes one 8-wide chunk of one query row:
+// D / 8 threads per row, 256 / (D / 8) rows per workgroup; grid = (B * Hkv, rows / that).
 template <int D>
 __global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnParams p, const int32_t *__restrict__ seq_lens) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -883,10 +965,12 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnParams p, cons
     const int w_last = range_of_unit(start + n_units - 1, U, p.n_ranges);
     if (w_first == w_last) return;   // finished in place by one workgroup
 
+    constexpr int kC = D / 8;                   // chunks (threads) per row
+    constexpr int kRowsPerBlock = 256 / kC;
     const int tid = threadIdx.x;
-    const int blocks_per_chunk = p.rows_per_wg / 32;
+    const int blocks_per_chunk = p.rows_per_wg / kRowsPerBlock;
     const int row_chunk = blockIdx.y / blocks_per_chunk;
-    const int row_local = (blockIdx.y - row_chunk * blocks_per_chunk) * 32 + (tid >> 3), part = tid & 7;
+    const int row_local = (blockIdx.y - row_chunk * blocks_per_chunk) * kRowsPerBlock + tid / kC, c = tid % kC;
     const int m_row = row_chunk * p.rows_per_wg + row_local;
     if (m_row >= p.M) return;
     const int node = m_row / p.G, group = m_row - node * p.G;
@@ -902,41 +986,37 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnParams p, cons
 
     float m_all = -INFINITY;
     for (int w = w_first; w <= w_last; ++w)
-        if (!empty(w)) m_all = fmaxf(m_all, record(w)[rows * D + row_local]);
+        if (!empty(w)) m_all = fmaxf(m_all, record(w)[rows * (D / 2) + row_local]);
     // m_all is finite: every query row sees at least its own tree node
 
-    constexpr int kPart = D / 8;
-    float acc[kPart];
+    float acc[8];
 #pragma unroll
-    for (int d = 0; d < kPart; ++d) acc[d] = 0.f;
+    for (int d = 0; d < 8; ++d) acc[d] = 0.f;
     float l_all = 0.f;
     for (int w = w_first; w <= w_last; ++w) {
         if (empty(w)) continue;
         const float *rec = record(w);
-        const float mw = rec[rows * D + row_local];
+        const float mw = rec[rows * (D / 2) + row_local];
         if (mw == -INFINITY) continue;
-        const float f = __builtin_amdgcn_exp2f(mw - m_all);
-        l_all += f * rec[rows * (D + 1) + row_local];
-        const float4 *src = reinterpret_cast<const float4 *>(rec + (size_t)row_local * D + part * kPart);
+        const float f = __builtin_amdgcn_exp2f(mw - m_all) * rec[rows * (D / 2 + 1) + row_local];
+        l_all += f;
+        const uint4 v = reinterpret_cast<const uint4 *>(rec)[(size_t)c * rows + row_local];
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-        for (int d4 = 0; d4 < kPart / 4; ++d4) {
-            const float4 v = src[d4];
-            acc[4 * d4] += f * v.x; acc[4 * d4 + 1] += f * v.y;
-            acc[4 * d4 + 2] += f * v.z; acc[4 * d4 + 3] += f * v.w;
+        for (int e = 0; e < 4; ++e) {
+            acc[2 * e] += f * __uint_as_float(u[e] << 16);
+            acc[2 * e + 1] += f * __uint_as_float(u[e] & 0xffff0000u);
         }
     }
     const float inv = 1.f / l_all;
-    uint16_t *orow = p.out + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D + part * kPart;
-#pragma unroll
-    for (int d8 = 0; d8 < kPart / 8; ++d8) {
-        uint4 w;
-        w.x = pack_bf16x2(acc[8 * d8] * inv, acc[8 * d8 + 1] * inv);
-        w.y = pack_bf16x2(acc[8 * d8 + 2] * inv, acc[8 * d8 + 3] * inv);
-        w.z = pack_bf16x2(acc[8 * d8 + 4] * inv, acc[8 * d8 + 5] * inv);
-        w.w = pack_bf16x2(acc[8 * d8 + 6] * inv, acc[8 * d8 + 7] * inv);
-        *reinterpret_cast<uint4 *>(orow + 8 * d8) = w;
-    }
-    if (p.lse && part == 0)
+    uint16_t *orow = p.out + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D + c * 8;
+    uint4 w;
+    w.x = pack_bf16x2(acc[0] * inv, acc[1] * inv);
+    w.y = pack_bf16x2(acc[2] * inv, acc[3] * inv);
+    w.z = pack_bf16x2(acc[4] * inv, acc[5] * inv);
+    w.w = pack_bf16x2(acc[6] * inv, acc[7] * inv);
+    *reinterpret_cast<uint4 *>(orow) = w;
+    if (p.lse && c == 0)
         p.lse[((size_t)b * p.Hq + hkv * p.G + group) * p.T + node] = (m_all + __builtin_amdgcn_logf(l_all)) * kLn2;
 }
 
@@ -946,7 +1026,8 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
     const size_t pref_bytes = ((size_t)(p.B + 1) * sizeof(int) + 15) & ~(size_t)15;
     const size_t main_lds = (size_t)kStages * G::kStageBytes + (RB == 4 ? (size_t)32 * RB * G::kRowBytes : 0) +
                             2 * READER_MAX_T * 4 * sizeof(uint32_t) + 2 * READER_MAX_T * sizeof(int) +
-                            64 * sizeof(float) + 8 * sizeof(int) + kDescSlots * sizeof(TileDesc) + pref_bytes;
+                            64 * sizeof(float) + 8 * sizeof(int) + kDescSlots * sizeof(TileDesc) + pref_bytes +
+                            (p.B <= kMaxLensInLds ? (size_t)p.B * sizeof(int) + 16 : 0);
     // More than 64 KB of LDS per workgroup has to be asked for; the limit counts the
     // kernel's static LDS too, so ask for exactly what this launch needs.
     static size_t lds_allowed = 0;
@@ -962,7 +1043,7 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
     hipError_t e = hipGetLastError();
     if (ev_stop) (void)hipEventRecord(ev_stop, stream);
     if (e != hipSuccess) return note_hip_error("launch tree_attn_mfma_kernel", e);
-    hipLaunchKernelGGL(tree_attn_merge_kernel<D>, dim3(p.B * p.Hkv, p.n_row_chunks * (p.rows_per_wg / 32)), dim3(256),
+    hipLaunchKernelGGL(tree_attn_merge_kernel<D>, dim3(p.B * p.Hkv, p.n_row_chunks * (p.rows_per_wg / (256 / (D / 8)))), dim3(256),
                        pref_bytes, stream, p, p.seq_lens);
     return note_hip_error("launch tree_attn_merge_kernel", hipGetLastError());
 }
