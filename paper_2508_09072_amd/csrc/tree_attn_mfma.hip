@@ -56,7 +56,8 @@ namespace {
 
 constexpr float kLn2 = 0.69314718055994530942f;
 constexpr int kWaves = kThreads / 64;
-constexpr int kStages = 3;
+// ring depth: 4 tile buffers when dedicated wavefronts copy (up to 128 query rows), else 3
+constexpr int ring_stages(int rb) { return rb == 4 ? 4 : 3; }
 constexpr int kMaxLensInLds = 1024;   // batches up to this size keep the clamped lengths in LDS
 
 __device__ inline int clamp_len(const AttnParams &p, const int32_t *__restrict__ seq_lens, int b) {
@@ -171,6 +172,7 @@ enum {
     kDescPairEnd = 4,     // last tile of its pair
     kDescMasks = 8,       // (on a fresh tile) the segment reaches the pair's tree tiles
     kDescPairStart = 16,  // first tile of its pair
+    kDescQ = 32,          // not a tile: the query rows of the segment that starts with the next item
 };
 constexpr int kDescSlots = 256;
 
@@ -213,6 +215,49 @@ __device__ inline void build_desc(const AttnParams &p, const int32_t *table, con
     int4 *dst = reinterpret_cast<int4 *>(slot);
     dst[0] = make_int4(blk[0], blk[1], blk[2], blk[3]);
     dst[1] = make_int4(n_valid, flags, b, hkv);
+}
+
+// Pair (sequence * Hkv + kv head) of flat tile x.
+__device__ inline int pair_of_tile(const int *s_pref, int B, int Hkv, long long x) {
+    const int b = find_seq(s_pref, B, Hkv, x);
+    const int n_b = s_pref[b + 1] - s_pref[b];
+    return b * Hkv + (int)((x - (long long)Hkv * s_pref[b]) / n_b);
+}
+
+// Up to 128 query rows: the list holds, in front of every segment, one query unit (the pair's
+// query rows, which travel through the ring like a tile).  Item i of the list of tile range
+// [lo, lo + n_tiles), whose first tile belongs to pair q_lo:
+//   the query unit of pair q > q_lo sits at position start(q) - lo + (q - q_lo), followed by the
+//   pair's tiles; the first segment's query unit sits at position 0, followed by tile lo.
+__device__ inline void build_item(const AttnParams &p, const int32_t *table, const int32_t *__restrict__ seq_lens,
+                                  const int *s_len, const int *s_pref, long long lo, int n_tiles, int q_lo, int i,
+                                  TileDesc *slot, int &bad) {
+    const long long target = lo + q_lo + i;   // largest pair q with start(q) + q <= target owns item i
+    int blo = 0, bhi = p.B - 1;
+    while (blo < bhi) {
+        const int mid = (blo + bhi + 1) >> 1;
+        if ((long long)p.Hkv * (s_pref[mid] + mid) <= target) blo = mid; else bhi = mid - 1;
+    }
+    int b = blo;
+    const int n_b = s_pref[b + 1] - s_pref[b];
+    int hkv = (int)((target - (long long)p.Hkv * (s_pref[b] + b)) / (n_b + 1));
+    hkv = hkv > p.Hkv - 1 ? p.Hkv - 1 : hkv;
+    const int q = b * p.Hkv + hkv;
+    long long pos_q = 0, first_tile = lo;
+    if (q > q_lo) {
+        first_tile = (long long)p.Hkv * s_pref[b] + (long long)hkv * n_b;
+        pos_q = first_tile - lo + (q - q_lo);
+    } else {
+        b = q_lo / p.Hkv;
+        hkv = q_lo - b * p.Hkv;
+    }
+    if (i == pos_q) {
+        int4 *dst = reinterpret_cast<int4 *>(slot);
+        dst[0] = make_int4(-1, -1, -1, -1);
+        dst[1] = make_int4(0, kDescQ, b, hkv);
+    } else {
+        build_desc(p, table, seq_lens, s_len, s_pref, lo, n_tiles, (int)(first_tile + (i - pos_q - 1) - lo), slot, bad);
+    }
 }
 
 // Asynchronous copy HBM -> LDS: lane l moves 16 bytes from its global address to LDS byte
@@ -350,20 +395,19 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     using G = Geometry<D, CW>;
     constexpr int kRowsPerWG = 32 * RB;
     constexpr int kCopiesPerTile = 2 * G::kCopies;   // per copying wavefront
-    constexpr int kQStageBytes = kDma ? kRowsPerWG * G::kRowBytes : 0;
+    constexpr int kS = ring_stages(RB);              // tile buffers in the ring
     constexpr int kHelpers = kDma ? 256 : kThreads;  // threads that build the tile list and the masks
+    static_assert(!kDma || kRowsPerWG * G::kRowBytes == G::kStageBytes, "a query unit fills exactly one ring stage");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    char *ring = smem;                                                               // [kStages][kStageBytes]
-    char *s_q = smem + kStages * G::kStageBytes;                                     // staged query rows (RB = 4)
-    uint32_t *s_anc = reinterpret_cast<uint32_t *>(s_q + kQStageBytes);              // [2][READER_MAX_T][4]
+    char *ring = smem;                                                               // [kS][kStageBytes]
+    uint32_t *s_anc = reinterpret_cast<uint32_t *>(smem + kS * G::kStageBytes);      // [2][READER_MAX_T][4]
     int *s_par = reinterpret_cast<int *>(s_anc + 2 * READER_MAX_T * 4);              // [2][READER_MAX_T]
     float *s_sink = reinterpret_cast<float *>(s_par + 2 * READER_MAX_T);             // [64] landing zone of cache-warming copies
     int *s_wsum = reinterpret_cast<int *>(s_sink + 64);                              // [8]
     TileDesc *s_desc = reinterpret_cast<TileDesc *>(s_wsum + 8);                     // [kDescSlots]
     int *s_pref = reinterpret_cast<int *>(s_desc + kDescSlots);                      // [B + 1]
     const unsigned ring_lds = (unsigned)(size_t)(lds_char *)ring;
-    const unsigned q_lds = (unsigned)(size_t)(lds_char *)s_q;
     const unsigned par_lds = (unsigned)(size_t)(lds_char *)reinterpret_cast<char *>(s_par);
     const unsigned prefetch_lds = (unsigned)(size_t)(lds_char *)reinterpret_cast<char *>(s_sink);
 
@@ -383,19 +427,19 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     const int group = row_real ? m_row - node * p.G : 0;
     const bool wave_active = is_computer && chunk_base + rb * 32 < p.M;
 
-    // A small page table is fetched whole into the third ring stage (idle until the main loop
+    // A small page table is fetched whole into the last ring stage (idle until the main loop
     // starts) while the sequence lengths are on their way, so that the tile list can be written
     // without a second trip to memory.
     const int table_ints = p.B * p.max_pages;
     const bool table_in_lds = (size_t)table_ints * 4 + 256 <= (size_t)G::kStageBytes;   // copies come in 256-byte pieces
     const int32_t *table = page_table;
     if (table_in_lds) {
-        const unsigned table_lds = ring_lds + 2 * G::kStageBytes;
+        const unsigned table_lds = ring_lds + (kS - 1) * G::kStageBytes;
         for (int base = wave_s * 64; base < table_ints; base += kThreads) {
             const int32_t *src = page_table + min(base + lane, table_ints - 1);
             asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" :: "v"(src), "s"(table_lds + base * 4) : "memory", "m0");
         }
-        table = reinterpret_cast<const int32_t *>(ring + 2 * G::kStageBytes);
+        table = reinterpret_cast<const int32_t *>(ring + (kS - 1) * G::kStageBytes);
     }
 
     // Tiles per sequence as prefix sums in LDS (and the clamped lengths, for up to 1024 sequences).
@@ -428,13 +472,24 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         __syncthreads();   // the copy of the page table is complete (every wavefront reaches this)
     }
     if (lo >= hi) return;
-    const int n_iter = (int)(hi - lo);
+    const int n_tiles = (int)(hi - lo);
+    // items of the list: the tiles, and with dedicated copy wavefronts one query unit per segment
+    int q_lo = 0, n_iter = n_tiles;
+    if (kDma) {
+        q_lo = __builtin_amdgcn_readfirstlane(pair_of_tile(s_pref, p.B, p.Hkv, lo));
+        n_iter += 1 + __builtin_amdgcn_readfirstlane(pair_of_tile(s_pref, p.B, p.Hkv, hi - 1)) - q_lo;
+    }
 
     int bad = 0;
+    auto write_item = [&](int i) {
+        if (kDma) build_item(p, i < kDescSlots ? table : page_table, seq_lens, s_len, s_pref, lo, n_tiles, q_lo, i,
+                             s_desc + (i & (kDescSlots - 1)), bad);
+        else build_desc(p, i < kDescSlots ? table : page_table, seq_lens, s_len, s_pref, lo, n_tiles, i,
+                        s_desc + (i & (kDescSlots - 1)), bad);
+    };
     if (htid >= 0)
-        for (int i = htid; i < min(n_iter, kDescSlots); i += kHelpers)
-            build_desc(p, table, seq_lens, s_len, s_pref, lo, n_iter, i, s_desc + i, bad);
-    __syncthreads();   // the tile list is written
+        for (int i = htid; i < min(n_iter, kDescSlots); i += kHelpers) write_item(i);
+    __syncthreads();   // the list is written
 
     auto desc_of = [&](int i) -> const TileDesc * { return s_desc + (i & (kDescSlots - 1)); };
     auto desc_b = [&](int i) { return __builtin_amdgcn_readfirstlane(desc_of(i)->b); };
@@ -457,28 +512,25 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off"
                      :: "v"(qrow + (h * 64) % D), "s"(prefetch_lds) : "memory", "m0");
     };
-    // RB = 4: the copying wavefronts stage a pair's query rows in LDS (rows swizzled like a K
-    // tile) two tiles before the pair starts; the computing wavefronts read their fragments
-    // from there.  Only done when the previous pair started at least three tiles earlier, so
-    // that the single buffer is never rewritten while it is read; otherwise rows are loaded
-    // straight from memory.
-    auto stage_q = [&](int b, int hkv) {
-        constexpr int kQCopies = kQStageBytes / 1024 / CW;
+    // RB = 4: a query unit.  The copying wavefronts move the pair's query rows into a ring
+    // stage (rows swizzled like a K tile, rows past the last one as zeros); the computing
+    // wavefronts read their fragments from there.
+    auto issue_q = [&](int b, int hkv, unsigned stage_lds) {
         const char *qbase = reinterpret_cast<const char *>(p.q) + ((size_t)b * p.T * p.Hq + hkv * p.G) * (D * 2);
         const char *zeros = reinterpret_cast<const char *>(kZeroRow) + (lane & 15) * 16;
 #pragma unroll
-        for (int i = 0; i < kQCopies; ++i) {
-            const int r = (cw * kQCopies + i) * G::kRowsPerCopy + lane / G::kChunks;
+        for (int i = 0; i < kCopiesPerTile; ++i) {
+            const int r = (cw * kCopiesPerTile + i) * G::kRowsPerCopy + lane / G::kChunks;
             const int c = (lane % G::kChunks) ^ swizzle_k<D>(r);
             const int nd = r / p.G, gr = r - nd * p.G;
             const char *src = r < p.M ? qbase + ((size_t)nd * p.Hq + gr) * (D * 2) + c * 16 : zeros;
-            copy16_lane(src, q_lds + (cw * kQCopies + i) * 1024);
+            copy16_lane(src, stage_lds + (cw * kCopiesPerTile + i) * 1024);
         }
     };
-    auto read_q_stage = [&]() {
+    auto read_q_stage = [&](const char *stage) {
 #pragma unroll
         for (int kk = 0; kk < G::kKSteps; ++kk)
-            qf[kk] = *reinterpret_cast<const bf16x8 *>(s_q + row_local * G::kRowBytes +
+            qf[kk] = *reinterpret_cast<const bf16x8 *>(stage + row_local * G::kRowBytes +
                                                        (((2 * kk + h) ^ swizzle_k<D>(row_local)) << 4));
     };
 
@@ -528,25 +580,35 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     // Which mask buffer a segment uses: segments that need masks alternate between the two
     // buffers; the parent copies, the mask builds and the computation each count them.
     int gen_cpy = 0, gen_bld = 0, gen_use = 0;
-    int prev_fresh_c = 0, prev_fresh_u = 0;   // last segment start seen by the copies / by the computation
     const uint32_t *anc = s_anc;
 
-    // prologue: tiles 0 and 1 (with the parent pointers their segments need), the first query rows
+    // One item of the list into a ring stage (RB = 4): a query unit, or a tile, preceded by the
+    // parent pointers if the tile starts a segment that reaches its tree.
+    auto issue_item = [&](const CopyLane<D, CW> &cl, int i, unsigned stage_lds) {
+        const TileDesc *d = desc_of(i);
+        const int fl = __builtin_amdgcn_readfirstlane(d->flags);
+        if (fl & kDescQ) {
+            issue_q(__builtin_amdgcn_readfirstlane(d->b), __builtin_amdgcn_readfirstlane(d->hkv), stage_lds);
+        } else {
+            if (fl & kDescMasks) { copy_parents(__builtin_amdgcn_readfirstlane(d->b), gen_cpy & 1); ++gen_cpy; }
+            issue_tile(cl, __builtin_amdgcn_readfirstlane(d->blk[cw >> kQuarterShift]),
+                       __builtin_amdgcn_readfirstlane(d->n_valid), fl, stage_lds);
+        }
+    };
+
+    // prologue: the first kS - 1 items are put in flight
     if (is_copier) {
         const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
-        const int f0 = desc_flags(0);
-        if (kDma && (f0 & kDescMasks)) { copy_parents(desc_b(0), 0); gen_cpy = 1; }
-        issue_tile_at(cl, 0, ring_lds);
-        if (n_iter > 1) {
-            const int f1 = desc_flags(1);
-            if (kDma && (f1 & kDescFresh)) {
-                if (f1 & kDescMasks) { copy_parents(desc_b(1), gen_cpy & 1); ++gen_cpy; }
-                prev_fresh_c = 1;
-            }
-            issue_tile_at(cl, 1, ring_lds + G::kStageBytes);
+        if (kDma) {
+#pragma unroll
+            for (int i = 0; i < kS - 1; ++i)
+                if (i < n_iter) issue_item(cl, i, ring_lds + i * G::kStageBytes);
+        } else {
+            issue_tile_at(cl, 0, ring_lds);
+            if (n_iter > 1) issue_tile_at(cl, 1, ring_lds + G::kStageBytes);
         }
     }
-    if (is_computer) load_q(desc_b(0), desc_hkv(0));
+    if (!kDma) load_q(desc_b(0), desc_hkv(0));
 
     // per-lane LDS offsets of the matrix-core operand reads (relative to the stage)
     int k_rd[G::kKSteps];   // K fragment of k-step kk, key block 0
@@ -800,11 +862,12 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     auto extend_list = [&](int it) {
         if ((it & (kDescSlots / 2 - 1)) == 0 && it > 0 && htid >= 0 && htid < kDescSlots / 2) {
             const int i = it + kDescSlots / 2 + htid;
-            if (i < n_iter) build_desc(p, page_table, seq_lens, s_len, s_pref, lo, n_iter, i, s_desc + (i & (kDescSlots - 1)), bad);
+            if (i < n_iter) write_item(i);
         }
     };
 
-    // LDS byte offsets of the ring stages: tile being computed, next tile, tile being copied
+    // LDS byte offsets of the ring stages (RB = 8, three stages): tile being computed, next
+    // tile, tile being copied
     int st_cur = 0, st_nxt = G::kStageBytes, st_cpy = 2 * G::kStageBytes;
     auto rotate_stages = [&]() {
         const int t = st_cur;
@@ -814,71 +877,49 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     if (kDma && is_copier) {
         // ---------------- wavefronts that only move data (RB = 4) ----------------
         const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
-        // descriptor words of the tile to copy, read one iteration ahead
-        int2 d_cpy = *reinterpret_cast<const int2 *>(&desc_of(2)->n_valid);
-        int d_blk = desc_of(2)->blk[cw >> kQuarterShift];
-        int n_flags = desc_flags(0);   // flags of tile it, then of tile it + 1
+        int n_flags = desc_flags(1);   // flags of item it + 1
         for (int it = 0; it < n_iter; ++it) {
-            const int c_valid = __builtin_amdgcn_readfirstlane(d_cpy.x);
-            const int c_flags = __builtin_amdgcn_readfirstlane(d_cpy.y);
-            const int c_blk = __builtin_amdgcn_readfirstlane(d_blk);
-            const int t_flags = n_flags;
-            const bool last_iter = it + 1 == n_iter;
-            // This wavefront's part of tile `it` has landed once at most its copies of tile
-            // it + 1 are outstanding (copies complete in the order they were issued).
-            if (!last_iter) wait_vmcnt<kCopiesPerTile>(); else wait_vmcnt<0>();
-            __syncthreads();   // tile `it` is complete in LDS; every wavefront is done with tile it - 1
+            // This wavefront's part of item `it` has landed once at most its copies of the items
+            // after it are outstanding (copies complete in the order they were issued).
+            const int ahead = n_iter - 1 - it;
+            if (ahead >= kS - 2) wait_vmcnt<(kS - 2) * kCopiesPerTile>();
+            else if (ahead == 1) wait_vmcnt<kCopiesPerTile>();
+            else wait_vmcnt<0>();
+            __syncthreads();   // item `it` is complete in LDS; every wavefront is done with item it - 1
 
-            d_cpy = *reinterpret_cast<const int2 *>(&desc_of(it + 3)->n_valid);
-            d_blk = desc_of(it + 3)->blk[cw >> kQuarterShift];
-            n_flags = desc_flags(it + 1);
             extend_list(it);
+            // masks of a segment that starts with the next item (its parent pointers were asked
+            // for before copies this wavefront has just waited for)
+            if (ahead >= 1 && (n_flags & kDescMasks)) { build_masks(gen_bld & 1); ++gen_bld; }
+            n_flags = desc_flags(it + 2);
 
-            // masks of the first segment, and of a segment that starts with the next tile (their
-            // parent pointers were asked for before the copies this wavefront has just waited for)
-            if (it == 0 && (t_flags & kDescMasks)) { build_masks(0); gen_bld = 1; }
-            if (!last_iter && (n_flags & kDescMasks)) { build_masks(gen_bld & 1); ++gen_bld; }
-            // only a range that starts inside a tree needs the first masks at once
-            if (it == 0 && (t_flags & kDescMasks) && (t_flags & kDescTree)) __syncthreads();
-
-            if (it + 2 < n_iter) {
-                if (c_flags & kDescFresh) {
-                    const int x = it + 2, xb = desc_b(x);
-                    if (c_flags & kDescMasks) { copy_parents(xb, gen_cpy & 1); ++gen_cpy; }
-                    if (x - prev_fresh_c >= 3) stage_q(xb, desc_hkv(x));
-                    prev_fresh_c = x;
-                }
-                issue_tile(cl, c_blk, c_valid, c_flags, ring_lds + st_cpy);
-            }
-            rotate_stages();
+            // item it + kS - 1 goes into the stage that item it - 1 has left
+            if (it + kS - 1 < n_iter) issue_item(cl, it + kS - 1, ring_lds + ((it + kS - 1) % kS) * G::kStageBytes);
         }
     } else if (kDma) {
         // ---------------- wavefronts that only compute (RB = 4) ----------------
         int2 d_cur = *reinterpret_cast<const int2 *>(&desc_of(0)->n_valid);
         for (int it = 0; it < n_iter; ++it) {
-            const char *stage = ring + st_cur;
+            const char *stage = ring + (it % kS) * G::kStageBytes;
             const int t_valid = __builtin_amdgcn_readfirstlane(d_cur.x);
             const int t_flags = __builtin_amdgcn_readfirstlane(d_cur.y);
             const bool last_iter = it + 1 == n_iter;
             const bool pair_ends = (t_flags & kDescPairEnd) != 0;
-            __syncthreads();   // tile `it` is complete in LDS
+            __syncthreads();   // item `it` is complete in LDS
             d_cur = *reinterpret_cast<const int2 *>(&desc_of(it + 1)->n_valid);
-            if (it == 0 && (t_flags & kDescMasks) && (t_flags & kDescTree)) __syncthreads();
 
+            if (t_flags & kDescQ) {
+                if (wave_active) read_q_stage(stage);
+                continue;
+            }
             if (t_flags & kDescFresh) {
                 reset_state(t_flags);
-                if (it != 0) {
-                    if (it - prev_fresh_u >= 3) read_q_stage();
-                    else load_q(desc_b(it), desc_hkv(it));
-                }
-                prev_fresh_u = it;
                 if (t_flags & kDescMasks) { anc = s_anc + (gen_use & 1) * READER_MAX_T * 4; ++gen_use; }
             }
             if (wave_active) {
                 compute_tile(stage, t_flags, t_valid, [](int) {});
                 if (pair_ends || last_iter) finish_segment(it, pair_ends);
             }
-            rotate_stages();
         }
     } else {
         // ---------------- every wavefront computes and copies (RB = 8) ----------------
@@ -1024,7 +1065,7 @@ template <int D, int RB>
 static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
     using G = Geometry<D, RB == 4 ? 4 : 8>;
     const size_t pref_bytes = ((size_t)(p.B + 1) * sizeof(int) + 15) & ~(size_t)15;
-    const size_t main_lds = (size_t)kStages * G::kStageBytes + (RB == 4 ? (size_t)32 * RB * G::kRowBytes : 0) +
+    const size_t main_lds = (size_t)ring_stages(RB) * G::kStageBytes +
                             2 * READER_MAX_T * 4 * sizeof(uint32_t) + 2 * READER_MAX_T * sizeof(int) +
                             64 * sizeof(float) + 8 * sizeof(int) + kDescSlots * sizeof(TileDesc) + pref_bytes +
                             (p.B <= kMaxLensInLds ? (size_t)p.B * sizeof(int) + 16 : 0);
