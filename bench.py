@@ -2,8 +2,10 @@
 """Benchmark of the draft-tree verification step on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic input:
-reader_tree_attn -> reader_accept_path -> reader_kv_compact, all on one stream,
-inputs resident in HBM before the clock starts.  The metric is tree tokens per
+attention over the draft tree, acceptance of the longest matching path, compaction of
+its rows into the cache (reader_verify_step: the three operations in two kernel launches;
+`--separate-calls` times reader_tree_attn -> reader_accept_path -> reader_kv_compact
+instead), all on one stream, inputs resident in HBM before the clock starts.  The metric is tree tokens per
 second (B * T draft-tree nodes verified per step) together with the achieved HBM
 bandwidth of the attention kernel, which streams the K/V cache and dominates.
 
@@ -42,8 +44,8 @@ def log(*a):
 class StepRunner:
     """Pre-marshalled C-ABI calls for K steps of one workload (no per-step Python marshalling)."""
 
-    def __init__(self, R, torch, w, n_steps):
-        self.R, self.torch, self.w = R, torch, w
+    def __init__(self, R, torch, w, n_steps, fused=True):
+        self.R, self.torch, self.w, self.fused = R, torch, w, fused
         self.lib = R.load()
         dw = R.to_device(w)
         self.dw = dw
@@ -56,7 +58,7 @@ class StepRunner:
         self.n_steps = n_steps
         self.dims = ctypes.byref(dw.dims)
         p = lambda t: ctypes.c_void_p(t.data_ptr())
-        self.attn_args, self.compact_args = [], []
+        self.attn_args, self.compact_args, self.step_args = [], [], []
         ws_bytes = dw.workspace.numel()
         for k in range(n_steps):
             r = k % self.n_copies
@@ -66,6 +68,10 @@ class StepRunner:
                                    p(dw.workspace), ws_bytes, p(dw.status)))
             self.compact_args.append((self.dims, p(dw.k_tree), p(dw.v_tree), p(dw.path), p(dw.accept_len),
                                       p(self.kc[r]), p(self.vc[r]), p(dw.page_table), seq, p(dw.status)))
+            self.step_args.append((self.dims, p(dw.q), p(dw.k_tree), p(dw.v_tree), p(self.kc[r]), p(self.vc[r]),
+                                   p(dw.page_table), seq, p(dw.parents), p(dw.draft_tokens), p(dw.target_tokens),
+                                   p(dw.out), None, p(dw.accept_len), p(dw.path), p(dw.bonus), dw.max_seq_len,
+                                   p(dw.workspace), ws_bytes, p(dw.status)))
         self.accept_args = (self.dims, p(dw.draft_tokens), p(dw.target_tokens), p(dw.parents), p(dw.accept_len),
                             p(dw.path), p(dw.bonus), p(dw.status))
 
@@ -76,17 +82,21 @@ class StepRunner:
         lib = self.lib
         stream = ctypes.c_void_p(self.torch.cuda.current_stream().cuda_stream)
         for k in range(first, first + count):
-            rc = lib.reader_tree_attn(*self.attn_args[k], stream)
-            rc |= lib.reader_accept_path(*self.accept_args, stream)
-            rc |= lib.reader_kv_compact(*self.compact_args[k], stream)
+            if self.fused:
+                rc = lib.reader_verify_step(*self.step_args[k], stream)
+            else:
+                rc = lib.reader_tree_attn(*self.attn_args[k], stream)
+                rc |= lib.reader_accept_path(*self.accept_args, stream)
+                rc |= lib.reader_kv_compact(*self.compact_args[k], stream)
             if rc:
                 raise RuntimeError("library call failed in step %d" % k)
 
 
-def time_workload(R, torch, w, steps, warmup, use_graph=True):
+def time_workload(R, torch, w, steps, warmup, use_graph=True, fused=True):
     total = warmup + steps
-    run = StepRunner(R, torch, w, total)
-    res = {"workload": w.name, "kv_copies_rotated": run.n_copies}
+    run = StepRunner(R, torch, w, total, fused=fused)
+    res = {"workload": w.name, "kv_copies_rotated": run.n_copies,
+           "entry_points": "reader_verify_step" if fused else "reader_tree_attn+reader_accept_path+reader_kv_compact"}
 
     # ---- eager: warmup, then exactly `steps` steps between two synchronisations
     run.run(0, warmup)
@@ -219,6 +229,8 @@ def main():
     ap.add_argument("--other-steps", type=int, default=30)
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="time the three entry points called one after the other instead of the fused step")
     ap.add_argument("--calibration-pass", action="store_true",
                     help="also run a plain elementwise pass of known size (for counter runs)")
     args = ap.parse_args()
@@ -240,7 +252,8 @@ def main():
         calibration_pass(torch)
     log("generating", W.CONFIG_NAMES[args.config])
     w = W.make_config(args.config)
-    head = time_workload(R, torch, w, args.steps, args.warmup, use_graph=not args.no_graph)
+    head = time_workload(R, torch, w, args.steps, args.warmup, use_graph=not args.no_graph,
+                         fused=not args.separate_calls)
     log("headline:", json.dumps(head))
 
     line = {
@@ -258,7 +271,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "T": w.T, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D,
                    "sum_L": int(w.seq_lens.sum()), "page_size": w.page_size,
-                   "launch_mode": head["launch_mode"], "kv_copies_rotated": head["kv_copies_rotated"]},
+                   "launch_mode": head["launch_mode"], "kv_copies_rotated": head["kv_copies_rotated"],
+                   "entry_points": head["entry_points"]},
         "eager_ms_per_step": head["eager_ms_per_step"],
         "graph_ms_per_step": head.get("graph_ms_per_step"),
         "roofline": head["roofline"],
@@ -274,7 +288,8 @@ def main():
             continue
         log("generating", W.CONFIG_NAMES[idx])
         wo = W.make_config(idx)
-        r = time_workload(R, torch, wo, args.other_steps, min(args.warmup, 5), use_graph=not args.no_graph)
+        r = time_workload(R, torch, wo, args.other_steps, min(args.warmup, 5), use_graph=not args.no_graph,
+                          fused=not args.separate_calls)
         others[wo.name] = {"tree_tokens_per_s": r["tree_tokens_per_s"], "ms_per_step": r["ms_per_step"],
                            "launch_mode": r["launch_mode"], "steps": args.other_steps,
                            "kernel_ms": r["roofline"]["kernel_ms"], "bound": r["roofline"]["bound"],

@@ -182,8 +182,31 @@ int reader_kv_compact(const reader_dims *dims,
                       int32_t *seq_lens, int32_t *status, void *stream);
 
 /*
+ * One whole verification step (Algorithm 5: base-model pass over the draft tree, longest
+ * accepted path; Section 4.3 / Algorithm 4: the accepted rows join the cache), with the
+ * arguments, layouts, results and status bits of
+ *     reader_tree_attn -> reader_accept_path -> reader_kv_compact
+ * called in that order on one stream, but in two kernel launches instead of four: the
+ * second launch merges the attention partials, accepts a path per sequence and compacts
+ * it.  target_tokens are an input here too (the base model's tokens come from outside
+ * this library), so the attention output is not consulted by the acceptance.
+ * k_cache, v_cache and seq_lens are read by the attention and then updated by the
+ * compaction.  dims->variant must be 0.  Errors as for the three calls.
+ */
+int reader_verify_step(const reader_dims *dims,
+                       const void *q, const void *k_tree, const void *v_tree,
+                       void *k_cache, void *v_cache,
+                       const int32_t *page_table, int32_t *seq_lens,
+                       const int32_t *parents,
+                       const int32_t *draft_tokens, const int32_t *target_tokens,
+                       void *out, float *lse,
+                       int32_t *accept_len, int32_t *path, int32_t *bonus_token,
+                       int32_t max_seq_len, void *workspace, size_t workspace_bytes,
+                       int32_t *status, void *stream);
+
+/*
  * Measurement hooks for benchmarks (not operations of the method).  While enabled,
- * every reader_tree_attn call records a HIP event pair on `stream` right before and
+ * every reader_tree_attn / reader_verify_step call records a HIP event pair on `stream` right before and
  * right after its main streaming kernel (the merge kernel is outside the pair).
  * reader_profile_collect waits for the recorded events (it synchronises the host with
  * them), adds up the elapsed times of all pairs recorded since the last collect into

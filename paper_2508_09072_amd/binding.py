@@ -26,7 +26,7 @@ STATUS_BAD_PATH = 4
 
 EXPORTS = (
     "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",
-    "reader_tree_attn", "reader_accept_path", "reader_kv_compact",
+    "reader_tree_attn", "reader_accept_path", "reader_kv_compact", "reader_verify_step",
     "reader_profile_enable", "reader_profile_collect",
 )
 
@@ -76,6 +76,8 @@ def load():
     lib.reader_accept_path.argtypes = [dp] + [vp] * 8
     lib.reader_kv_compact.restype = ctypes.c_int
     lib.reader_kv_compact.argtypes = [dp] + [vp] * 10
+    lib.reader_verify_step.restype = ctypes.c_int
+    lib.reader_verify_step.argtypes = [dp] + [vp] * 15 + [i32, vp, ctypes.c_size_t, vp, vp]
     lib.reader_profile_enable.restype = ctypes.c_int
     lib.reader_profile_enable.argtypes = [i32]
     lib.reader_profile_collect.restype = ctypes.c_int
@@ -165,6 +167,20 @@ def reader_kv_compact(dims, k_tree, v_tree, path, accept_len, k_cache, v_cache, 
         _dev(page_table, torch.int32), _dev(seq_lens, torch.int32), _dev(status, torch.int32, optional=True),
         _stream())
     _check(code, "reader_kv_compact")
+
+
+def reader_verify_step(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, draft_tokens,
+                       target_tokens, out, lse, accept_len, path, bonus_token, max_seq_len, workspace, status=None):
+    import torch
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    code = load().reader_verify_step(
+        ctypes.byref(dims), _dev(q, torch.bfloat16), _dev(k_tree, torch.bfloat16), _dev(v_tree, torch.bfloat16),
+        _dev(k_cache, torch.bfloat16), _dev(v_cache, torch.bfloat16), _dev(page_table, torch.int32),
+        _dev(seq_lens, torch.int32), _dev(parents, torch.int32), _dev(draft_tokens, torch.int32),
+        _dev(target_tokens, torch.int32), _dev(out, torch.bfloat16), _dev(lse, torch.float32, optional=True),
+        _dev(accept_len, torch.int32), _dev(path, torch.int32), _dev(bonus_token, torch.int32), int(max_seq_len),
+        _dev(workspace, optional=True), ws_bytes, _dev(status, torch.int32, optional=True), _stream())
+    _check(code, "reader_verify_step")
 
 
 def reader_profile_enable(on: bool) -> None:

@@ -1,111 +1,11 @@
-// Greedy lossless acceptance and accepted-path KV compaction for gfx950.
-//
-// Acceptance (Algorithm 5; Appendix C invariants 2-3): one 64-lane wavefront per
-// sequence.  Each lane owns up to two tree nodes.  A node "matches" when its drafted
-// token equals the base model's token at its parent; the matches of all nodes are
-// gathered with two wavefront ballots.  Every lane then walks its nodes' parent
-// chains to get their ancestor-or-self sets as 128-bit masks; a node is accepted
-// iff its whole set lies inside the match ballot, and its depth is the set's
-// population count minus one.  A wavefront max-reduction over (depth, lowest id)
-// picks the terminal node; the nodes of its ancestor set scatter themselves into
-// `path` at their own depth.
-//
-// Compaction (Section 4.3 / Algorithm 4, applied every step): one workgroup per
-// sequence copies the accepted rows with 128-bit accesses and then bumps seq_lens.
-#include "internal.h"
+// Kernels of reader_accept_path and reader_kv_compact (the device code is in accept_compact.h).
+#include "accept_compact.h"
 
 namespace reader {
 
 __global__ __launch_bounds__(64) void accept_path_kernel(AcceptParams p) {
-    const int b = blockIdx.x;
-    const int lane = threadIdx.x;
-    const int T = p.T;
-    __shared__ int s_par[READER_MAX_T];
-    __shared__ unsigned long long s_term[2];
-
-    const int32_t *par = p.parents + (size_t)b * T;
-    const int32_t *draft = p.draft + (size_t)b * T;
-    const int32_t *target = p.target + (size_t)b * T;
-
-    bool bad_tree = false;
-    bool match[2];
-    int my_target[2];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const int i = lane + 64 * s;
-        match[s] = false;
-        my_target[s] = 0;
-        if (i < T) {
-            int pi = par[i];
-            bool valid = (i == 0) ? (pi == -1) : (pi >= 0 && pi < i);
-            if (!valid) { bad_tree = true; pi = -1; }
-            s_par[i] = pi;
-            my_target[s] = target[i];
-            match[s] = (i == 0) || (valid && draft[i] == target[pi]);
-        }
-    }
-    const unsigned long long m_lo = __ballot(match[0]);
-    const unsigned long long m_hi = __ballot(match[1]);
-    __syncthreads();
-
-    // ancestor-or-self sets by walking the parent chain (at most T steps, always ends)
-    unsigned long long a_lo[2], a_hi[2];
-    int key[2];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const int i = lane + 64 * s;
-        a_lo[s] = 0; a_hi[s] = 0; key[s] = -1;
-        if (i < T) {
-            int t = i;
-            for (int step = 0; step < T && t >= 0; ++step) {
-                if (t < 64) a_lo[s] |= 1ull << t; else a_hi[s] |= 1ull << (t - 64);
-                t = s_par[t];
-            }
-            const bool ok = ((a_lo[s] & ~m_lo) == 0) && ((a_hi[s] & ~m_hi) == 0);
-            const int depth = __popcll(a_lo[s]) + __popcll(a_hi[s]) - 1;
-            if (ok) key[s] = depth * 256 + (255 - i);   // deeper first, then lower node id
-        }
-    }
-    int best = max(key[0], key[1]);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) best = max(best, __shfl_xor(best, off));
-    // the root always qualifies, so best >= 255
-    const int term = 255 - (best & 255);
-    const int depth_term = best >> 8;
-    const int n_out = min(depth_term, p.max_path - 1);
-
-    if (lane == (term & 63)) {
-        const int s = term >> 6;
-        s_term[0] = a_lo[s];
-        s_term[1] = a_hi[s];
-    }
-    __syncthreads();
-    const unsigned long long t_lo = s_term[0], t_hi = s_term[1];
-
-    int32_t *path = p.path + (size_t)b * p.max_path;
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        const int i = lane + 64 * s;
-        if (i < T) {
-            const bool on_path = (s == 0) ? ((t_lo >> lane) & 1ull) : ((t_hi >> lane) & 1ull);
-            if (on_path) {
-                const int depth = __popcll(a_lo[s]) + __popcll(a_hi[s]) - 1;
-                if (depth < p.max_path) path[depth] = i;
-                if (depth == n_out) {
-                    p.accept_len[b] = n_out;
-                    p.bonus[b] = my_target[s];
-                }
-            }
-        }
-    }
-    for (int j = n_out + 1 + lane; j < p.max_path; j += 64) path[j] = -1;
-
-    const bool any_bad_tree = __ballot(bad_tree) != 0ull;
-    if (p.status && lane == 0) {
-        int bits = (any_bad_tree ? READER_STATUS_BAD_TREE : 0) |
-                   (depth_term > n_out ? READER_STATUS_BAD_PATH : 0);
-        if (bits) atomicOr(p.status, bits);
-    }
+    __shared__ AcceptShared sh;
+    accept_path_body(p, blockIdx.x, threadIdx.x, true, sh);
 }
 
 hipError_t launch_accept_path(const AcceptParams &p, hipStream_t stream) {
@@ -115,54 +15,7 @@ hipError_t launch_accept_path(const AcceptParams &p, hipStream_t stream) {
 
 __global__ __launch_bounds__(256) void kv_compact_kernel(CompactParams p) {
     const int b = blockIdx.x;
-    const int tid = threadIdx.x;
-    const int n = p.accept_len[b];
-    const int L = p.seq_lens[b];
-    const int32_t *path = p.path + (size_t)b * p.max_path;
-    const int32_t *pt = p.page_table + (size_t)b * p.max_pages;
-
-    // Every item this sequence would touch is checked before anything is written.
-    int bad = 0;
-    if (n < 0 || n > p.max_path - 1 || L < 0 || (long long)L + n + 1 > (long long)p.max_pages * READER_PAGE_SIZE) {
-        bad = READER_STATUS_BAD_PATH;
-    } else {
-        for (int j = tid; j <= n; j += 256) {
-            const int node = path[j];
-            if (node < 0 || node >= p.T) bad |= READER_STATUS_BAD_PATH;
-            const int page = pt[(L + j) / READER_PAGE_SIZE];
-            if (page < 0 || page >= p.num_pages) bad |= READER_STATUS_BAD_PAGE;
-        }
-    }
-    // the barriers also order every thread's read of seq_lens before its update below
-    const int bad_path = __syncthreads_or(bad & READER_STATUS_BAD_PATH);
-    const int bad_page = __syncthreads_or(bad & READER_STATUS_BAD_PAGE);
-    if (bad_path || bad_page) {
-        if (tid == 0 && p.status)
-            atomicOr(p.status, (bad_path ? READER_STATUS_BAD_PATH : 0) | (bad_page ? READER_STATUS_BAD_PAGE : 0));
-        return;
-    }
-
-    const int chunks_per_head = p.D / 8;                 // 16-byte chunks
-    const int chunks_per_row = p.Hkv * chunks_per_head;  // one position, all kv heads, K or V
-    const int total = (n + 1) * 2 * chunks_per_row;
-    for (int idx = tid; idx < total; idx += 256) {
-        const int j = idx / (2 * chunks_per_row);
-        const int rem = idx - j * 2 * chunks_per_row;
-        const int which = rem / chunks_per_row;
-        const int c = rem - which * chunks_per_row;
-        const int h = c / chunks_per_head;
-        const int dc = c - h * chunks_per_head;
-        const int node = path[j];
-        const int pos = L + j;
-        const long long page = pt[pos / READER_PAGE_SIZE];
-        const int slot = pos % READER_PAGE_SIZE;
-        const size_t src = (((size_t)b * p.T + node) * p.Hkv + h) * p.D + dc * 8;
-        const size_t dst = (((size_t)page * p.Hkv + h) * READER_PAGE_SIZE + slot) * p.D + dc * 8;
-        const uint16_t *tree = which ? p.v_tree : p.k_tree;
-        uint16_t *cache = which ? p.v_cache : p.k_cache;
-        *reinterpret_cast<uint4 *>(cache + dst) = *reinterpret_cast<const uint4 *>(tree + src);
-    }
-    if (tid == 0) p.seq_lens[b] = L + n + 1;
+    kv_compact_body(p, b, threadIdx.x, p.accept_len[b], p.path + (size_t)b * p.max_path);
 }
 
 hipError_t launch_kv_compact(const CompactParams &p, hipStream_t stream) {

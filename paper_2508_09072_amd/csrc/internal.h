@@ -31,7 +31,9 @@ struct AttnParams {
     const int32_t *page_table, *seq_lens, *parents;
     uint16_t *out;
     float *lse;
-    float *workspace;  // partial records, see attn_slot_floats()
+    float *workspace;  // partial records, see attn_slot_floats() (behind the header, see attn_header_bytes())
+    int32_t *pair_info;      // header: per (sequence, kv head) the first and the last workgroup that hold its tiles
+    long long *total_units;  // header: number of tiles of the whole launch
     int32_t *status;
     int32_t B, T, Hq, Hkv, D, G, M;       // G = Hq/Hkv, M = T*G query rows per (sequence, kv head)
     int32_t max_pages, max_seq_len;
@@ -47,12 +49,22 @@ struct AttnParams {
 // record's own sum), then the rows' running maxima and running sums as fp32.
 __host__ __device__ inline size_t attn_slot_floats(int D, int rows) { return (size_t)rows * (size_t)(D / 2 + 2); }
 
+// The workspace starts with a header the main kernel leaves for the merge kernel: the tile
+// total (8 bytes, padded to 16), then two ints per (sequence, kv head).
+__host__ __device__ inline size_t attn_header_bytes(int B, int Hkv) {
+    return ((size_t)16 + (size_t)B * (size_t)Hkv * 8 + 255) & ~(size_t)255;
+}
+
 // Number of range workgroups the planner picks; a pure function of the dims so that
 // reader_workspace_bytes and the launch agree.
 int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len);
 
-// ev_start / ev_stop: optional events recorded around the main kernel only.
-hipError_t launch_tree_attn_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
+struct AcceptParams;
+struct CompactParams;
+// ev_start / ev_stop: optional events recorded around the main kernel only.  With `ap` and
+// `cp` the second launch also accepts a path per sequence and compacts it (the fused step).
+hipError_t launch_tree_attn_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop,
+                                 const AcceptParams *ap = nullptr, const CompactParams *cp = nullptr);
 hipError_t launch_tree_attn_scalar(const AttnParams &p, hipStream_t stream);
 
 struct AcceptParams {

@@ -119,30 +119,34 @@ extern "C" size_t reader_workspace_bytes(const reader_dims *dims, int32_t max_se
     if (dims->B == 0) return 256;
     size_t slots = 2 * (size_t)attn_plan_ranges(*dims, max_seq_len) * (size_t)row_chunks(*dims);
     size_t bytes = slots * attn_slot_floats(dims->D, attn_rows_per_wg(dims->T * (dims->Hq / dims->Hkv))) * sizeof(float);
-    return (bytes + 255) & ~(size_t)255;
+    return attn_header_bytes(dims->B, dims->Hkv) + ((bytes + 255) & ~(size_t)255);
 }
 
-extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const void *k_tree,
-                                const void *v_tree, const void *k_cache, const void *v_cache,
-                                const int32_t *page_table, const int32_t *seq_lens,
-                                const int32_t *parents, void *out, float *lse, int32_t max_seq_len,
-                                void *workspace, size_t workspace_bytes, int32_t *status,
-                                void *stream) {
+// Argument checks and kernel parameters of the attention step (shared by reader_tree_attn and
+// reader_verify_step).  Returns READER_OK and fills `p`, or an error code; *empty is set when
+// there is nothing to do.
+static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tree, const void *v_tree,
+                        const void *k_cache, const void *v_cache, const int32_t *page_table,
+                        const int32_t *seq_lens, const int32_t *parents, void *out, float *lse,
+                        int32_t max_seq_len, void *workspace, int32_t *status, AttnParams &p, bool *empty) {
     int err = 0;
+    *empty = false;
     if (!dims_ok(dims, &err)) return err;
     if (max_seq_len < 0) return READER_EINVAL;
-    if (dims->B == 0) return READER_OK;
+    if (dims->B == 0) { *empty = true; return READER_OK; }
     if (!q || !k_tree || !v_tree || !k_cache || !v_cache || !page_table || !seq_lens || !parents || !out)
         return READER_EINVAL;
     if ((long long)dims->max_pages_per_seq * dims->page_size < max_seq_len) return READER_EINVAL;
     if (max_seq_len > 0 && (dims->num_pages < 1 || dims->max_pages_per_seq < 1)) return READER_EINVAL;
     if (dims->variant != 0 && dims->variant != 1) return READER_EINVAL;
 
-    AttnParams p;
     p.q = (const uint16_t *)q; p.k_tree = (const uint16_t *)k_tree; p.v_tree = (const uint16_t *)v_tree;
     p.k_cache = (const uint16_t *)k_cache; p.v_cache = (const uint16_t *)v_cache;
     p.page_table = page_table; p.seq_lens = seq_lens; p.parents = parents;
-    p.out = (uint16_t *)out; p.lse = lse; p.workspace = (float *)workspace; p.status = status;
+    p.out = (uint16_t *)out; p.lse = lse; p.status = status;
+    p.total_units = (long long *)workspace;
+    p.pair_info = workspace ? (int32_t *)((char *)workspace + 16) : nullptr;
+    p.workspace = workspace ? (float *)((char *)workspace + attn_header_bytes(dims->B, dims->Hkv)) : nullptr;
     p.B = dims->B; p.T = dims->T; p.Hq = dims->Hq; p.Hkv = dims->Hkv; p.D = dims->D;
     p.G = dims->Hq / dims->Hkv; p.M = p.T * p.G;
     p.max_pages = dims->max_pages_per_seq; p.max_seq_len = max_seq_len;
@@ -153,7 +157,39 @@ extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const vo
     p.num_pages = dims->num_pages;
     float scale = dims->sm_scale > 0.f ? dims->sm_scale : 1.0f / sqrtf((float)dims->D);
     p.scale_log2 = scale * 1.44269504088896340736f;
+    return READER_OK;
+}
 
+static void accept_fill(const reader_dims *dims, const int32_t *draft_tokens, const int32_t *target_tokens,
+                        const int32_t *parents, int32_t *accept_len, int32_t *path, int32_t *bonus_token,
+                        int32_t *status, AcceptParams &p) {
+    p.draft = draft_tokens; p.target = target_tokens; p.parents = parents;
+    p.accept_len = accept_len; p.path = path; p.bonus = bonus_token; p.status = status;
+    p.B = dims->B; p.T = dims->T; p.max_path = dims->max_path;
+}
+
+static void compact_fill(const reader_dims *dims, const void *k_tree, const void *v_tree, const int32_t *path,
+                         const int32_t *accept_len, void *k_cache, void *v_cache, const int32_t *page_table,
+                         int32_t *seq_lens, int32_t *status, CompactParams &p) {
+    p.k_tree = (const uint16_t *)k_tree; p.v_tree = (const uint16_t *)v_tree;
+    p.path = path; p.accept_len = accept_len; p.page_table = page_table;
+    p.k_cache = (uint16_t *)k_cache; p.v_cache = (uint16_t *)v_cache;
+    p.seq_lens = seq_lens; p.status = status;
+    p.B = dims->B; p.T = dims->T; p.Hkv = dims->Hkv; p.D = dims->D;
+    p.max_pages = dims->max_pages_per_seq; p.max_path = dims->max_path; p.num_pages = dims->num_pages;
+}
+
+extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const void *k_tree,
+                                const void *v_tree, const void *k_cache, const void *v_cache,
+                                const int32_t *page_table, const int32_t *seq_lens,
+                                const int32_t *parents, void *out, float *lse, int32_t max_seq_len,
+                                void *workspace, size_t workspace_bytes, int32_t *status,
+                                void *stream) {
+    AttnParams p;
+    bool empty = false;
+    const int rc = attn_prepare(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, out, lse,
+                                max_seq_len, workspace, status, p, &empty);
+    if (rc != READER_OK || empty) return rc;
     hipError_t e;
     if (dims->variant == 1) {
         e = launch_tree_attn_scalar(p, (hipStream_t)stream);
@@ -165,6 +201,30 @@ extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const vo
         e = launch_tree_attn_mfma(p, (hipStream_t)stream, ev_a, ev_b);
     }
     return e == hipSuccess ? READER_OK : READER_EHIP;
+}
+
+extern "C" int reader_verify_step(const reader_dims *dims, const void *q, const void *k_tree, const void *v_tree,
+                                  void *k_cache, void *v_cache, const int32_t *page_table, int32_t *seq_lens,
+                                  const int32_t *parents, const int32_t *draft_tokens,
+                                  const int32_t *target_tokens, void *out, float *lse, int32_t *accept_len,
+                                  int32_t *path, int32_t *bonus_token, int32_t max_seq_len, void *workspace,
+                                  size_t workspace_bytes, int32_t *status, void *stream) {
+    AttnParams p;
+    bool empty = false;
+    const int rc = attn_prepare(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, out, lse,
+                                max_seq_len, workspace, status, p, &empty);
+    if (rc != READER_OK || empty) return rc;
+    if (!draft_tokens || !target_tokens || !accept_len || !path || !bonus_token) return READER_EINVAL;
+    if (dims->variant != 0) return READER_EINVAL;   // the fused step exists for the matrix-core kernel only
+    if (!workspace || ((uintptr_t)workspace & 255) != 0) return READER_EWORKSPACE;
+    if (workspace_bytes < reader_workspace_bytes(dims, max_seq_len)) return READER_EWORKSPACE;
+    AcceptParams ap;
+    CompactParams cp;
+    accept_fill(dims, draft_tokens, target_tokens, parents, accept_len, path, bonus_token, status, ap);
+    compact_fill(dims, k_tree, v_tree, path, accept_len, k_cache, v_cache, page_table, seq_lens, status, cp);
+    hipEvent_t ev_a, ev_b;
+    profile_next(&ev_a, &ev_b);
+    return launch_tree_attn_mfma(p, (hipStream_t)stream, ev_a, ev_b, &ap, &cp) == hipSuccess ? READER_OK : READER_EHIP;
 }
 
 extern "C" int reader_profile_enable(int32_t on) {
@@ -203,9 +263,7 @@ extern "C" int reader_accept_path(const reader_dims *dims, const int32_t *draft_
     if (!draft_tokens || !target_tokens || !parents || !accept_len || !path || !bonus_token)
         return READER_EINVAL;
     AcceptParams p;
-    p.draft = draft_tokens; p.target = target_tokens; p.parents = parents;
-    p.accept_len = accept_len; p.path = path; p.bonus = bonus_token; p.status = status;
-    p.B = dims->B; p.T = dims->T; p.max_path = dims->max_path;
+    accept_fill(dims, draft_tokens, target_tokens, parents, accept_len, path, bonus_token, status, p);
     return launch_accept_path(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }
 
@@ -219,11 +277,6 @@ extern "C" int reader_kv_compact(const reader_dims *dims, const void *k_tree, co
     if (!k_tree || !v_tree || !path || !accept_len || !k_cache || !v_cache || !page_table || !seq_lens)
         return READER_EINVAL;
     CompactParams p;
-    p.k_tree = (const uint16_t *)k_tree; p.v_tree = (const uint16_t *)v_tree;
-    p.path = path; p.accept_len = accept_len; p.page_table = page_table;
-    p.k_cache = (uint16_t *)k_cache; p.v_cache = (uint16_t *)v_cache;
-    p.seq_lens = seq_lens; p.status = status;
-    p.B = dims->B; p.T = dims->T; p.Hkv = dims->Hkv; p.D = dims->D;
-    p.max_pages = dims->max_pages_per_seq; p.max_path = dims->max_path; p.num_pages = dims->num_pages;
+    compact_fill(dims, k_tree, v_tree, path, accept_len, k_cache, v_cache, page_table, seq_lens, status, p);
     return launch_kv_compact(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }

@@ -36,6 +36,7 @@
 // in flight while one is consumed; one barrier per tile.  16-byte chunks are XOR-swizzled
 // inside a tile row (applied on the global-address side of the copy) so that operand reads
 // hit every LDS bank once.
+#include "accept_compact.h"
 #include "internal.h"
 
 namespace reader {
@@ -206,7 +207,13 @@ __device__ inline void build_desc(const AttnParams &p, const int32_t *table, con
         flags = kDescTree | (tt << 8);
         blk[0] = blk[1] = blk[2] = blk[3] = (b * p.T + tt * kTile) * p.Hkv + hkv;
     }
-    if (idx == 0) flags |= kDescPairStart;
+    if (idx == 0) {
+        flags |= kDescPairStart;
+        // for the merge kernel: which workgroups hold tiles of this pair
+        const long long U = (long long)p.Hkv * s_pref[p.B];
+        int2 *info = reinterpret_cast<int2 *>(p.pair_info) + (b * p.Hkv + hkv);
+        *info = make_int2((int)blockIdx.x, range_of_unit(x + n_units - 1, U, p.n_ranges));
+    }
     if (idx + 1 == n_units) flags |= kDescPairEnd;
     if (idx == 0 || i == 0) {
         flags |= kDescFresh;
@@ -471,6 +478,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         wait_vmcnt<0>();
         __syncthreads();   // the copy of the page table is complete (every wavefront reaches this)
     }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *p.total_units = U;
     if (lo >= hi) return;
     const int n_tiles = (int)(hi - lo);
     // items of the list: the tiles, and with dedicated copy wavefronts one query unit per segment
@@ -989,66 +997,58 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
 
 // Merge the partial records of every pair that was cut between workgroups.
 // A record holds [D / 8 chunks][rows][8 bf16] of output normalised by the record's own sum, then
-// the rows' running maxima, then their running sums.  One thread takes one 8-wide chunk of one query row:
-// D / 8 threads per row, 256 / (D / 8) rows per workgroup; grid = (B * Hkv, rows / that).
+// the rows' running maxima, then their running sums.  One thread takes one 8-wide chunk of one
+// query row: D / 8 threads per row, 256 / (D / 8) rows per workgroup; grid = (B * Hkv, rows / that).
+// Which workgroups hold a pair's records, and the tile total that tells an empty range, come
+// from the header the main kernel wrote.
 template <int D>
-__global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnParams p, const int32_t *__restrict__ seq_lens) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    int *s_pref = reinterpret_cast<int *>(smem);
-    __shared__ int s_wsum[8];
-    scan_units(p, seq_lens, s_pref, s_wsum);
-
-    const int pair = blockIdx.x, b = pair / p.Hkv, hkv = pair - b * p.Hkv;
-    const int n_units = s_pref[b + 1] - s_pref[b];
-    const long long U = (long long)p.Hkv * s_pref[p.B];
-    const long long start = (long long)p.Hkv * s_pref[b] + (long long)hkv * n_units;
-    const int w_first = range_of_unit(start, U, p.n_ranges);
-    const int w_last = range_of_unit(start + n_units - 1, U, p.n_ranges);
+__device__ inline void merge_body(const AttnParams &p, int pair, int block_y) {
+    const int b = pair / p.Hkv, hkv = pair - b * p.Hkv;
+    const int2 info = reinterpret_cast<const int2 *>(p.pair_info)[pair];
+    const int w_first = info.x, w_last = info.y;
     if (w_first == w_last) return;   // finished in place by one workgroup
+    const long long U = *p.total_units;
 
     constexpr int kC = D / 8;                   // chunks (threads) per row
     constexpr int kRowsPerBlock = 256 / kC;
     const int tid = threadIdx.x;
     const int blocks_per_chunk = p.rows_per_wg / kRowsPerBlock;
-    const int row_chunk = blockIdx.y / blocks_per_chunk;
-    const int row_local = (blockIdx.y - row_chunk * blocks_per_chunk) * kRowsPerBlock + tid / kC, c = tid % kC;
+    const int row_chunk = block_y / blocks_per_chunk;
+    const int row_local = (block_y - row_chunk * blocks_per_chunk) * kRowsPerBlock + tid / kC, c = tid % kC;
     const int m_row = row_chunk * p.rows_per_wg + row_local;
     if (m_row >= p.M) return;
     const int node = m_row / p.G, group = m_row - node * p.G;
     const size_t rows = p.rows_per_wg;
     const size_t rec_floats = attn_slot_floats(D, p.rows_per_wg);
 
-    // Ranges that hold no unit (more workgroups than units) wrote no record.
-    auto empty = [&](int w) { return range_begin(w, U, p.n_ranges) >= range_begin(w + 1, U, p.n_ranges); };
-    auto record = [&](int w) -> const float * {
-        const size_t slot = ((size_t)(2 * w + (w == w_first ? 1 : 0)) * p.n_row_chunks + row_chunk);
-        return p.workspace + slot * rec_floats;
-    };
-
-    float m_all = -INFINITY;
-    for (int w = w_first; w <= w_last; ++w)
-        if (!empty(w)) m_all = fmaxf(m_all, record(w)[rows * (D / 2) + row_local]);
-    // m_all is finite: every query row sees at least its own tree node
-
+    // online merge: every part's loads are independent of the other parts' values
+    float m_all = -INFINITY, l_all = 0.f;
     float acc[8];
 #pragma unroll
     for (int d = 0; d < 8; ++d) acc[d] = 0.f;
-    float l_all = 0.f;
+#pragma unroll 2
     for (int w = w_first; w <= w_last; ++w) {
-        if (empty(w)) continue;
-        const float *rec = record(w);
+        // a range that holds no tile (more workgroups than tiles) wrote no record
+        if (range_begin(w, U, p.n_ranges) >= range_begin(w + 1, U, p.n_ranges)) continue;
+        const size_t slot = ((size_t)(2 * w + (w == w_first ? 1 : 0)) * p.n_row_chunks + row_chunk);
+        const float *rec = p.workspace + slot * rec_floats;
         const float mw = rec[rows * (D / 2) + row_local];
-        if (mw == -INFINITY) continue;
-        const float f = __builtin_amdgcn_exp2f(mw - m_all) * rec[rows * (D / 2 + 1) + row_local];
-        l_all += f;
+        const float lw = rec[rows * (D / 2 + 1) + row_local];
         const uint4 v = reinterpret_cast<const uint4 *>(rec)[(size_t)c * rows + row_local];
+        if (mw == -INFINITY) continue;   // this row saw no key of that part
+        const float m_new = fmaxf(m_all, mw);
+        const float fa = __builtin_amdgcn_exp2f(m_all - m_new);      // 0 for the first part
+        const float fb = __builtin_amdgcn_exp2f(mw - m_new) * lw;
         const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            acc[2 * e] += f * __uint_as_float(u[e] << 16);
-            acc[2 * e + 1] += f * __uint_as_float(u[e] & 0xffff0000u);
+            acc[2 * e] = acc[2 * e] * fa + fb * __uint_as_float(u[e] << 16);
+            acc[2 * e + 1] = acc[2 * e + 1] * fa + fb * __uint_as_float(u[e] & 0xffff0000u);
         }
+        l_all = l_all * fa + fb;
+        m_all = m_new;
     }
+    // l_all > 0: every query row sees at least its own tree node
     const float inv = 1.f / l_all;
     uint16_t *orow = p.out + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D + c * 8;
     uint4 w;
@@ -1061,8 +1061,32 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnParams p, cons
         p.lse[((size_t)b * p.Hq + hkv * p.G + group) * p.T + node] = (m_all + __builtin_amdgcn_logf(l_all)) * kLn2;
 }
 
+template <int D>
+__global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnParams p) {
+    merge_body<D>(p, blockIdx.x, blockIdx.y);
+}
+
+// Tail of the fused step: the merge blocks, then one workgroup per sequence that accepts a
+// path and appends its rows to the cache.  The three jobs touch disjoint data (the merge reads
+// the workspace and writes `out`; acceptance reads tokens; compaction writes cache slots past
+// the old lengths and the lengths themselves, which the merge does not read).
+template <int D>
+__global__ __launch_bounds__(256) void verify_tail_kernel(AttnParams p, AcceptParams ap, CompactParams cp,
+                                                           int n_merge_blocks, int merge_blocks_y) {
+    if ((int)blockIdx.x < n_merge_blocks) {
+        merge_body<D>(p, blockIdx.x / merge_blocks_y, blockIdx.x % merge_blocks_y);
+        return;
+    }
+    __shared__ AcceptShared sh;
+    const int b = blockIdx.x - n_merge_blocks, tid = threadIdx.x;
+    accept_path_body(ap, b, tid, tid < 64, sh);
+    __syncthreads();
+    kv_compact_body(cp, b, tid, sh.accept_len, sh.path);
+}
+
 template <int D, int RB>
-static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop,
+                              const AcceptParams *ap, const CompactParams *cp) {
     using G = Geometry<D, RB == 4 ? 4 : 8>;
     const size_t pref_bytes = ((size_t)(p.B + 1) * sizeof(int) + 15) & ~(size_t)15;
     const size_t main_lds = (size_t)ring_stages(RB) * G::kStageBytes +
@@ -1084,15 +1108,23 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
     hipError_t e = hipGetLastError();
     if (ev_stop) (void)hipEventRecord(ev_stop, stream);
     if (e != hipSuccess) return note_hip_error("launch tree_attn_mfma_kernel", e);
-    hipLaunchKernelGGL(tree_attn_merge_kernel<D>, dim3(p.B * p.Hkv, p.n_row_chunks * (p.rows_per_wg / (256 / (D / 8)))), dim3(256),
-                       pref_bytes, stream, p, p.seq_lens);
+    const int merge_y = p.n_row_chunks * (p.rows_per_wg / (256 / (D / 8)));
+    if (ap && cp) {
+        const int n_merge = p.B * p.Hkv * merge_y;
+        hipLaunchKernelGGL(verify_tail_kernel<D>, dim3(n_merge + p.B), dim3(256), 0, stream, p, *ap, *cp, n_merge, merge_y);
+        return note_hip_error("launch verify_tail_kernel", hipGetLastError());
+    }
+    hipLaunchKernelGGL(tree_attn_merge_kernel<D>, dim3(p.B * p.Hkv, merge_y), dim3(256), 0, stream, p);
     return note_hip_error("launch tree_attn_merge_kernel", hipGetLastError());
 }
 
-hipError_t launch_tree_attn_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+hipError_t launch_tree_attn_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop,
+                                 const AcceptParams *ap, const CompactParams *cp) {
     if (p.rows_per_wg == 128)
-        return p.D == 64 ? launch_mfma<64, 4>(p, stream, ev_start, ev_stop) : launch_mfma<128, 4>(p, stream, ev_start, ev_stop);
-    return p.D == 64 ? launch_mfma<64, 8>(p, stream, ev_start, ev_stop) : launch_mfma<128, 8>(p, stream, ev_start, ev_stop);
+        return p.D == 64 ? launch_mfma<64, 4>(p, stream, ev_start, ev_stop, ap, cp)
+                         : launch_mfma<128, 4>(p, stream, ev_start, ev_stop, ap, cp);
+    return p.D == 64 ? launch_mfma<64, 8>(p, stream, ev_start, ev_stop, ap, cp)
+                     : launch_mfma<128, 8>(p, stream, ev_start, ev_stop, ap, cp);
 }
 
 }  // namespace reader

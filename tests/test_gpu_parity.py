@@ -273,3 +273,45 @@ def test_whole_step_then_next_step_attention(R, oracle_mod, index, scale):
                        dw.seq_lens, dw.parents, dw.out, dw.lse, int(sl.max()), dw.workspace, dw.status)
     torch.cuda.synchronize()
     assert_close(bf16_to_np(dw.out), ref, what="second step")
+
+
+# ---------------------------------------------------------------- fused step (two launches)
+
+@pytest.mark.parametrize("index,scale", [(0, 1.0), (1, 0.1), (2, 0.1), (2, 1.0), (3, 0.02), (4, 0.05)])
+def test_verify_step_equals_the_three_calls_and_the_oracle(R, oracle_mod, index, scale):
+    import torch
+    w = W.make_config(index, length_scale=scale)
+    # the three entry points, one after the other
+    dw3 = run_step(R, w)
+    # the fused entry point on a fresh upload of the same workload
+    dw = R.to_device(w)
+    R.reader_verify_step(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table, dw.seq_lens,
+                         dw.parents, dw.draft_tokens, dw.target_tokens, dw.out, dw.lse, dw.accept_len, dw.path,
+                         dw.bonus, dw.max_seq_len, dw.workspace, dw.status)
+    torch.cuda.synchronize()
+    assert int(dw.status.item()) == 0
+    for name in ("out", "lse", "accept_len", "path", "bonus", "seq_lens"):
+        a, b = getattr(dw, name), getattr(dw3, name)
+        assert torch.equal(a, b), "fused step differs from the three calls in " + name
+    for name in ("k_cache", "v_cache"):   # bit patterns: unused slots hold NaN canaries
+        assert np.array_equal(cache_bits(getattr(dw, name)), cache_bits(getattr(dw3, name))), name
+    # and against the oracle
+    ref, _ = oracle_mod.tree_attn(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table, w.seq_lens, w.parents)
+    assert_close(bf16_to_np(dw.out), ref, what="fused step attention")
+    al, path, bonus, kc, vc, sl = oracle_step(oracle_mod, w)
+    assert np.array_equal(dw.accept_len.cpu().numpy(), al) and np.array_equal(dw.bonus.cpu().numpy(), bonus)
+    assert np.array_equal(dw.path.cpu().numpy(), path)
+    assert np.array_equal(dw.seq_lens.cpu().numpy(), sl)
+    assert np.array_equal(cache_bits(dw.k_cache), kc) and np.array_equal(cache_bits(dw.v_cache), vc)
+
+
+def test_verify_step_rejects_bad_arguments(R):
+    import torch
+    w = W.make_config(0)
+    dw = R.to_device(w)
+    with pytest.raises(R.ReaderError):   # workspace too small
+        R.reader_verify_step(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table, dw.seq_lens,
+                             dw.parents, dw.draft_tokens, dw.target_tokens, dw.out, dw.lse, dw.accept_len, dw.path,
+                             dw.bonus, dw.max_seq_len, dw.workspace[:256], dw.status)
+    torch.cuda.synchronize()
+    assert int(dw.status.item()) == 0 and torch.equal(dw.seq_lens.cpu(), torch.from_numpy(w.seq_lens))

@@ -77,6 +77,7 @@ def test_bad_dims_are_refused_on_the_host(R, change, code):
     assert lib.reader_tree_attn(ctypes.byref(d), *null, 0, None, 0, None, None) == code
     assert lib.reader_accept_path(ctypes.byref(d), *[None] * 8) == code
     assert lib.reader_kv_compact(ctypes.byref(d), *[None] * 10) == code
+    assert lib.reader_verify_step(ctypes.byref(d), *[None] * 15, 0, None, 0, None, None) == code
 
 
 def test_null_pointers_and_workspace_are_refused(R):
@@ -95,6 +96,13 @@ def test_null_pointers_and_workspace_are_refused(R):
     assert lib.reader_tree_attn(ctypes.byref(d0), *[None] * 10, 0, None, 0, None, None) == R.READER_OK
     assert lib.reader_accept_path(ctypes.byref(d0), *[None] * 8) == R.READER_OK
     assert lib.reader_kv_compact(ctypes.byref(d0), *[None] * 10) == R.READER_OK
+    assert lib.reader_verify_step(ctypes.byref(d0), *[None] * 15, 0, None, 0, None, None) == R.READER_OK
+    # the fused step checks what the three calls check
+    assert lib.reader_verify_step(ctypes.byref(d), *[None] * 15, 128, None, 0, None, None) == R.READER_EINVAL
+    assert lib.reader_verify_step(ctypes.byref(d), *[one] * 8, None, one, one, None, one, one, one, 128, one, 1 << 40,
+                                  None, None) == R.READER_EINVAL            # draft tokens missing
+    assert lib.reader_verify_step(ctypes.byref(d), *[one] * 11, None, one, one, one, 128, one, 16, None, None) \
+        == R.READER_EWORKSPACE
 
 
 def test_binding_refuses_cpu_tensors(R):
