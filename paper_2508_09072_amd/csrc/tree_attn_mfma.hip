@@ -683,75 +683,22 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         }
         between(0);
 
-        // V^T fragments, as the two transposed reads of each (16-key step, output block).  A
-        // wavefront that has a SIMD to itself asks for all of them now, so that they arrive
-        // during the softmax; with two wavefronts per SIMD (and fewer registers to spare) the
-        // reads of a step are issued one step ahead of its products.
-        constexpr int kVSlots = kDma ? 4 : 2;
-        s16x4 vh[kVSlots][G::kOBlocks][2];
+        // V^T fragments, as the two transposed reads of each (16-key step, output block); the
+        // reads of a step are issued one step ahead of its products (asking for all of them
+        // before the softmax costs more in registers than it saves in waiting).
+        s16x4 vh[2][G::kOBlocks][2];
         auto read_v_step = [&](int ks) {
             const int key_base = ((ks >> 1) * 32 + (ks & 1) * 16) * G::kRowBytes;
 #pragma unroll
             for (int db = 0; db < G::kOBlocks; ++db) {
                 const char *src = stage + v_rd[db] + key_base;
-                vh[ks % kVSlots][db][0] = lds_read_tr16(src);                         // keys +0..3 (+4h)
-                vh[ks % kVSlots][db][1] = lds_read_tr16(src + 8 * G::kRowBytes);      // keys +8..11 (+4h)
+                vh[ks & 1][db][0] = lds_read_tr16(src);                         // keys +0..3 (+4h)
+                vh[ks & 1][db][1] = lds_read_tr16(src + 8 * G::kRowBytes);      // keys +8..11 (+4h)
             }
         };
-        if (kDma) {
-            __builtin_amdgcn_sched_barrier(0);   // not before the K fragments are consumed: registers
-            read_v_step(0);
-            read_v_step(1);
-            read_v_step(2);
-            read_v_step(3);
-            __builtin_amdgcn_sched_barrier(0);
-        }
 
-        // ---- masks (ragged last prefix tile, tree tiles) ----
-        if (is_tree) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                uint32_t bits = row_real ? anc[node * 4 + tt * 2 + kb] : 0u;
-                bits >>= 4 * h;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int r = (i >> 2) * 8 + (i & 3);    // + 4h, already shifted out
-                    if (!((bits >> r) & 1u)) s[kb][i] = -INFINITY;
-                }
-            }
-        } else if (n_valid < kTile) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int key = kb * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
-                    if (key >= n_valid) s[kb][i] = -INFINITY;
-                }
-        }
-        // ---- online softmax along the keys (all values of a lane share one query row) ----
-        float mx0 = fmaxf(s[0][0], s[0][1]), mx1 = fmaxf(s[1][0], s[1][1]);
-#pragma unroll
-        for (int i = 2; i < 16; i += 2) {
-            mx0 = fmaxf(fmaxf(mx0, s[0][i]), s[0][i + 1]);
-            mx1 = fmaxf(fmaxf(mx1, s[1][i]), s[1][i + 1]);
-        }
-        float mx = fmaxf(mx0, mx1);
-        {   // the other half of the row's keys sits in lane ^ 32
-            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-            mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        }
-        const bool grow = mx > m_run + grow_margin;     // also the first finite maximum (m_run = -inf)
-        if (__any(grow)) {
-            const float alpha = grow ? __builtin_amdgcn_exp2f((m_run - mx) * c2) : 1.f;   // m_run = -inf gives 0
-            m_run = grow ? mx : m_run;
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < G::kOBlocks; ++db)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-        }
-        between(1);
-        {
+        // softmax weights of the tile relative to the running reference -> pk; returns the lane's sum
+        auto weights = [&]() {
             const float mc = (m_run == -INFINITY) ? 0.f : m_run * c2;
             float lsum0 = 0.f, lsum1 = 0.f;
 #pragma unroll
@@ -764,7 +711,65 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                     lsum1 += p1;
                     pk[kb][i >> 1] = pack_bf16x2(p0, p1);
                 }
-            l_run += lsum0 + lsum1;
+            return lsum0 + lsum1;
+        };
+        // A whole prefix tile that does not start a segment: every row already has a finite
+        // reference, so the weights are taken against it right away, without looking for the
+        // row maximum first; only if some weight comes out huge (a score far above the
+        // reference) is the tile redone the careful way.  bf16 and fp32 share the exponent
+        // range, so large weights lose nothing.
+        bool careful = is_tree || n_valid < kTile || (flags & kDescFresh);
+        if (!careful) {
+            const float lsum = weights();
+            if (__any(!(lsum < 0x1p40f))) careful = true;
+            else l_run += lsum;
+        }
+        between(1);
+        if (careful) {
+            // ---- masks (ragged last prefix tile, tree tiles) ----
+            if (is_tree) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    uint32_t bits = row_real ? anc[node * 4 + tt * 2 + kb] : 0u;
+                    bits >>= 4 * h;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int r = (i >> 2) * 8 + (i & 3);    // + 4h, already shifted out
+                        if (!((bits >> r) & 1u)) s[kb][i] = -INFINITY;
+                    }
+                }
+            } else if (n_valid < kTile) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = kb * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
+                        if (key >= n_valid) s[kb][i] = -INFINITY;
+                    }
+            }
+            // ---- online softmax along the keys (all values of a lane share one query row) ----
+            float mx0 = fmaxf(s[0][0], s[0][1]), mx1 = fmaxf(s[1][0], s[1][1]);
+#pragma unroll
+            for (int i = 2; i < 16; i += 2) {
+                mx0 = fmaxf(fmaxf(mx0, s[0][i]), s[0][i + 1]);
+                mx1 = fmaxf(fmaxf(mx1, s[1][i]), s[1][i + 1]);
+            }
+            float mx = fmaxf(mx0, mx1);
+            {   // the other half of the row's keys sits in lane ^ 32
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
+            const bool grow = mx > m_run + grow_margin;     // also the first finite maximum (m_run = -inf)
+            if (__any(grow)) {
+                const float alpha = grow ? __builtin_amdgcn_exp2f((m_run - mx) * c2) : 1.f;   // m_run = -inf gives 0
+                m_run = grow ? mx : m_run;
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < G::kOBlocks; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+            }
+            l_run += weights();
         }
         between(2);
 
@@ -776,22 +781,15 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             const bf16x8 pb = __builtin_bit_cast(bf16x8, pv);
 #pragma unroll
             for (int db = 0; db < G::kOBlocks; ++db) {
-                const s16x8 a8 = __builtin_shufflevector(vh[ks % kVSlots][db][0], vh[ks % kVSlots][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                const s16x8 a8 = __builtin_shufflevector(vh[ks & 1][db][0], vh[ks & 1][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a8), pb, o[db], 0, 0, 0);
             }
         };
-        if (kDma) {
-            pv_step(0);
-            pv_step(1);
-            pv_step(2);
-            pv_step(3);
-        } else {
-            read_v_step(0);
+        read_v_step(0);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                if (ks + 1 < 4) read_v_step(ks + 1);
-                pv_step(ks);
-            }
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks + 1 < 4) read_v_step(ks + 1);
+            pv_step(ks);
         }
         between(3);
     };
