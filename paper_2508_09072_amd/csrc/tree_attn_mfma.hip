@@ -970,21 +970,24 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             if (pair_ends && !last_iter) prefetch_q(desc_b(it + 1), desc_hkv(it + 1));
 
             // Tile it + 2 is copied into the stage that tile it - 1 has left.  A wavefront stalls on
-            // a copy instruction while the memory pipeline is full, so the copies are spread over
-            // the iteration, each behind a batch of matrix or vector work.
+            // a copy instruction while the memory pipeline is full.  The two wavefronts that share a
+            // SIMD (w and w + 4) are kept out of step by it: one copies before it computes, the other
+            // after, so that one's matrix work tends to run under the other's vector work.
             CopyPlan cp;
             if (copy_next) cp = plan_copy<D, CW>(p, c_blk, c_valid, c_flags, cw);
-            auto copy_part = [&](int part) {   // part 0..3
+            auto copy_all = [&]() {
                 if (copy_next) {
-                    if (kCopiesPerTile == 4) emit_copy<D, CW>(cp, cl, next_stage, cw, part);
-                    else if ((part & 1) == 0) emit_copy<D, CW>(cp, cl, next_stage, cw, part >> 1);
+#pragma unroll
+                    for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D, CW>(cp, cl, next_stage, cw, j);
                 }
             };
             if (wave_active) {
-                compute_tile(stage, t_flags, t_valid, copy_part);
+                if (wave_s >= 4) copy_all();
+                compute_tile(stage, t_flags, t_valid, [](int) {});
+                if (wave_s < 4) copy_all();
                 if (pair_ends || last_iter) finish_segment(it, pair_ends);
             } else {
-                copy_part(0); copy_part(1); copy_part(2); copy_part(3);
+                copy_all();
             }
             rotate_stages();
         }
