@@ -206,8 +206,9 @@ int reader_verify_step(const reader_dims *dims,
 
 /*
  * Measurement hooks for benchmarks (not operations of the method).  While enabled,
- * every reader_tree_attn / reader_verify_step call records a HIP event pair on `stream` right before and
- * right after its main streaming kernel (the merge kernel is outside the pair).
+ * every reader_tree_attn / reader_verify_step call launches its main streaming kernel
+ * with a HIP event pair that takes the kernel's own start and end time stamps (the
+ * second launch of the call is outside the pair).
  * reader_profile_collect waits for the recorded events (it synchronises the host with
  * them), adds up the elapsed times of all pairs recorded since the last collect into
  * *kernel_ms_sum, stores their count in *launches, and forgets them.  The event

@@ -9,33 +9,45 @@
 //   range [w*U/n_ranges, (w+1)*U/n_ranges), so every workgroup moves the same number of
 //   K/V bytes whatever the ragged sequence lengths are.  A range may cover several
 //   whole pairs and at most one pair at each end in part.  Whole pairs are finished
-//   in place; a pair cut between workgroups leaves one partial record (unnormalised
-//   output, running max, running sum) per workgroup and a second kernel merges them.
-//   blockIdx.y selects a chunk of query rows when T*G exceeds what a workgroup carries.
-//   Each workgroup first writes the list of its tiles (page ids, row counts, segment
-//   flags) into LDS, so the main loop does no bookkeeping.
+//   in place; a pair cut between workgroups leaves one partial record (bf16 output
+//   normalised by its own sum, running max, running sum) per workgroup and a second
+//   kernel merges them.  blockIdx.y selects a chunk of query rows when T*G exceeds what
+//   a workgroup carries.
+//   Each workgroup first writes the list of its items (page ids, row counts, segment
+//   flags) into LDS, from a copy of the page table it fetched while the sequence lengths
+//   were on their way, so the main loop does no bookkeeping.
 //
 // One workgroup = 8 wavefronts.  A query row is a (tree node, grouped query head) pair, so
 // one K/V tile serves all heads of the group and all tree nodes.
 //   T*G <= 128: wavefronts 0..3 compute one block of 32 query rows each, wavefronts 4..7
-//               only move data (tile copies, the next pair's query rows, parent pointers
-//               and ancestor masks, the tile list), always ahead of the computation;
-//   T*G  > 128: 8 row blocks of 32 rows, every wavefront computes and copies.
-// Per tile and 32-key block a computing wavefront runs
-//     S^T[32 keys][32 rows] = K_block . Q^T        8 x v_mfma_f32_32x32x16_bf16 (D = 128)
-//     online softmax down the key axis: the scores a lane holds all belong to one
-//     query row, so the row max is in-lane max ops plus one cross-lane swap
-//     O^T[D][32 rows] += V_block^T . P^T           8 x v_mfma_f32_32x32x16_bf16
+//               only move data, always ahead of the computation: the tiles, the query
+//               rows of every segment (a list item of their own that travels through the
+//               ring like a tile), parent pointers and the ancestor masks made from them,
+//               the list itself.  A computing wavefront never issues a memory instruction
+//               inside the loop except to store finished rows.
+//   T*G  > 128: 8 row blocks of 32 rows, every wavefront computes and copies; the two
+//               wavefronts of a SIMD copy at opposite ends of the tile so that they run
+//               out of step.
+// Per tile a computing wavefront runs
+//     S^T[64 keys][32 rows] = K . Q^T             2 x 8 v_mfma_f32_32x32x16_bf16 (D = 128)
+//     online softmax down the key axis: the scores a lane holds all belong to one query
+//     row; weights are taken against the running reference at once and the row maximum is
+//     looked for only in tiles that need it (first of a segment, masked, overflowing)
+//     O^T[D][32 rows] += V^T . P^T                2 x 8 v_mfma_f32_32x32x16_bf16
 //   The S^T accumulator registers of a lane are, eight at a time, exactly the B
 //   operand of the second product, so the softmax weights never leave the registers.
 //   V^T fragments come out of the row-major V tile through the transposing LDS load
-//   (ds_read_b64_tr_b16), K fragments through plain 128-bit LDS loads.
+//   (ds_read_b64_tr_b16), K fragments through plain 128-bit LDS loads.  (A wavefront's
+//   own vector instructions do not run under its own matrix instructions on this part,
+//   only another wavefront's do; the tile code is a plain sequence.)
 //
 // K/V tiles go HBM -> LDS directly (global_load_lds_dwordx4: each wavefront instruction
-// moves 1 KB, no staging registers) into a ring of three tile buffers, so two tiles are
-// in flight while one is consumed; one barrier per tile.  16-byte chunks are XOR-swizzled
-// inside a tile row (applied on the global-address side of the copy) so that operand reads
-// hit every LDS bank once.
+// moves 1 KB, no staging registers) into a ring of four (three for T*G > 128) tile
+// buffers; one barrier per item.  16-byte chunks are XOR-swizzled inside a tile row
+// (applied on the global-address side of the copy) so that operand reads hit every LDS
+// bank once.
+#include <hip/hip_ext.h>
+
 #include "accept_compact.h"
 #include "internal.h"
 
@@ -1103,11 +1115,14 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
         if (e != hipSuccess) { (void)hipGetLastError(); return note_hip_error("hipFuncSetAttribute(attention LDS size)", e); }
         lds_allowed = main_lds;
     }
-    if (ev_start) (void)hipEventRecord(ev_start, stream);
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<D, RB>), dim3(p.n_ranges, p.n_row_chunks), dim3(kThreads),
-                       main_lds, stream, p, p.page_table, p.seq_lens);
+    // with events: they take the kernel's own start and end time stamps
+    if (ev_start && ev_stop)
+        hipExtLaunchKernelGGL((tree_attn_mfma_kernel<D, RB>), dim3(p.n_ranges, p.n_row_chunks), dim3(kThreads),
+                              main_lds, stream, ev_start, ev_stop, 0, p, p.page_table, p.seq_lens);
+    else
+        hipLaunchKernelGGL((tree_attn_mfma_kernel<D, RB>), dim3(p.n_ranges, p.n_row_chunks), dim3(kThreads),
+                           main_lds, stream, p, p.page_table, p.seq_lens);
     hipError_t e = hipGetLastError();
-    if (ev_stop) (void)hipEventRecord(ev_stop, stream);
     if (e != hipSuccess) return note_hip_error("launch tree_attn_mfma_kernel", e);
     const int merge_y = p.n_row_chunks * (p.rows_per_wg / (256 / (D / 8)));
     if (ap && cp) {
