@@ -38,11 +38,9 @@ int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len) {
     // (sequence, kv head, tile) axis.  One workgroup (8 waves, ~100 KB of LDS) occupies a
     // compute unit, so at most 256 ranges; short problems get fewer so that a range holds
     // a few tiles.
-    static int forced = -1;
-    if (forced < 0) {
-        const char *e = getenv("READER_ATTN_RANGES");
-        forced = e ? atoi(e) : 0;
-    }
+    // READER_ATTN_RANGES (tests, experiments): ask for this many ranges instead; read at every call
+    const char *env = getenv("READER_ATTN_RANGES");
+    const int forced = env ? atoi(env) : 0;
     long long tiles_per_pair = (max_seq_len + kTile - 1) / kTile + (d.T + kTile - 1) / kTile;
     long long units = (long long)d.B * d.Hkv * tiles_per_pair;
     long long n = forced > 0 ? forced : units / 4;

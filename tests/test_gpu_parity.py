@@ -87,6 +87,24 @@ def test_attn_many_short_sequences(R, oracle_mod):
     check_attn(R, oracle_mod, w)
 
 
+def test_attn_more_sequences_than_lengths_fit_in_lds(R, oracle_mod):
+    # above 1024 sequences the clamped lengths are re-read from memory while the tile list is written
+    rng = np.random.Generator(np.random.PCG64(6))
+    w = W.make_custom("very_many", B=1100, Hq=4, Hkv=2, D=64, T=4, seq_lens=rng.integers(0, 40, size=1100),
+                      tree="uniform", depth=3, seed=404)
+    check_attn(R, oracle_mod, w)
+
+
+@pytest.mark.parametrize("T,Hq", [(16, 8), (48, 16)])
+def test_attn_ranges_longer_than_the_tile_list(R, oracle_mod, T, Hq, monkeypatch):
+    # few, long ranges: a workgroup walks more items than its list holds at once and has to
+    # extend the list on the way (both kernel flavours: up to 128 query rows, and more)
+    monkeypatch.setenv("READER_ATTN_RANGES", "8")
+    w = W.make_custom("long_ranges", B=1, Hq=Hq, Hkv=4, D=128, T=T, seq_lens=[35000], tree="trie", depth=6,
+                      seed=405)
+    check_attn(R, oracle_mod, w)
+
+
 def test_attn_custom_scale_and_peaked_scores(R, oracle_mod):
     w = W.make_custom("peaked", B=1, Hq=8, Hkv=2, D=128, T=16, seq_lens=[700], tree="trie", depth=5,
                       k_outlier_frac=0.05, seed=402)
