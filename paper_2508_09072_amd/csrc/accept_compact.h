@@ -22,6 +22,7 @@ namespace reader {
 // LDS the acceptance of one sequence needs.
 struct AcceptShared {
     int par[READER_MAX_T];
+    int target[READER_MAX_T];        // the base model's tokens, so that target[parent] is an LDS read
     int path[READER_MAX_T];          // the accepted path, for a compaction that follows in the same workgroup
     unsigned long long term[2];
     int accept_len;
@@ -37,25 +38,36 @@ __device__ inline void accept_path_body(const AcceptParams &p, int b, int lane, 
 
     bool bad_tree = false;
     bool match[2] = {false, false};
-    int my_target[2] = {0, 0};
+    int my_target[2] = {0, 0}, my_draft[2] = {0, 0}, my_par[2] = {-1, -1};
+    bool my_valid[2] = {false, false};
     unsigned long long m_lo = 0ull, m_hi = 0ull;
     if (active) {
+        // one trip to memory for the three token/parent rows; target[parent] then comes from LDS
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const int i = lane + 64 * s;
             if (i < T) {
                 int pi = par[i];
-                bool valid = (i == 0) ? (pi == -1) : (pi >= 0 && pi < i);
-                if (!valid) { bad_tree = true; pi = -1; }
-                sh.par[i] = pi;
+                my_draft[s] = draft[i];
                 my_target[s] = target[i];
-                match[s] = (i == 0) || (valid && draft[i] == target[pi]);
+                my_valid[s] = (i == 0) ? (pi == -1) : (pi >= 0 && pi < i);
+                if (!my_valid[s]) { bad_tree = true; pi = -1; }
+                my_par[s] = pi;
+                sh.par[i] = pi;
+                sh.target[i] = my_target[s];
             }
+        }
+    }
+    __syncthreads();
+    if (active) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int i = lane + 64 * s;
+            if (i < T) match[s] = (i == 0) || (my_valid[s] && my_draft[s] == sh.target[my_par[s]]);
         }
         m_lo = __ballot(match[0]);
         m_hi = __ballot(match[1]);
     }
-    __syncthreads();
 
     // ancestor-or-self sets by walking the parent chain (at most T steps, always ends)
     unsigned long long a_lo[2] = {0ull, 0ull}, a_hi[2] = {0ull, 0ull};
@@ -121,11 +133,30 @@ __device__ inline void accept_path_body(const AcceptParams &p, int b, int lane, 
     }
 }
 
-// Called by all 256 threads of the workgroup.  n = accept_len of the sequence, path = its
-// accepted path (global or LDS).
-__device__ inline void kv_compact_body(const CompactParams &p, int b, int tid, int n, const int *path) {
+// What compaction needs that does not depend on the accepted path: the old length and the page
+// ids of the positions a path could be appended to.  Loaded up front so that, in the fused tail
+// kernel, they travel while the acceptance runs.
+struct CompactShared {
+    int L;
+    int page[READER_MAX_T];   // page id of position L + j (or -1 past the page table)
+};
+
+// Called by all 256 threads of the workgroup, before a barrier.
+__device__ inline void kv_compact_prefetch(const CompactParams &p, int b, int tid, CompactShared &cs) {
     const int L = p.seq_lens[b];
-    const int32_t *pt = p.page_table + (size_t)b * p.max_pages;
+    if (tid == 0) cs.L = L;
+    if (tid < p.max_path) {
+        const long long pos = (long long)L + tid;
+        const bool in_table = L >= 0 && pos < (long long)p.max_pages * READER_PAGE_SIZE;
+        cs.page[tid] = in_table ? p.page_table[(size_t)b * p.max_pages + pos / READER_PAGE_SIZE] : -1;
+    }
+}
+
+// Called by all 256 threads of the workgroup, after kv_compact_prefetch and a barrier.
+// n = accept_len of the sequence, path = its accepted path (global or LDS).
+__device__ inline void kv_compact_body(const CompactParams &p, int b, int tid, int n, const int *path,
+                                       const CompactShared &cs) {
+    const int L = cs.L;
 
     // Every item this sequence would touch is checked before anything is written.
     int bad = 0;
@@ -135,7 +166,7 @@ __device__ inline void kv_compact_body(const CompactParams &p, int b, int tid, i
         for (int j = tid; j <= n; j += 256) {
             const int node = path[j];
             if (node < 0 || node >= p.T) bad |= READER_STATUS_BAD_PATH;
-            const int page = pt[(L + j) / READER_PAGE_SIZE];
+            const int page = cs.page[j];
             if (page < 0 || page >= p.num_pages) bad |= READER_STATUS_BAD_PAGE;
         }
     }
@@ -160,7 +191,7 @@ __device__ inline void kv_compact_body(const CompactParams &p, int b, int tid, i
         const int dc = c - h * chunks_per_head;
         const int node = path[j];
         const int pos = L + j;
-        const long long page = pt[pos / READER_PAGE_SIZE];
+        const long long page = cs.page[j];
         const int slot = pos % READER_PAGE_SIZE;
         const size_t src = (((size_t)b * p.T + node) * p.Hkv + h) * p.D + dc * 8;
         const size_t dst = (((size_t)page * p.Hkv + h) * READER_PAGE_SIZE + slot) * p.D + dc * 8;

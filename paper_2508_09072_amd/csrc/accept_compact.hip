@@ -14,8 +14,12 @@ hipError_t launch_accept_path(const AcceptParams &p, hipStream_t stream) {
 }
 
 __global__ __launch_bounds__(256) void kv_compact_kernel(CompactParams p) {
+    __shared__ CompactShared cs;
     const int b = blockIdx.x;
-    kv_compact_body(p, b, threadIdx.x, p.accept_len[b], p.path + (size_t)b * p.max_path);
+    kv_compact_prefetch(p, b, threadIdx.x, cs);
+    const int n = p.accept_len[b];
+    __syncthreads();
+    kv_compact_body(p, b, threadIdx.x, n, p.path + (size_t)b * p.max_path, cs);
 }
 
 hipError_t launch_kv_compact(const CompactParams &p, hipStream_t stream) {

@@ -1079,22 +1079,27 @@ __global__ __launch_bounds__(256) void tree_attn_merge_kernel(AttnParams p) {
     merge_body<D>(p, blockIdx.x, blockIdx.y);
 }
 
-// Tail of the fused step: the merge blocks, then one workgroup per sequence that accepts a
-// path and appends its rows to the cache.  The three jobs touch disjoint data (the merge reads
+// Tail of the fused step: one workgroup per sequence that accepts a path and appends its rows
+// to the cache, then the merge blocks.  The three jobs touch disjoint data (the merge reads
 // the workspace and writes `out`; acceptance reads tokens; compaction writes cache slots past
 // the old lengths and the lengths themselves, which the merge does not read).
 template <int D>
 __global__ __launch_bounds__(256) void verify_tail_kernel(AttnParams p, AcceptParams ap, CompactParams cp,
-                                                           int n_merge_blocks, int merge_blocks_y) {
-    if ((int)blockIdx.x < n_merge_blocks) {
-        merge_body<D>(p, blockIdx.x / merge_blocks_y, blockIdx.x % merge_blocks_y);
+                                                           int merge_blocks_y) {
+    // the per-sequence workgroups come first in the grid: theirs is the longest chain of
+    // dependent memory accesses, so they should start first
+    if ((int)blockIdx.x >= p.B) {
+        const int m = blockIdx.x - p.B;
+        merge_body<D>(p, m / merge_blocks_y, m % merge_blocks_y);
         return;
     }
     __shared__ AcceptShared sh;
-    const int b = blockIdx.x - n_merge_blocks, tid = threadIdx.x;
+    __shared__ CompactShared cs;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    kv_compact_prefetch(cp, b, tid, cs);   // on its way while the path is being chosen
     accept_path_body(ap, b, tid, tid < 64, sh);
     __syncthreads();
-    kv_compact_body(cp, b, tid, sh.accept_len, sh.path);
+    kv_compact_body(cp, b, tid, sh.accept_len, sh.path, cs);
 }
 
 template <int D, int RB>
@@ -1127,7 +1132,7 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
     const int merge_y = p.n_row_chunks * (p.rows_per_wg / (256 / (D / 8)));
     if (ap && cp) {
         const int n_merge = p.B * p.Hkv * merge_y;
-        hipLaunchKernelGGL(verify_tail_kernel<D>, dim3(n_merge + p.B), dim3(256), 0, stream, p, *ap, *cp, n_merge, merge_y);
+        hipLaunchKernelGGL(verify_tail_kernel<D>, dim3(p.B + n_merge), dim3(256), 0, stream, p, *ap, *cp, merge_y);
         return note_hip_error("launch verify_tail_kernel", hipGetLastError());
     }
     hipLaunchKernelGGL(tree_attn_merge_kernel<D>, dim3(p.B * p.Hkv, merge_y), dim3(256), 0, stream, p);
