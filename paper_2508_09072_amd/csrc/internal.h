@@ -33,7 +33,8 @@ struct AttnParams {
     float *lse;
     float *workspace;  // partial records, see attn_slot_floats() (behind the header, see attn_header_bytes())
     int32_t *pair_info;      // header: per (sequence, kv head) the first and the last workgroup that hold its tiles
-    long long *total_units;  // header: number of tiles of the whole launch
+    int32_t *range_tiles;    // header: per range workgroup the number of tiles it holds (0: it wrote no record)
+    int32_t pair_cost;       // what the start of a pair costs a workgroup, in tiles, when the ranges are cut
     int32_t *status;
     int32_t B, T, Hq, Hkv, D, G, M;       // G = Hq/Hkv, M = T*G query rows per (sequence, kv head)
     int32_t max_pages, max_seq_len;
@@ -49,10 +50,10 @@ struct AttnParams {
 // record's own sum), then the rows' running maxima and running sums as fp32.
 __host__ __device__ inline size_t attn_slot_floats(int D, int rows) { return (size_t)rows * (size_t)(D / 2 + 2); }
 
-// The workspace starts with a header the main kernel leaves for the merge kernel: the tile
-// total (8 bytes, padded to 16), then two ints per (sequence, kv head).
+// The workspace starts with a header the main kernel leaves for the merge kernel: one int per
+// range workgroup (kNumCU of them at most), then two ints per (sequence, kv head).
 __host__ __device__ inline size_t attn_header_bytes(int B, int Hkv) {
-    return ((size_t)16 + (size_t)B * (size_t)Hkv * 8 + 255) & ~(size_t)255;
+    return ((size_t)kNumCU * 4 + (size_t)B * (size_t)Hkv * 8 + 255) & ~(size_t)255;
 }
 
 // Number of range workgroups the planner picks; a pure function of the dims so that

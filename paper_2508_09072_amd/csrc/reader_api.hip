@@ -142,8 +142,8 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     p.k_cache = (const uint16_t *)k_cache; p.v_cache = (const uint16_t *)v_cache;
     p.page_table = page_table; p.seq_lens = seq_lens; p.parents = parents;
     p.out = (uint16_t *)out; p.lse = lse; p.status = status;
-    p.total_units = (long long *)workspace;
-    p.pair_info = workspace ? (int32_t *)((char *)workspace + 16) : nullptr;
+    p.range_tiles = (int32_t *)workspace;
+    p.pair_info = workspace ? (int32_t *)((char *)workspace + kNumCU * 4) : nullptr;
     p.workspace = workspace ? (float *)((char *)workspace + attn_header_bytes(dims->B, dims->Hkv)) : nullptr;
     p.B = dims->B; p.T = dims->T; p.Hq = dims->Hq; p.Hkv = dims->Hkv; p.D = dims->D;
     p.G = dims->Hq / dims->Hkv; p.M = p.T * p.G;
@@ -152,6 +152,14 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     p.rows_per_wg = attn_rows_per_wg(p.M);
     p.n_row_chunks = row_chunks(*dims);
     p.n_ranges = attn_plan_ranges(*dims, max_seq_len);
+    {
+        // A pair that starts inside a range costs its workgroup extra (query rows to fetch, a
+        // segment to finish): about three tiles' time when dedicated wavefronts copy, one otherwise.
+        // READER_ATTN_PAIR_COST (experiments) overrides it.
+        const char *env = getenv("READER_ATTN_PAIR_COST");
+        p.pair_cost = env ? atoi(env) : (p.rows_per_wg == 128 ? 3 : 1);
+        if (p.pair_cost < 0 || p.pair_cost > 64) p.pair_cost = 0;
+    }
     p.num_pages = dims->num_pages;
     float scale = dims->sm_scale > 0.f ? dims->sm_scale : 1.0f / sqrtf((float)dims->D);
     p.scale_log2 = scale * 1.44269504088896340736f;

@@ -135,6 +135,36 @@ __device__ inline int range_of_unit(long long x, long long U, int n_ranges) {
     return (int)w;
 }
 
+// Cutting the tile axis into ranges of equal cost.  Every pair is given E extra positions in
+// front of its tiles (E = pair_cost: what starting a pair costs a workgroup, in tiles), and the
+// axis of these "cost positions" is cut evenly; a workgroup owns the tiles whose positions fall
+// into its share.  Pair q of sequence b has n_b tiles; its cost positions start at
+//     Hkv * (pref[b] + b * E) + hkv * (n_b + E),
+// the first E are padding, tile t sits at padding + t.
+__device__ inline long long cost_total(const AttnParams &p, const int *s_pref) {
+    return (long long)p.Hkv * (s_pref[p.B] + (long long)p.B * p.pair_cost);
+}
+__device__ inline long long cost_pos_of_tile(const AttnParams &p, const int *s_pref, int b, int hkv, int t) {
+    const int n_b = s_pref[b + 1] - s_pref[b];
+    return (long long)p.Hkv * (s_pref[b] + (long long)b * p.pair_cost) + (long long)hkv * (n_b + p.pair_cost) +
+           p.pair_cost + t;
+}
+// Number of tiles whose cost position is below v = flat index of the first tile at or after v.
+__device__ inline long long tiles_below_cost(const AttnParams &p, const int *s_pref, long long v) {
+    if (v >= cost_total(p, s_pref)) return (long long)p.Hkv * s_pref[p.B];
+    int lo = 0, hi = p.B - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if ((long long)p.Hkv * (s_pref[mid] + (long long)mid * p.pair_cost) <= v) lo = mid; else hi = mid - 1;
+    }
+    const int b = lo, n_b = s_pref[b + 1] - s_pref[b];
+    const long long rel = v - (long long)p.Hkv * (s_pref[b] + (long long)b * p.pair_cost);
+    int hkv = (int)(rel / (n_b + p.pair_cost));
+    hkv = hkv > p.Hkv - 1 ? p.Hkv - 1 : hkv;
+    const long long r = rel - (long long)hkv * (n_b + p.pair_cost) - p.pair_cost;
+    return (long long)p.Hkv * s_pref[b] + (long long)hkv * n_b + (r > 0 ? (r < n_b ? r : n_b) : 0);
+}
+
 __device__ inline u32x4 ld16(const void *ptr) { return *reinterpret_cast<const u32x4 *>(ptr); }
 __device__ inline u32x4 keep_if(bool ok, u32x4 v) {
     v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
@@ -222,9 +252,9 @@ __device__ inline void build_desc(const AttnParams &p, const int32_t *table, con
     if (idx == 0) {
         flags |= kDescPairStart;
         // for the merge kernel: which workgroups hold tiles of this pair
-        const long long U = (long long)p.Hkv * s_pref[p.B];
         int2 *info = reinterpret_cast<int2 *>(p.pair_info) + (b * p.Hkv + hkv);
-        *info = make_int2((int)blockIdx.x, range_of_unit(x + n_units - 1, U, p.n_ranges));
+        *info = make_int2((int)blockIdx.x, range_of_unit(cost_pos_of_tile(p, s_pref, b, hkv, n_units - 1),
+                                                         cost_total(p, s_pref), p.n_ranges));
     }
     if (idx + 1 == n_units) flags |= kDescPairEnd;
     if (idx == 0 || i == 0) {
@@ -483,14 +513,15 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     } else {
         scan_units(p, seq_lens, s_pref, s_wsum, s_len);
     }
-    const long long U = (long long)p.Hkv * __builtin_amdgcn_readfirstlane(s_pref[p.B]);
-    const long long lo = range_begin(blockIdx.x, U, p.n_ranges);
-    const long long hi = range_begin(blockIdx.x + 1, U, p.n_ranges);
+    // this workgroup's tiles: [lo, hi) of the flat tile axis, an even share of the cost axis
+    const long long cost_all = cost_total(p, s_pref);
+    const long long lo = __builtin_amdgcn_readfirstlane((int)tiles_below_cost(p, s_pref, range_begin(blockIdx.x, cost_all, p.n_ranges)));
+    const long long hi = __builtin_amdgcn_readfirstlane((int)tiles_below_cost(p, s_pref, range_begin(blockIdx.x + 1, cost_all, p.n_ranges)));
     if (table_in_lds) {
         wait_vmcnt<0>();
         __syncthreads();   // the copy of the page table is complete (every wavefront reaches this)
     }
-    if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *p.total_units = U;
+    if (blockIdx.y == 0 && tid == 0) p.range_tiles[blockIdx.x] = (int)(hi - lo);
     if (lo >= hi) return;
     const int n_tiles = (int)(hi - lo);
     // items of the list: the tiles, and with dedicated copy wavefronts one query unit per segment
@@ -1012,15 +1043,14 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
 // A record holds [D / 8 chunks][rows][8 bf16] of output normalised by the record's own sum, then
 // the rows' running maxima, then their running sums.  One thread takes one 8-wide chunk of one
 // query row: D / 8 threads per row, 256 / (D / 8) rows per workgroup; grid = (B * Hkv, rows / that).
-// Which workgroups hold a pair's records, and the tile total that tells an empty range, come
-// from the header the main kernel wrote.
+// Which workgroups hold a pair's records, and which ranges are empty, come from the header the
+// main kernel wrote.
 template <int D>
 __device__ inline void merge_body(const AttnParams &p, int pair, int block_y) {
     const int b = pair / p.Hkv, hkv = pair - b * p.Hkv;
     const int2 info = reinterpret_cast<const int2 *>(p.pair_info)[pair];
     const int w_first = info.x, w_last = info.y;
     if (w_first == w_last) return;   // finished in place by one workgroup
-    const long long U = *p.total_units;
 
     constexpr int kC = D / 8;                   // chunks (threads) per row
     constexpr int kRowsPerBlock = 256 / kC;
@@ -1042,7 +1072,7 @@ __device__ inline void merge_body(const AttnParams &p, int pair, int block_y) {
 #pragma unroll 2
     for (int w = w_first; w <= w_last; ++w) {
         // a range that holds no tile (more workgroups than tiles) wrote no record
-        if (range_begin(w, U, p.n_ranges) >= range_begin(w + 1, U, p.n_ranges)) continue;
+        if (p.range_tiles[w] == 0) continue;
         const size_t slot = ((size_t)(2 * w + (w == w_first ? 1 : 0)) * p.n_row_chunks + row_chunk);
         const float *rec = p.workspace + slot * rec_floats;
         const float mw = rec[rows * (D / 2) + row_local];
