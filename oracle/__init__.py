@@ -150,3 +150,19 @@ def kv_compact(k_tree, v_tree, path, accept_len, k_cache, v_cache, page_table, s
         _p(k_cache, np.uint16), _p(v_cache, np.uint16), _p(page_table, np.int32), _p(seq_lens, np.int32))
     if rc:
         raise ValueError("oracle_kv_compact failed (rc=%d)" % rc)
+
+
+def kv_rearrange(k_pad, v_pad, valid):
+    """Periodic rearrangement of a padded cache IN PLACE (Section 4.3 / Algorithm 4).
+
+    k_pad, v_pad: uint16 (bf16 bits) [NL, B, S, Hkv, D]; valid: uint8 [B, S], updated in place.
+    Returns new_len int32 [B]."""
+    NL, B, S, Hkv, D = k_pad.shape
+    assert v_pad.shape == k_pad.shape and valid.shape == (B, S)
+    new_len = np.zeros(B, dtype=np.int32)
+    rc = _load().oracle_kv_rearrange(NL, B, S, Hkv, D, _p(k_pad, np.uint16), _p(v_pad, np.uint16),
+                                     _p(valid, np.uint8), _p(new_len, np.int32))
+    if rc:
+        raise ValueError("oracle_kv_rearrange failed (rc=%d)" % rc)
+    return new_len
+

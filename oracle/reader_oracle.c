@@ -29,6 +29,13 @@
  *   oracle_kv_compact     - Section 4.3 / Algorithm 4: the accepted span is
  *                           appended tightly behind each sample's cache so that
  *                           no hole remains inside it.
+ *   oracle_kv_rearrange   - Section 4.3 / Algorithm 4 as the paper runs it on a
+ *                           padded cache, every N-th step: per sample, internal
+ *                           padding is removed and the real entries are
+ *                           concatenated tightly; padding may only remain at the
+ *                           end.  Which positions are padding comes from the
+ *                           bookkeeping (a validity flag per position), never
+ *                           from testing values for zero.
  *
  * Layouts (shared with the library's boundary by definition of the problem):
  *   q               bf16 [B, T, Hq, D]
@@ -329,6 +336,50 @@ int oracle_kv_compact(int B, int T, int Hkv, int D, int page_size, int max_pages
 }
 
 /* Number of host threads the parallel loops above will use. */
+/*
+ * Padded layout: k_pad, v_pad bf16 [NL, B, S, Hkv, D] (NL layers share one validity
+ * map), valid u8 [B, S].  In place, per sample and layer: the rows of the valid
+ * positions move to the front in their order, every later row up to the old extent
+ * (last valid position + 1) becomes zero, rows past the old extent are left alone.
+ * valid becomes ones-then-zeros, new_len[b] = number of valid positions.
+ * Walking left to right is safe in place: a row never moves to the right.
+ */
+int oracle_kv_rearrange(int NL, int B, int S, int Hkv, int D, uint16_t *k_pad, uint16_t *v_pad,
+                        uint8_t *valid, int32_t *new_len) {
+    if (NL < 0 || B < 0 || S < 0 || Hkv < 1 || D < 1) return 1;
+    const size_t row = (size_t)Hkv * (size_t)D;
+    for (int b = 0; b < B; ++b) {
+        uint8_t *vb = valid + (size_t)b * S;
+        int extent = 0;
+        for (int j = 0; j < S; ++j)
+            if (vb[j]) extent = j + 1;
+        int n = 0;
+        for (int l = 0; l < NL; ++l) {
+            uint16_t *kb = k_pad + ((size_t)l * B + b) * (size_t)S * row;
+            uint16_t *vv = v_pad + ((size_t)l * B + b) * (size_t)S * row;
+            int w = 0;
+            for (int j = 0; j < S; ++j) {
+                if (!vb[j]) continue;
+                if (w != j) {
+                    memcpy(kb + (size_t)w * row, kb + (size_t)j * row, row * sizeof(uint16_t));
+                    memcpy(vv + (size_t)w * row, vv + (size_t)j * row, row * sizeof(uint16_t));
+                }
+                ++w;
+            }
+            for (int j = w; j < extent; ++j) {
+                memset(kb + (size_t)j * row, 0, row * sizeof(uint16_t));
+                memset(vv + (size_t)j * row, 0, row * sizeof(uint16_t));
+            }
+            n = w;
+        }
+        if (NL == 0)
+            for (int j = 0; j < S; ++j) n += vb[j] != 0;
+        for (int j = 0; j < S; ++j) vb[j] = j < n;
+        new_len[b] = n;
+    }
+    return 0;
+}
+
 int oracle_num_threads(void) {
     int n = 1;
 #pragma omp parallel

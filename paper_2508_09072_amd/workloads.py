@@ -330,3 +330,66 @@ def make_config(index: int, seed: Optional[int] = None, length_scale: float = 1.
         return make_custom(CONFIG_NAMES[4], B=64, Hq=64, Hkv=8, D=128, T=64, seq_lens=[sc(x) for x in L],
                            tree="trie", depth=10, branch=4, vocab=128256, p_match=0.7, seed=seed + 1000)
     raise ValueError("config index must be 0..4")
+
+
+# ---------------------------------------------------------------------------------------------
+# Padded cache for the periodic rearrangement pass (Section 4.3, Algorithm 4)
+
+@dataclasses.dataclass
+class PaddedCache:
+    """A batch's KV cache in the padded layout the paper starts from: every sample owns S slots,
+    all samples append at one common cursor, a sample that accepted fewer tokens than the longest
+    one in a step is padded.  k_pad, v_pad: uint16 (bf16 bits) [NL, B, S, Hkv, D], zero where
+    valid == 0; valid: uint8 [B, S]."""
+    name: str
+    k_pad: np.ndarray
+    v_pad: np.ndarray
+    valid: np.ndarray
+
+    @property
+    def shape(self):
+        return self.k_pad.shape
+
+    def moved_bytes(self) -> int:
+        """Bytes the pass must move: every valid row behind its sample's first hole is read and
+        written once (K and V, all layers); rows in front of the first hole stay where they are."""
+        NL, B, S, Hkv, D = self.k_pad.shape
+        rows = 0
+        for b in range(B):
+            v = self.valid[b]
+            holes = np.flatnonzero(v == 0)
+            if holes.size:
+                rows += int(v[holes[0]:].sum())
+        return rows * NL * Hkv * D * 2 * 2 * 2
+
+
+def make_padded_cache(name: str, NL: int, B: int, Hkv: int, D: int, prompt_lens: Sequence[int], steps: int,
+                      p_long: float = 0.1, seed: int = 0, slack: int = 8) -> PaddedCache:
+    """Simulate `steps` decoding steps after the prompts: per step each sample accepts 1 + Geometric
+    tokens, with probability p_long a long span of 8..24 (a long retrieval hit); all samples advance by
+    the longest acceptance of the step, the others are padded (the situation Section 4.3 describes)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    prompt_lens = [int(x) for x in prompt_lens]
+    assert len(prompt_lens) == B
+    cursor = max(prompt_lens) if B else 0
+    spans = []
+    for _ in range(steps):
+        a = 1 + rng.geometric(0.5, size=B) - 1 + 1           # 2 on average
+        long_hit = rng.random(B) < p_long
+        a = np.where(long_hit, rng.integers(8, 25, size=B), a)
+        spans.append((cursor, a.astype(np.int64)))
+        cursor += int(a.max()) if B else 0
+    S = cursor + slack
+    valid = np.zeros((B, S), dtype=np.uint8)
+    for b in range(B):
+        valid[b, :prompt_lens[b]] = 1
+    for start, a in spans:
+        for b in range(B):
+            valid[b, start:start + int(a[b])] = 1
+    k = to_bf16_bits(rng.standard_normal((NL, B, S, Hkv, D), dtype=np.float32))
+    v = to_bf16_bits(rng.standard_normal((NL, B, S, Hkv, D), dtype=np.float32))
+    hole = (valid == 0)[None, :, :, None, None]
+    k = np.where(hole, np.uint16(0), k).astype(np.uint16)
+    v = np.where(hole, np.uint16(0), v).astype(np.uint16)
+    return PaddedCache(name=name, k_pad=np.ascontiguousarray(k), v_pad=np.ascontiguousarray(v), valid=valid)
+
