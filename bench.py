@@ -219,6 +219,50 @@ def cpu_baseline(w, budget_s=12.0):
             "sample": "%d whole step(s) of %s (attention + acceptance + compaction), %.1f s" % (reps, w.name, dt)}
 
 
+def time_rearrange(R, torch, W, reps=10):
+    """The periodic rearrangement pass on a padded cache (Section 4.3): 16 samples with the prompt
+    lengths of the headline preset, 25 decoding steps of holes (the paper's N), 8 layers.  The values
+    are filled on the device (they do not matter for the timing; parity is the tests' business)."""
+    import numpy as np
+    NL, B, Hkv, D, steps = 8, 16, 8, 128, 25
+    rng = np.random.Generator(np.random.PCG64(W.SEED_BASE + 77))
+    prompts = rng.integers(1024, 4096 + 1, size=B)
+    valid_np = W.padded_valid_flags(prompts, steps, 0.1, rng)
+    S = valid_np.shape[1]
+    rows_moved = rows_zeroed = 0
+    for b in range(B):
+        holes = np.flatnonzero(valid_np[b] == 0)
+        n, last = int(valid_np[b].sum()), int(np.flatnonzero(valid_np[b]).max()) + 1
+        if holes.size and holes[0] < last:
+            rows_moved += int(valid_np[b, holes[0]:].sum())
+            rows_zeroed += last - n
+    row_bytes = NL * Hkv * D * 2 * 2                               # K and V, all layers, one position
+    alg_bytes = rows_moved * row_bytes * 2 + rows_zeroed * row_bytes
+    k0 = torch.randn((NL, B, S, Hkv, D), device="cuda", dtype=torch.bfloat16)
+    v0 = torch.randn((NL, B, S, Hkv, D), device="cuda", dtype=torch.bfloat16)
+    valid0 = torch.from_numpy(valid_np).cuda()
+    k, v, valid = k0.clone(), v0.clone(), valid0.clone()
+    new_len = torch.zeros(B, dtype=torch.int32, device="cuda")
+    scratch = torch.empty(R.reader_kv_rearrange_scratch_bytes(B, S), dtype=torch.uint8, device="cuda")
+    times = []
+    for rep in range(reps + 2):
+        k.copy_(k0); v.copy_(v0); valid.copy_(valid0)               # holes again (not timed)
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        R.reader_kv_rearrange(k, v, valid, new_len, scratch)
+        b_.record()
+        torch.cuda.synchronize()
+        if rep >= 2:
+            times.append(a.elapsed_time(b_))
+    assert np.array_equal(new_len.cpu().numpy(), valid_np.sum(axis=1))
+    ms = float(np.median(times))
+    return {"workload": "padded cache B=%d S=%d layers=%d Hkv=%d D=%d, %d steps of holes" % (B, S, NL, Hkv, D, steps),
+            "ms_per_pass": ms, "rows_moved": rows_moved, "rows_zeroed": rows_zeroed, "algorithmic_bytes": alg_bytes,
+            "hbm_gbs": alg_bytes / (ms * 1e-3) / 1e9, "hbm_frac": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "ms_per_step_amortised_over_25": ms / 25}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -231,6 +275,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-calls", action="store_true",
                     help="time the three entry points called one after the other instead of the fused step")
+    ap.add_argument("--no-rearrange", action="store_true", help="skip the padded-cache rearrangement timing")
     ap.add_argument("--calibration-pass", action="store_true",
                     help="also run a plain elementwise pass of known size (for counter runs)")
     args = ap.parse_args()
@@ -299,6 +344,9 @@ def main():
         del wo, r
         torch.cuda.empty_cache()
     line["other_workloads"] = others
+    if not args.no_rearrange:
+        log("timing the periodic rearrangement pass")
+        line["kv_rearrange"] = time_rearrange(R, torch, W)
     print(json.dumps(line), flush=True)
 
 

@@ -205,6 +205,29 @@ int reader_verify_step(const reader_dims *dims,
                        int32_t *status, void *stream);
 
 /*
+ * Periodic rearrangement of a padded cache (Section 4.3; Algorithm 4, KVCacheRearrange).
+ * The padded layout is the one the paper starts from: every sample owns S slots, all
+ * samples append at one common position, and a sample that accepted fewer tokens than
+ * the longest acceptance of a step is padded.  Which slots hold a token is bookkeeping
+ * (`valid`), never read off the values.  In place, for every sample b and layer l:
+ *     the rows of the valid positions move to the front, in their order;
+ *     every later row up to the old extent (last valid position + 1) becomes zero;
+ *     rows past the old extent, and rows in front of the first hole, are not touched.
+ * valid[b] becomes ones-then-zeros and new_len[b] the number of valid positions.
+ *
+ *   k_pad, v_pad  bf16 [NL, B, S, Hkv, D]   in/out   NL layers share one validity map
+ *   valid         u8   [B, S]               in/out   nonzero = the slot holds a token
+ *   new_len       i32  [B]                  out
+ *   scratch       >= reader_kv_rearrange_scratch_bytes(B, S) bytes of device memory,
+ *                 4-byte aligned; contents meaningless between calls
+ * D must be 64 or 128.  Returns READER_OK or a READER_E* code (nothing is enqueued then).
+ */
+size_t reader_kv_rearrange_scratch_bytes(int32_t B, int32_t S);
+int reader_kv_rearrange(int32_t NL, int32_t B, int32_t S, int32_t Hkv, int32_t D,
+                        void *k_pad, void *v_pad, uint8_t *valid, int32_t *new_len,
+                        void *scratch, size_t scratch_bytes, void *stream);
+
+/*
  * Measurement hooks for benchmarks (not operations of the method).  While enabled,
  * every reader_tree_attn / reader_verify_step call launches its main streaming kernel
  * with a HIP event pair that takes the kernel's own start and end time stamps (the

@@ -27,6 +27,7 @@ STATUS_BAD_PATH = 4
 EXPORTS = (
     "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",
     "reader_tree_attn", "reader_accept_path", "reader_kv_compact", "reader_verify_step",
+    "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange",
     "reader_profile_enable", "reader_profile_collect",
 )
 
@@ -78,6 +79,10 @@ def load():
     lib.reader_kv_compact.argtypes = [dp] + [vp] * 10
     lib.reader_verify_step.restype = ctypes.c_int
     lib.reader_verify_step.argtypes = [dp] + [vp] * 15 + [i32, vp, ctypes.c_size_t, vp, vp]
+    lib.reader_kv_rearrange_scratch_bytes.restype = ctypes.c_size_t
+    lib.reader_kv_rearrange_scratch_bytes.argtypes = [i32, i32]
+    lib.reader_kv_rearrange.restype = ctypes.c_int
+    lib.reader_kv_rearrange.argtypes = [i32] * 5 + [vp] * 5 + [ctypes.c_size_t, vp]
     lib.reader_profile_enable.restype = ctypes.c_int
     lib.reader_profile_enable.argtypes = [i32]
     lib.reader_profile_collect.restype = ctypes.c_int
@@ -181,6 +186,22 @@ def reader_verify_step(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, se
         _dev(accept_len, torch.int32), _dev(path, torch.int32), _dev(bonus_token, torch.int32), int(max_seq_len),
         _dev(workspace, optional=True), ws_bytes, _dev(status, torch.int32, optional=True), _stream())
     _check(code, "reader_verify_step")
+
+
+def reader_kv_rearrange_scratch_bytes(B: int, S: int) -> int:
+    return int(load().reader_kv_rearrange_scratch_bytes(int(B), int(S)))
+
+
+def reader_kv_rearrange(k_pad, v_pad, valid, new_len, scratch):
+    """k_pad, v_pad: bf16 [NL, B, S, Hkv, D] device tensors (in place); valid: uint8 [B, S] (in place);
+    new_len: int32 [B] (out); scratch: uint8 device tensor of reader_kv_rearrange_scratch_bytes(B, S)."""
+    import torch
+    NL, B, S, Hkv, D = k_pad.shape
+    assert tuple(v_pad.shape) == (NL, B, S, Hkv, D) and tuple(valid.shape) == (B, S) and tuple(new_len.shape) == (B,)
+    code = load().reader_kv_rearrange(
+        NL, B, S, Hkv, D, _dev(k_pad, torch.bfloat16), _dev(v_pad, torch.bfloat16), _dev(valid, torch.uint8),
+        _dev(new_len, torch.int32), _dev(scratch), scratch.numel() * scratch.element_size(), _stream())
+    _check(code, "reader_kv_rearrange")
 
 
 def reader_profile_enable(on: bool) -> None:

@@ -85,4 +85,13 @@ struct CompactParams {
 };
 hipError_t launch_kv_compact(const CompactParams &p, hipStream_t stream);
 
+struct RearrangeParams {
+    uint16_t *k_pad, *v_pad;   // [NL, B, S, Hkv, D]
+    uint8_t *valid;            // [B, S]
+    int32_t *new_len;          // [B]
+    int32_t *dest;             // scratch: [B, S] destinations, then [B][4] = new length, old extent, first hole
+    int32_t NL, B, S, Hkv, D;
+};
+hipError_t launch_kv_rearrange(const RearrangeParams &p, hipStream_t stream);
+
 }  // namespace reader

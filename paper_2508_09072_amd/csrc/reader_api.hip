@@ -286,3 +286,26 @@ extern "C" int reader_kv_compact(const reader_dims *dims, const void *k_tree, co
     compact_fill(dims, k_tree, v_tree, path, accept_len, k_cache, v_cache, page_table, seq_lens, status, p);
     return launch_kv_compact(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }
+
+extern "C" size_t reader_kv_rearrange_scratch_bytes(int32_t B, int32_t S) {
+    if (B < 0 || S < 0) return 0;
+    return (((size_t)B * (size_t)S + (size_t)B * 4) * sizeof(int32_t) + 255) & ~(size_t)255;
+}
+
+extern "C" int reader_kv_rearrange(int32_t NL, int32_t B, int32_t S, int32_t Hkv, int32_t D, void *k_pad,
+                                   void *v_pad, uint8_t *valid, int32_t *new_len, void *scratch,
+                                   size_t scratch_bytes, void *stream) {
+    if (NL < 0 || B < 0 || S < 0 || Hkv < 1 || D < 1) return READER_EINVAL;
+    if (D != 64 && D != 128) return READER_EUNSUPPORTED;
+    if ((long long)B * Hkv > 0x7fffffffLL || NL > 65535) return READER_EUNSUPPORTED;
+    if (B == 0 || S == 0) return READER_OK;
+    if (!valid || !new_len || (NL > 0 && (!k_pad || !v_pad))) return READER_EINVAL;
+    if (!scratch || ((uintptr_t)scratch & 3) != 0 || scratch_bytes < reader_kv_rearrange_scratch_bytes(B, S))
+        return READER_EWORKSPACE;
+    RearrangeParams p;
+    p.k_pad = (uint16_t *)k_pad; p.v_pad = (uint16_t *)v_pad; p.valid = valid; p.new_len = new_len;
+    p.dest = (int32_t *)scratch;
+    p.NL = NL; p.B = B; p.S = S; p.Hkv = Hkv; p.D = D;
+    return launch_kv_rearrange(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
+}
+

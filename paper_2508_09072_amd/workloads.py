@@ -363,18 +363,17 @@ class PaddedCache:
         return rows * NL * Hkv * D * 2 * 2 * 2
 
 
-def make_padded_cache(name: str, NL: int, B: int, Hkv: int, D: int, prompt_lens: Sequence[int], steps: int,
-                      p_long: float = 0.1, seed: int = 0, slack: int = 8) -> PaddedCache:
-    """Simulate `steps` decoding steps after the prompts: per step each sample accepts 1 + Geometric
-    tokens, with probability p_long a long span of 8..24 (a long retrieval hit); all samples advance by
-    the longest acceptance of the step, the others are padded (the situation Section 4.3 describes)."""
-    rng = np.random.Generator(np.random.PCG64(seed))
+def padded_valid_flags(prompt_lens: Sequence[int], steps: int, p_long: float, rng, slack: int = 8) -> np.ndarray:
+    """Validity flags uint8 [B, S] after `steps` decoding steps behind the prompts: per step each sample
+    accepts 1 + Geometric tokens, with probability p_long a long span of 8..24 (a long retrieval hit);
+    all samples advance by the longest acceptance of the step, the others are padded (the situation
+    Section 4.3 describes)."""
     prompt_lens = [int(x) for x in prompt_lens]
-    assert len(prompt_lens) == B
+    B = len(prompt_lens)
     cursor = max(prompt_lens) if B else 0
     spans = []
     for _ in range(steps):
-        a = 1 + rng.geometric(0.5, size=B) - 1 + 1           # 2 on average
+        a = 1 + rng.geometric(0.5, size=B)                    # 3 on average
         long_hit = rng.random(B) < p_long
         a = np.where(long_hit, rng.integers(8, 25, size=B), a)
         spans.append((cursor, a.astype(np.int64)))
@@ -386,10 +385,19 @@ def make_padded_cache(name: str, NL: int, B: int, Hkv: int, D: int, prompt_lens:
     for start, a in spans:
         for b in range(B):
             valid[b, start:start + int(a[b])] = 1
+    return valid
+
+
+def make_padded_cache(name: str, NL: int, B: int, Hkv: int, D: int, prompt_lens: Sequence[int], steps: int,
+                      p_long: float = 0.1, seed: int = 0, slack: int = 8) -> PaddedCache:
+    """Flags from padded_valid_flags, bf16 ~N(0,1) values in the valid slots, zeros in the padding."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    assert len(prompt_lens) == B
+    valid = padded_valid_flags(prompt_lens, steps, p_long, rng, slack)
+    S = valid.shape[1]
     k = to_bf16_bits(rng.standard_normal((NL, B, S, Hkv, D), dtype=np.float32))
     v = to_bf16_bits(rng.standard_normal((NL, B, S, Hkv, D), dtype=np.float32))
     hole = (valid == 0)[None, :, :, None, None]
     k = np.where(hole, np.uint16(0), k).astype(np.uint16)
     v = np.where(hole, np.uint16(0), v).astype(np.uint16)
     return PaddedCache(name=name, k_pad=np.ascontiguousarray(k), v_pad=np.ascontiguousarray(v), valid=valid)
-

@@ -111,3 +111,17 @@ def test_binding_refuses_cpu_tensors(R):
     t = torch.zeros(4, dtype=torch.int32)
     with pytest.raises(ValueError):
         R.reader_accept_path(d, t, t, t, t, t, t)
+
+
+def test_rearrange_arguments_are_checked_on_the_host(R):
+    lib = R.load()
+    one = ctypes.c_void_p(256)
+    assert R.reader_kv_rearrange_scratch_bytes(16, 4224) >= (16 * 4224 + 64) * 4
+    assert R.reader_kv_rearrange_scratch_bytes(16, 4224) % 256 == 0
+    assert lib.reader_kv_rearrange(1, 2, 8, 0, 128, one, one, one, one, one, 1 << 20, None) == R.READER_EINVAL
+    assert lib.reader_kv_rearrange(1, 2, 8, 2, 96, one, one, one, one, one, 1 << 20, None) == R.READER_EUNSUPPORTED
+    assert lib.reader_kv_rearrange(1, 2, 8, 2, 128, None, one, one, one, one, 1 << 20, None) == R.READER_EINVAL
+    assert lib.reader_kv_rearrange(1, 2, 8, 2, 128, one, one, one, one, None, 0, None) == R.READER_EWORKSPACE
+    assert lib.reader_kv_rearrange(1, 2, 8, 2, 128, one, one, one, one, one, 16, None) == R.READER_EWORKSPACE
+    assert lib.reader_kv_rearrange(1, 0, 8, 2, 128, None, None, None, None, None, 0, None) == R.READER_OK   # empty batch
+
