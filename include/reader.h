@@ -228,6 +228,18 @@ int reader_kv_rearrange(int32_t NL, int32_t B, int32_t S, int32_t Hkv, int32_t D
                         void *scratch, size_t scratch_bytes, void *stream);
 
 /*
+ * The base model's greedy tokens from its logits (Algorithm 5, "compare base logits with
+ * drafted tokens"): target_tokens[r] = argmax over v of logits[r][v], for the B*T rows of
+ * a verification step; the result is the target_tokens input of reader_accept_path.
+ *
+ *   logits         bf16 [rows, V]   in    compared exactly as bf16 values
+ *   target_tokens  i32  [rows]      out   lowest index among equal maxima; a NaN is never
+ *                                         the maximum (a row of NaNs gives 0)
+ * Returns READER_OK or READER_EINVAL (rows < 0, V < 1, null pointer).
+ */
+int reader_target_argmax(int32_t rows, int32_t V, const void *logits, int32_t *target_tokens, void *stream);
+
+/*
  * Measurement hooks for benchmarks (not operations of the method).  While enabled,
  * every reader_tree_attn / reader_verify_step call launches its main streaming kernel
  * with a HIP event pair that takes the kernel's own start and end time stamps (the

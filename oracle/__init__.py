@@ -166,3 +166,14 @@ def kv_rearrange(k_pad, v_pad, valid):
         raise ValueError("oracle_kv_rearrange failed (rc=%d)" % rc)
     return new_len
 
+
+def target_argmax(logits):
+    """logits: uint16 (bf16 bits) [..., V].  Returns int32 [...] greedy tokens (Algorithm 5)."""
+    V = logits.shape[-1]
+    rows = logits.size // V
+    out = np.zeros(rows, dtype=np.int32)
+    rc = _load().oracle_target_argmax(rows, V, _p(logits, np.uint16), _p(out, np.int32))
+    if rc:
+        raise ValueError("oracle_target_argmax failed (rc=%d)" % rc)
+    return out.reshape(logits.shape[:-1])
+

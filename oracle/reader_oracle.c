@@ -29,6 +29,9 @@
  *   oracle_kv_compact     - Section 4.3 / Algorithm 4: the accepted span is
  *                           appended tightly behind each sample's cache so that
  *                           no hole remains inside it.
+ *   oracle_target_argmax  - Algorithm 5: the base model's own (greedy) token at every
+ *                           tree node, i.e. the arg max of its logits there; these
+ *                           are the tokens the drafted ones are compared with.
  *   oracle_kv_rearrange   - Section 4.3 / Algorithm 4 as the paper runs it on a
  *                           padded cache, every N-th step: per sample, internal
  *                           padding is removed and the real entries are
@@ -376,6 +379,27 @@ int oracle_kv_rearrange(int NL, int B, int S, int Hkv, int D, uint16_t *k_pad, u
             for (int j = 0; j < S; ++j) n += vb[j] != 0;
         for (int j = 0; j < S; ++j) vb[j] = j < n;
         new_len[b] = n;
+    }
+    return 0;
+}
+
+/*
+ * target[r] = index of the largest of logits[r][0..V) (bf16 bit patterns, compared as
+ * the values they encode), the lowest index among equals; NaNs are skipped, a row
+ * without any number gives 0.
+ */
+int oracle_target_argmax(int rows, int V, const uint16_t *logits, int32_t *target) {
+    if (rows < 0 || V < 1) return 1;
+    for (int r = 0; r < rows; ++r) {
+        const uint16_t *row = logits + (size_t)r * V;
+        int best_i = -1;
+        double best_v = 0.0;
+        for (int v = 0; v < V; ++v) {
+            const double x = widen_bf16(row[v]);
+            if (x != x) continue;
+            if (best_i < 0 || x > best_v) { best_i = v; best_v = x; }
+        }
+        target[r] = best_i < 0 ? 0 : best_i;
     }
     return 0;
 }

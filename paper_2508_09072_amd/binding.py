@@ -27,7 +27,7 @@ STATUS_BAD_PATH = 4
 EXPORTS = (
     "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",
     "reader_tree_attn", "reader_accept_path", "reader_kv_compact", "reader_verify_step",
-    "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange",
+    "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax",
     "reader_profile_enable", "reader_profile_collect",
 )
 
@@ -83,6 +83,8 @@ def load():
     lib.reader_kv_rearrange_scratch_bytes.argtypes = [i32, i32]
     lib.reader_kv_rearrange.restype = ctypes.c_int
     lib.reader_kv_rearrange.argtypes = [i32] * 5 + [vp] * 5 + [ctypes.c_size_t, vp]
+    lib.reader_target_argmax.restype = ctypes.c_int
+    lib.reader_target_argmax.argtypes = [i32, i32, vp, vp, vp]
     lib.reader_profile_enable.restype = ctypes.c_int
     lib.reader_profile_enable.argtypes = [i32]
     lib.reader_profile_collect.restype = ctypes.c_int
@@ -202,6 +204,16 @@ def reader_kv_rearrange(k_pad, v_pad, valid, new_len, scratch):
         NL, B, S, Hkv, D, _dev(k_pad, torch.bfloat16), _dev(v_pad, torch.bfloat16), _dev(valid, torch.uint8),
         _dev(new_len, torch.int32), _dev(scratch), scratch.numel() * scratch.element_size(), _stream())
     _check(code, "reader_kv_rearrange")
+
+
+def reader_target_argmax(logits, target_tokens):
+    """logits: bf16 [..., V] device tensor; target_tokens: int32 tensor with one entry per row."""
+    import torch
+    V = logits.shape[-1]
+    rows = logits.numel() // V
+    assert target_tokens.numel() == rows
+    code = load().reader_target_argmax(rows, V, _dev(logits, torch.bfloat16), _dev(target_tokens, torch.int32), _stream())
+    _check(code, "reader_target_argmax")
 
 
 def reader_profile_enable(on: bool) -> None:

@@ -94,4 +94,6 @@ struct RearrangeParams {
 };
 hipError_t launch_kv_rearrange(const RearrangeParams &p, hipStream_t stream);
 
+hipError_t launch_target_argmax(const uint16_t *logits, int32_t *out, int rows, int V, hipStream_t stream);
+
 }  // namespace reader

@@ -309,3 +309,12 @@ extern "C" int reader_kv_rearrange(int32_t NL, int32_t B, int32_t S, int32_t Hkv
     return launch_kv_rearrange(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }
 
+extern "C" int reader_target_argmax(int32_t rows, int32_t V, const void *logits, int32_t *target_tokens,
+                                    void *stream) {
+    if (rows < 0 || V < 1) return READER_EINVAL;
+    if (rows == 0) return READER_OK;
+    if (!logits || !target_tokens) return READER_EINVAL;
+    return launch_target_argmax((const uint16_t *)logits, target_tokens, rows, V, (hipStream_t)stream) == hipSuccess
+               ? READER_OK : READER_EHIP;
+}
+
