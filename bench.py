@@ -263,6 +263,34 @@ def time_rearrange(R, torch, W, reps=10):
             "ms_per_step_amortised_over_25": ms / 25}
 
 
+def time_argmax(R, torch, reps=20):
+    """Greedy target tokens from base-model logits (vocabulary 128256) for the rows of one step of the
+    headline preset (B*T = 512) and of the large-batch preset (4096); the logits are filled on the device."""
+    import numpy as np
+    out = {}
+    V = 128256
+    for name, rows in (("rows_512", 512), ("rows_4096", 4096)):
+        n_buf = max(2, -(-ROTATE_BYTES // (rows * V * 2)))         # rotate so that the 256 MB cache cannot serve it
+        logits = [torch.randn((rows, V), device="cuda", dtype=torch.bfloat16) for _ in range(n_buf)]
+        tok = torch.zeros(rows, dtype=torch.int32, device="cuda")
+        for l in logits[:2]:
+            R.reader_target_argmax(l, tok)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for k in range(reps):
+            R.reader_target_argmax(logits[k % n_buf], tok)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        nbytes = rows * V * 2
+        out[name] = {"ms": ms, "bytes": nbytes, "hbm_gbs": nbytes / (ms * 1e-3) / 1e9,
+                     "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del logits
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -275,7 +303,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-calls", action="store_true",
                     help="time the three entry points called one after the other instead of the fused step")
-    ap.add_argument("--no-rearrange", action="store_true", help="skip the padded-cache rearrangement timing")
+    ap.add_argument("--no-rearrange", action="store_true", help="skip the timings of the padded-cache rearrangement and of the logits arg max")
     ap.add_argument("--calibration-pass", action="store_true",
                     help="also run a plain elementwise pass of known size (for counter runs)")
     args = ap.parse_args()
@@ -347,6 +375,8 @@ def main():
     if not args.no_rearrange:
         log("timing the periodic rearrangement pass")
         line["kv_rearrange"] = time_rearrange(R, torch, W)
+        log("timing the arg max over logits")
+        line["target_argmax"] = time_argmax(R, torch)
     print(json.dumps(line), flush=True)
 
 

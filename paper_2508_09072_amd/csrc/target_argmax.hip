@@ -30,8 +30,7 @@ __global__ __launch_bounds__(256) void target_argmax_kernel(const uint16_t *__re
     if (tid < head) take(best, __uint_as_float((uint32_t)src[tid] << 16), tid);
     const int n_vec = (V - head) / 8;
     const uint4 *vec = reinterpret_cast<const uint4 *>(src + head);
-    for (int c = tid; c < n_vec; c += 256) {
-        const uint4 w = vec[c];
+    auto scan = [&](const uint4 &w, int c) {
         const uint32_t u[4] = {w.x, w.y, w.z, w.w};
         const int base = head + c * 8;
 #pragma unroll
@@ -39,7 +38,13 @@ __global__ __launch_bounds__(256) void target_argmax_kernel(const uint16_t *__re
             take(best, __uint_as_float(u[e] << 16), base + 2 * e);
             take(best, __uint_as_float(u[e] & 0xffff0000u), base + 2 * e + 1);
         }
+    };
+    int c = tid;
+    for (; c + 3 * 256 < n_vec; c += 4 * 256) {      // four loads in flight per thread
+        const uint4 w0 = vec[c], w1 = vec[c + 256], w2 = vec[c + 512], w3 = vec[c + 768];
+        scan(w0, c); scan(w1, c + 256); scan(w2, c + 512); scan(w3, c + 768);
     }
+    for (; c < n_vec; c += 256) scan(vec[c], c);
     for (int j = head + n_vec * 8 + tid; j < V; j += 256) take(best, __uint_as_float((uint32_t)src[j] << 16), j);
 
 #pragma unroll
