@@ -11,8 +11,8 @@
 //   whole pairs and at most one pair at each end in part.  Whole pairs are finished
 //   in place; a pair cut between workgroups leaves one partial record (bf16 output
 //   normalised by its own sum, running max, running sum) per workgroup and a second
-//   kernel merges them.  blockIdx.y selects a chunk of query rows when T*G exceeds what
-//   a workgroup carries.
+//   kernel merges them.  When T*G exceeds what a workgroup carries, the query rows are cut
+//   into chunks, one workgroup per (range, chunk).
 //   Each workgroup first writes the list of its items (page ids, row counts, segment
 //   flags) into LDS, from a copy of the page table it fetched while the sequence lengths
 //   were on their way, so the main loop does no bookkeeping.
@@ -223,7 +223,7 @@ constexpr int kDescSlots = 256;
 // `table` is the page table or a copy of it; `s_len` the clamped lengths in LDS, or null.
 __device__ inline void build_desc(const AttnParams &p, const int32_t *table, const int32_t *__restrict__ seq_lens,
                                   const int *s_len, const int *s_pref, long long lo, int n_iter, int i, TileDesc *slot,
-                                  int &bad) {
+                                  int &bad, int range_id) {
     const long long x = lo + i;
     const int b = find_seq(s_pref, p.B, p.Hkv, x);
     const int L = s_len ? s_len[b] : clamp_len(p, seq_lens, b);
@@ -253,7 +253,7 @@ __device__ inline void build_desc(const AttnParams &p, const int32_t *table, con
         flags |= kDescPairStart;
         // for the merge kernel: which workgroups hold tiles of this pair
         int2 *info = reinterpret_cast<int2 *>(p.pair_info) + (b * p.Hkv + hkv);
-        *info = make_int2((int)blockIdx.x, range_of_unit(cost_pos_of_tile(p, s_pref, b, hkv, n_units - 1),
+        *info = make_int2(range_id, range_of_unit(cost_pos_of_tile(p, s_pref, b, hkv, n_units - 1),
                                                          cost_total(p, s_pref), p.n_ranges));
     }
     if (idx + 1 == n_units) flags |= kDescPairEnd;
@@ -280,7 +280,7 @@ __device__ inline int pair_of_tile(const int *s_pref, int B, int Hkv, long long 
 //   pair's tiles; the first segment's query unit sits at position 0, followed by tile lo.
 __device__ inline void build_item(const AttnParams &p, const int32_t *table, const int32_t *__restrict__ seq_lens,
                                   const int *s_len, const int *s_pref, long long lo, int n_tiles, int q_lo, int i,
-                                  TileDesc *slot, int &bad) {
+                                  TileDesc *slot, int &bad, int range_id) {
     const long long target = lo + q_lo + i;   // largest pair q with start(q) + q <= target owns item i
     int blo = 0, bhi = p.B - 1;
     while (blo < bhi) {
@@ -305,7 +305,8 @@ __device__ inline void build_item(const AttnParams &p, const int32_t *table, con
         dst[0] = make_int4(-1, -1, -1, -1);
         dst[1] = make_int4(0, kDescQ, b, hkv);
     } else {
-        build_desc(p, table, seq_lens, s_len, s_pref, lo, n_tiles, (int)(first_tile + (i - pos_q - 1) - lo), slot, bad);
+        build_desc(p, table, seq_lens, s_len, s_pref, lo, n_tiles, (int)(first_tile + (i - pos_q - 1) - lo), slot, bad,
+                   range_id);
     }
 }
 
@@ -460,6 +461,18 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     const unsigned par_lds = (unsigned)(size_t)(lds_char *)reinterpret_cast<char *>(s_par);
     const unsigned prefetch_lds = (unsigned)(size_t)(lds_char *)reinterpret_cast<char *>(s_sink);
 
+    // 1-D grid.  Workgroups are handed to the XCDs round robin (id mod 8); the row chunks of
+    // one range get ids 8 apart, so they run at the same time on the same XCD and the second
+    // one finds the range's K/V tiles in that XCD's L2.
+    int range_id, chunk_id;
+    if (p.n_ranges % kNumXCD == 0) {
+        const int per_group = kNumXCD * p.n_row_chunks, g = blockIdx.x / per_group, r = blockIdx.x - g * per_group;
+        chunk_id = r / kNumXCD;
+        range_id = g * kNumXCD + r % kNumXCD;
+    } else {
+        chunk_id = blockIdx.x / p.n_ranges;
+        range_id = blockIdx.x - chunk_id * p.n_ranges;
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool is_computer = !kDma || wave_s < 4;
@@ -468,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     const int rb = kDma ? (wave_s & 3) : wave_s;         // row block of a computing wavefront
     const int htid = kDma ? tid - 256 : tid;             // index among the helper threads, negative: none
     const int n = lane & 31, h = lane >> 5;
-    const int chunk_base = blockIdx.y * kRowsPerWG;
+    const int chunk_base = chunk_id * kRowsPerWG;
     const int row_local = rb * 32 + n;             // row inside this workgroup's chunk
     const int m_row = chunk_base + row_local;      // query row inside the pair
     const bool row_real = m_row < p.M;
@@ -515,13 +528,13 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     }
     // this workgroup's tiles: [lo, hi) of the flat tile axis, an even share of the cost axis
     const long long cost_all = cost_total(p, s_pref);
-    const long long lo = __builtin_amdgcn_readfirstlane((int)tiles_below_cost(p, s_pref, range_begin(blockIdx.x, cost_all, p.n_ranges)));
-    const long long hi = __builtin_amdgcn_readfirstlane((int)tiles_below_cost(p, s_pref, range_begin(blockIdx.x + 1, cost_all, p.n_ranges)));
+    const long long lo = __builtin_amdgcn_readfirstlane((int)tiles_below_cost(p, s_pref, range_begin(range_id, cost_all, p.n_ranges)));
+    const long long hi = __builtin_amdgcn_readfirstlane((int)tiles_below_cost(p, s_pref, range_begin(range_id + 1, cost_all, p.n_ranges)));
     if (table_in_lds) {
         wait_vmcnt<0>();
         __syncthreads();   // the copy of the page table is complete (every wavefront reaches this)
     }
-    if (blockIdx.y == 0 && tid == 0) p.range_tiles[blockIdx.x] = (int)(hi - lo);
+    if (chunk_id == 0 && tid == 0) p.range_tiles[range_id] = (int)(hi - lo);
     if (lo >= hi) return;
     const int n_tiles = (int)(hi - lo);
     // items of the list: the tiles, and with dedicated copy wavefronts one query unit per segment
@@ -534,9 +547,9 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     int bad = 0;
     auto write_item = [&](int i) {
         if (kDma) build_item(p, i < kDescSlots ? table : page_table, seq_lens, s_len, s_pref, lo, n_tiles, q_lo, i,
-                             s_desc + (i & (kDescSlots - 1)), bad);
+                             s_desc + (i & (kDescSlots - 1)), bad, range_id);
         else build_desc(p, i < kDescSlots ? table : page_table, seq_lens, s_len, s_pref, lo, n_tiles, i,
-                        s_desc + (i & (kDescSlots - 1)), bad);
+                        s_desc + (i & (kDescSlots - 1)), bad, range_id);
     };
     if (htid >= 0)
         for (int i = htid; i < min(n_iter, kDescSlots); i += kHelpers) write_item(i);
@@ -880,7 +893,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             // Partial record: the output so far, normalised by its own sum and rounded to bf16,
             // as [D / 8 chunks][rows][8 values] (the order the swapped registers hold it, so every
             // store instruction writes whole 512-byte runs), then the maxima and the sums.
-            const size_t slot = ((size_t)(2 * blockIdx.x + (seg_from_pair_start ? 1 : 0)) * p.n_row_chunks + blockIdx.y);
+            const size_t slot = ((size_t)(2 * range_id + (seg_from_pair_start ? 1 : 0)) * p.n_row_chunks + chunk_id);
             float *rec = p.workspace + slot * attn_slot_floats(D, kRowsPerWG);
             u32x4 *rec16 = reinterpret_cast<u32x4 *>(rec);
             const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;   // a row may see no key of this segment
@@ -1152,10 +1165,10 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
     }
     // with events: they take the kernel's own start and end time stamps
     if (ev_start && ev_stop)
-        hipExtLaunchKernelGGL((tree_attn_mfma_kernel<D, RB>), dim3(p.n_ranges, p.n_row_chunks), dim3(kThreads),
+        hipExtLaunchKernelGGL((tree_attn_mfma_kernel<D, RB>), dim3(p.n_ranges * p.n_row_chunks), dim3(kThreads),
                               main_lds, stream, ev_start, ev_stop, 0, p, p.page_table, p.seq_lens);
     else
-        hipLaunchKernelGGL((tree_attn_mfma_kernel<D, RB>), dim3(p.n_ranges, p.n_row_chunks), dim3(kThreads),
+        hipLaunchKernelGGL((tree_attn_mfma_kernel<D, RB>), dim3(p.n_ranges * p.n_row_chunks), dim3(kThreads),
                            main_lds, stream, p, p.page_table, p.seq_lens);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return note_hip_error("launch tree_attn_mfma_kernel", e);
