@@ -313,12 +313,15 @@ __device__ inline void build_item(const AttnParams &p, const int32_t *table, con
 // Asynchronous copy HBM -> LDS: lane l moves 16 bytes from its global address to LDS byte
 // lds_base + 16 * l.  The compiler does not track these copies; the caller counts them
 // (every wavefront issues the same number per tile) and waits with s_waitcnt vmcnt.
+// The copies carry the non-temporal hint: K/V rows are read once per launch, and streamed
+// that way the same loop moves about a sixth more bytes per second out of HBM (measured:
+// 6.9 against 5.9 TB/s for a bare copy ring) while rows that are in the caches still hit.
 __device__ inline void copy16_uniform(const void *sbase, unsigned lane_off, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 nt"
                  :: "v"(lane_off), "s"(sbase), "s"(lds_base) : "memory", "m0");
 }
 __device__ inline void copy16_lane(const void *addr, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off nt"
                  :: "v"(addr), "s"(lds_base) : "memory", "m0");
 }
 
