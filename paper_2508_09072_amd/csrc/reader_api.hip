@@ -159,6 +159,10 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
         const char *env = getenv("READER_ATTN_PAIR_COST");
         p.pair_cost = env ? atoi(env) : (p.rows_per_wg == 128 ? 3 : 1);
         if (p.pair_cost < 0 || p.pair_cost > 64) p.pair_cost = 0;
+        // the kernel cuts the ranges with 32-bit arithmetic when nothing on the cost axis can overflow it
+        const long long axis_max = (long long)p.Hkv * p.B * ((max_seq_len + kTile - 1) / kTile + p.n_tree_tiles + p.pair_cost);
+        p.axis32 = (axis_max + 2) * (p.n_ranges + 1) < 0x7fffffffLL ? 1 : 0;
+        if (getenv("READER_ATTN_AXIS64")) p.axis32 = 0;   // tests: force the 64-bit path
     }
     p.num_pages = dims->num_pages;
     float scale = dims->sm_scale > 0.f ? dims->sm_scale : 1.0f / sqrtf((float)dims->D);

@@ -114,55 +114,65 @@ __device__ inline void scan_units(const AttnParams &p, const int32_t *__restrict
     }
 }
 
-// Largest b in [0, B) with Hkv * s_pref[b] <= x   (x < Hkv * s_pref[B]).
-__device__ inline int find_seq(const int *s_pref, int B, int Hkv, long long x) {
-    int lo = 0, hi = B - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if ((long long)Hkv * s_pref[mid] <= x) lo = mid; else hi = mid - 1;
-    }
-    return lo;
-}
-
-__device__ inline long long range_begin(long long w, long long U, int n_ranges) { return w * U / n_ranges; }
-
-// Workgroup whose range contains unit x.
-__device__ inline int range_of_unit(long long x, long long U, int n_ranges) {
-    long long w = ((x + 1) * n_ranges - 1) / U;
-    if (w >= n_ranges) w = n_ranges - 1;
-    while (w + 1 < n_ranges && range_begin(w + 1, U, n_ranges) <= x) ++w;
-    while (w > 0 && range_begin(w, U, n_ranges) > x) --w;
-    return (int)w;
-}
-
-// Cutting the tile axis into ranges of equal cost.  Every pair is given E extra positions in
-// front of its tiles (E = pair_cost: what starting a pair costs a workgroup, in tiles), and the
-// axis of these "cost positions" is cut evenly; a workgroup owns the tiles whose positions fall
-// into its share.  Pair q of sequence b has n_b tiles; its cost positions start at
+// Cutting the tile axis into ranges of equal cost.  Every pair (sequence b, kv head) is given
+// E extra positions in front of its tiles (E = pair_cost: what starting a pair costs a
+// workgroup, in tiles), and the axis of these "cost positions" is cut evenly; a workgroup owns
+// the tiles whose positions fall into its share.  The pair's n_b tiles and its padding start at
 //     Hkv * (pref[b] + b * E) + hkv * (n_b + E),
-// the first E are padding, tile t sits at padding + t.
-__device__ inline long long cost_total(const AttnParams &p, const int *s_pref) {
-    return (long long)p.Hkv * (s_pref[p.B] + (long long)p.B * p.pair_cost);
+// the first E positions are padding, tile t sits at padding + t.
+// I is the integer type of the axis: int when the host has checked that every position times
+// the number of ranges fits (64-bit division costs a workgroup a good part of a microsecond).
+template <typename I>
+__device__ inline I range_begin(I w, I U, int n_ranges) { return w * U / n_ranges; }
+
+// Workgroup whose range contains cost position x.
+template <typename I>
+__device__ inline int range_of_position(I x, I U, int n_ranges) {
+    // largest w with floor(w * U / n) <= x  <=>  w * U < (x + 1) * n  <=>  w <= ((x + 1) * n - 1) / U
+    const I w = ((x + 1) * n_ranges - 1) / U;
+    return (int)(w < n_ranges ? w : n_ranges - 1);
 }
-__device__ inline long long cost_pos_of_tile(const AttnParams &p, const int *s_pref, int b, int hkv, int t) {
+
+template <typename I>
+__device__ inline I cost_total(const AttnParams &p, const int *s_pref) {
+    return (I)p.Hkv * (s_pref[p.B] + (I)p.B * p.pair_cost);
+}
+template <typename I>
+__device__ inline I cost_pos_of_tile(const AttnParams &p, const int *s_pref, int b, int hkv, int t) {
     const int n_b = s_pref[b + 1] - s_pref[b];
-    return (long long)p.Hkv * (s_pref[b] + (long long)b * p.pair_cost) + (long long)hkv * (n_b + p.pair_cost) +
-           p.pair_cost + t;
+    return (I)p.Hkv * (s_pref[b] + (I)b * p.pair_cost) + (I)hkv * (n_b + p.pair_cost) + p.pair_cost + t;
 }
-// Number of tiles whose cost position is below v = flat index of the first tile at or after v.
-__device__ inline long long tiles_below_cost(const AttnParams &p, const int *s_pref, long long v) {
-    if (v >= cost_total(p, s_pref)) return (long long)p.Hkv * s_pref[p.B];
+
+// A place on the tile axis: tile t of pair (b, hkv); `flat` counts the tiles in front of it.
+// The end of the axis is (B, 0, 0).
+struct TilePos {
+    int b, hkv, t, flat;
+};
+// First tile whose cost position is at or after v.
+template <typename I>
+__device__ inline TilePos locate(const AttnParams &p, const int *s_pref, I v) {
+    TilePos r;
+    if (v >= cost_total<I>(p, s_pref)) {
+        r.b = p.B; r.hkv = 0; r.t = 0; r.flat = p.Hkv * s_pref[p.B];
+        return r;
+    }
     int lo = 0, hi = p.B - 1;
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
-        if ((long long)p.Hkv * (s_pref[mid] + (long long)mid * p.pair_cost) <= v) lo = mid; else hi = mid - 1;
+        if ((I)p.Hkv * (s_pref[mid] + (I)mid * p.pair_cost) <= v) lo = mid; else hi = mid - 1;
     }
     const int b = lo, n_b = s_pref[b + 1] - s_pref[b];
-    const long long rel = v - (long long)p.Hkv * (s_pref[b] + (long long)b * p.pair_cost);
-    int hkv = (int)(rel / (n_b + p.pair_cost));
+    const int rel = (int)(v - (I)p.Hkv * (s_pref[b] + (I)b * p.pair_cost));   // < Hkv * (n_b + E)
+    int hkv = rel / (n_b + p.pair_cost);
     hkv = hkv > p.Hkv - 1 ? p.Hkv - 1 : hkv;
-    const long long r = rel - (long long)hkv * (n_b + p.pair_cost) - p.pair_cost;
-    return (long long)p.Hkv * s_pref[b] + (long long)hkv * n_b + (r > 0 ? (r < n_b ? r : n_b) : 0);
+    const int rr = rel - hkv * (n_b + p.pair_cost) - p.pair_cost;
+    r.b = b; r.hkv = hkv; r.t = rr > 0 ? (rr < n_b ? rr : n_b) : 0;
+    r.flat = p.Hkv * s_pref[b] + hkv * n_b + r.t;
+    if (r.t == n_b) {   // (not reached: rr < n_b by construction; kept so that t is always a tile of the pair)
+        r.t = 0;
+        if (++r.hkv == p.Hkv) { r.hkv = 0; ++r.b; }
+    }
+    return r;
 }
 
 __device__ inline u32x4 ld16(const void *ptr) { return *reinterpret_cast<const u32x4 *>(ptr); }
@@ -219,17 +229,13 @@ enum {
 };
 constexpr int kDescSlots = 256;
 
-// Descriptor of tile i of the range that starts at unit lo and holds n_iter tiles.
+// Descriptor of tile idx of pair (b, hkv); it is tile i_tile of a range of n_tiles tiles.
 // `table` is the page table or a copy of it; `s_len` the clamped lengths in LDS, or null.
-__device__ inline void build_desc(const AttnParams &p, const int32_t *table, const int32_t *__restrict__ seq_lens,
-                                  const int *s_len, const int *s_pref, long long lo, int n_iter, int i, TileDesc *slot,
-                                  int &bad, int range_id) {
-    const long long x = lo + i;
-    const int b = find_seq(s_pref, p.B, p.Hkv, x);
+__device__ inline void write_tile_desc(const AttnParams &p, const int32_t *table, const int32_t *__restrict__ seq_lens,
+                                       const int *s_len, const int *s_pref, int b, int hkv, int idx, int i_tile,
+                                       int n_tiles, TileDesc *slot, int &bad, int range_id) {
     const int L = s_len ? s_len[b] : clamp_len(p, seq_lens, b);
     const int n_pre = (L + kTile - 1) / kTile, n_units = n_pre + p.n_tree_tiles;
-    const int rel = (int)(x - (long long)p.Hkv * s_pref[b]);
-    const int hkv = rel / n_units, idx = rel - hkv * n_units;
     int blk[4], n_valid, flags = 0;
     if (idx < n_pre) {
         n_valid = min(kTile, L - idx * kTile);
@@ -253,60 +259,53 @@ __device__ inline void build_desc(const AttnParams &p, const int32_t *table, con
         flags |= kDescPairStart;
         // for the merge kernel: which workgroups hold tiles of this pair
         int2 *info = reinterpret_cast<int2 *>(p.pair_info) + (b * p.Hkv + hkv);
-        *info = make_int2(range_id, range_of_unit(cost_pos_of_tile(p, s_pref, b, hkv, n_units - 1),
-                                                         cost_total(p, s_pref), p.n_ranges));
+        const int w_last =
+            p.axis32 ? range_of_position<int>(cost_pos_of_tile<int>(p, s_pref, b, hkv, n_units - 1),
+                                              cost_total<int>(p, s_pref), p.n_ranges)
+                     : range_of_position<long long>(cost_pos_of_tile<long long>(p, s_pref, b, hkv, n_units - 1),
+                                                    cost_total<long long>(p, s_pref), p.n_ranges);
+        *info = make_int2(range_id, w_last);
     }
     if (idx + 1 == n_units) flags |= kDescPairEnd;
-    if (idx == 0 || i == 0) {
+    if (idx == 0 || i_tile == 0) {
         flags |= kDescFresh;
-        if (idx + (n_iter - i) > n_pre) flags |= kDescMasks;
+        if (idx + (n_tiles - i_tile) > n_pre) flags |= kDescMasks;
     }
     int4 *dst = reinterpret_cast<int4 *>(slot);
     dst[0] = make_int4(blk[0], blk[1], blk[2], blk[3]);
     dst[1] = make_int4(n_valid, flags, b, hkv);
 }
 
-// Pair (sequence * Hkv + kv head) of flat tile x.
-__device__ inline int pair_of_tile(const int *s_pref, int B, int Hkv, long long x) {
-    const int b = find_seq(s_pref, B, Hkv, x);
-    const int n_b = s_pref[b + 1] - s_pref[b];
-    return b * Hkv + (int)((x - (long long)Hkv * s_pref[b]) / n_b);
-}
-
-// Up to 128 query rows: the list holds, in front of every segment, one query unit (the pair's
-// query rows, which travel through the ring like a tile).  Item i of the list of tile range
-// [lo, lo + n_tiles), whose first tile belongs to pair q_lo:
-//   the query unit of pair q > q_lo sits at position start(q) - lo + (q - q_lo), followed by the
-//   pair's tiles; the first segment's query unit sits at position 0, followed by tile lo.
+// Item i of the list of a range of n_tiles tiles that starts at tile `start`.  The items are
+// the tiles in order; with kWithQ every segment (the part of a pair inside the range) is
+// preceded by one query unit: the pair's query rows, which travel through the ring like a
+// tile.  The item is found by walking the pairs from the start of the range (a range holds
+// few pairs unless the sequences are very short); i must be below the number of items.
+template <bool kWithQ>
 __device__ inline void build_item(const AttnParams &p, const int32_t *table, const int32_t *__restrict__ seq_lens,
-                                  const int *s_len, const int *s_pref, long long lo, int n_tiles, int q_lo, int i,
+                                  const int *s_len, const int *s_pref, const TilePos &start, int n_tiles, int i,
                                   TileDesc *slot, int &bad, int range_id) {
-    const long long target = lo + q_lo + i;   // largest pair q with start(q) + q <= target owns item i
-    int blo = 0, bhi = p.B - 1;
-    while (blo < bhi) {
-        const int mid = (blo + bhi + 1) >> 1;
-        if ((long long)p.Hkv * (s_pref[mid] + mid) <= target) blo = mid; else bhi = mid - 1;
-    }
-    int b = blo;
-    const int n_b = s_pref[b + 1] - s_pref[b];
-    int hkv = (int)((target - (long long)p.Hkv * (s_pref[b] + b)) / (n_b + 1));
-    hkv = hkv > p.Hkv - 1 ? p.Hkv - 1 : hkv;
-    const int q = b * p.Hkv + hkv;
-    long long pos_q = 0, first_tile = lo;
-    if (q > q_lo) {
-        first_tile = (long long)p.Hkv * s_pref[b] + (long long)hkv * n_b;
-        pos_q = first_tile - lo + (q - q_lo);
-    } else {
-        b = q_lo / p.Hkv;
-        hkv = q_lo - b * p.Hkv;
-    }
-    if (i == pos_q) {
-        int4 *dst = reinterpret_cast<int4 *>(slot);
-        dst[0] = make_int4(-1, -1, -1, -1);
-        dst[1] = make_int4(0, kDescQ, b, hkv);
-    } else {
-        build_desc(p, table, seq_lens, s_len, s_pref, lo, n_tiles, (int)(first_tile + (i - pos_q - 1) - lo), slot, bad,
-                   range_id);
+    int b = start.b, hkv = start.hkv, t = start.t, pos = i, tiles_before = 0;
+    while (b < p.B) {
+        if (kWithQ) {
+            if (pos == 0) {
+                int4 *dst = reinterpret_cast<int4 *>(slot);
+                dst[0] = make_int4(-1, -1, -1, -1);
+                dst[1] = make_int4(0, kDescQ, b, hkv);
+                return;
+            }
+            --pos;
+        }
+        const int avail = s_pref[b + 1] - s_pref[b] - t;   // tiles of this pair from t on
+        if (pos < avail) {
+            write_tile_desc(p, table, seq_lens, s_len, s_pref, b, hkv, t + pos, tiles_before + pos, n_tiles, slot, bad,
+                            range_id);
+            return;
+        }
+        pos -= avail;
+        tiles_before += avail;
+        t = 0;
+        if (++hkv == p.Hkv) { hkv = 0; ++b; }
     }
 }
 
@@ -512,13 +511,15 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     // same values, so a wavefront may read them back without a barrier (its own LDS accesses
     // execute in order).
     int *s_len = p.B <= kMaxLensInLds ? s_pref + p.B + 1 : nullptr;
-    if (p.B <= 64) {
-        int v = 0;
+    TilePos lo, hi;
+    if (p.B <= 64 && p.Hkv <= 64 && p.axis32) {
+        int units = 0;
         if (lane < p.B) {
             const int L = clamp_len(p, seq_lens, lane);
             s_len[lane] = L;
-            v = (L + kTile - 1) / kTile + p.n_tree_tiles;
+            units = (L + kTile - 1) / kTile + p.n_tree_tiles;
         }
+        int v = units;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const int t = __shfl_up(v, off);
@@ -526,33 +527,79 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         }
         if (lane < p.B) s_pref[lane + 1] = v;
         if (lane == 0) s_pref[0] = 0;
+        // This workgroup's tiles: [lo, hi) of the tile axis, an even share of the cost axis.  Lane b
+        // holds sequence b's tile count and the tiles in front of it, so a place on the cost axis
+        // is found with two votes (which sequence, which kv head) instead of searches and divisions.
+        const int excl = v - units;
+        const int base = p.Hkv * (excl + lane * p.pair_cost);   // where sequence `lane` starts on the cost axis
+        const int total = __shfl(v, p.B - 1);
+        const int cost_all = p.Hkv * (total + p.B * p.pair_cost);
+        auto locate_by_vote = [&](int pos) {
+            TilePos r;
+            if (pos >= cost_all) {
+                r.b = p.B; r.hkv = 0; r.t = 0; r.flat = p.Hkv * total;
+                return r;
+            }
+            const int b = __popcll(__ballot(lane < p.B && base <= pos)) - 1;   // pos >= 0 = base of sequence 0
+            const int span = __shfl(units, b) + p.pair_cost;                    // cost positions per pair
+            const int rel = pos - __shfl(base, b);
+            const int hkv = __popcll(__ballot(lane < p.Hkv && lane * span <= rel)) - 1;
+            const int rr = rel - hkv * span - p.pair_cost;
+            r.b = b; r.hkv = hkv; r.t = rr > 0 ? rr : 0;
+            r.flat = p.Hkv * __shfl(excl, b) + hkv * (span - p.pair_cost) + r.t;
+            return r;
+        };
+        lo = locate_by_vote(range_begin<int>(range_id, cost_all, p.n_ranges));
+        hi = locate_by_vote(range_begin<int>(range_id + 1, cost_all, p.n_ranges));
     } else {
-        scan_units(p, seq_lens, s_pref, s_wsum, s_len);
+        if (p.B <= 64) {
+            int v = 0;
+            if (lane < p.B) {
+                const int L = clamp_len(p, seq_lens, lane);
+                s_len[lane] = L;
+                v = (L + kTile - 1) / kTile + p.n_tree_tiles;
+            }
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int t = __shfl_up(v, off);
+                if (lane >= off) v += t;
+            }
+            if (lane < p.B) s_pref[lane + 1] = v;
+            if (lane == 0) s_pref[0] = 0;
+        } else {
+            scan_units(p, seq_lens, s_pref, s_wsum, s_len);
+        }
+        // this workgroup's tiles: [lo, hi) of the tile axis, an even share of the cost axis
+        if (p.axis32) {
+            const int cost_all = cost_total<int>(p, s_pref);
+            lo = locate<int>(p, s_pref, range_begin<int>(range_id, cost_all, p.n_ranges));
+            hi = locate<int>(p, s_pref, range_begin<int>(range_id + 1, cost_all, p.n_ranges));
+        } else {
+            const long long cost_all = cost_total<long long>(p, s_pref);
+            lo = locate<long long>(p, s_pref, range_begin<long long>(range_id, cost_all, p.n_ranges));
+            hi = locate<long long>(p, s_pref, range_begin<long long>(range_id + 1, cost_all, p.n_ranges));
+        }
     }
-    // this workgroup's tiles: [lo, hi) of the flat tile axis, an even share of the cost axis
-    const long long cost_all = cost_total(p, s_pref);
-    const long long lo = __builtin_amdgcn_readfirstlane((int)tiles_below_cost(p, s_pref, range_begin(range_id, cost_all, p.n_ranges)));
-    const long long hi = __builtin_amdgcn_readfirstlane((int)tiles_below_cost(p, s_pref, range_begin(range_id + 1, cost_all, p.n_ranges)));
+    lo.b = __builtin_amdgcn_readfirstlane(lo.b); lo.hkv = __builtin_amdgcn_readfirstlane(lo.hkv);
+    lo.t = __builtin_amdgcn_readfirstlane(lo.t); lo.flat = __builtin_amdgcn_readfirstlane(lo.flat);
+    hi.b = __builtin_amdgcn_readfirstlane(hi.b); hi.hkv = __builtin_amdgcn_readfirstlane(hi.hkv);
+    hi.t = __builtin_amdgcn_readfirstlane(hi.t); hi.flat = __builtin_amdgcn_readfirstlane(hi.flat);
     if (table_in_lds) {
         wait_vmcnt<0>();
         __syncthreads();   // the copy of the page table is complete (every wavefront reaches this)
     }
-    if (chunk_id == 0 && tid == 0) p.range_tiles[range_id] = (int)(hi - lo);
-    if (lo >= hi) return;
-    const int n_tiles = (int)(hi - lo);
+    const int n_tiles = hi.flat - lo.flat;
+    if (chunk_id == 0 && tid == 0) p.range_tiles[range_id] = n_tiles;
+    if (n_tiles <= 0) return;
     // items of the list: the tiles, and with dedicated copy wavefronts one query unit per segment
-    int q_lo = 0, n_iter = n_tiles;
-    if (kDma) {
-        q_lo = __builtin_amdgcn_readfirstlane(pair_of_tile(s_pref, p.B, p.Hkv, lo));
-        n_iter += 1 + __builtin_amdgcn_readfirstlane(pair_of_tile(s_pref, p.B, p.Hkv, hi - 1)) - q_lo;
-    }
+    // (one segment per pair the range touches)
+    int n_iter = n_tiles;
+    if (kDma) n_iter += (hi.b * p.Hkv + hi.hkv) - (lo.b * p.Hkv + lo.hkv) + (hi.t > 0 ? 1 : 0);
 
     int bad = 0;
     auto write_item = [&](int i) {
-        if (kDma) build_item(p, i < kDescSlots ? table : page_table, seq_lens, s_len, s_pref, lo, n_tiles, q_lo, i,
-                             s_desc + (i & (kDescSlots - 1)), bad, range_id);
-        else build_desc(p, i < kDescSlots ? table : page_table, seq_lens, s_len, s_pref, lo, n_tiles, i,
-                        s_desc + (i & (kDescSlots - 1)), bad, range_id);
+        build_item<kDma>(p, i < kDescSlots ? table : page_table, seq_lens, s_len, s_pref, lo, n_tiles, i,
+                         s_desc + (i & (kDescSlots - 1)), bad, range_id);
     };
     if (htid >= 0)
         for (int i = htid; i < min(n_iter, kDescSlots); i += kHelpers) write_item(i);

@@ -105,6 +105,16 @@ def test_attn_ranges_longer_than_the_tile_list(R, oracle_mod, T, Hq, monkeypatch
     check_attn(R, oracle_mod, w)
 
 
+@pytest.mark.parametrize("T,Hq", [(16, 8), (48, 16)])
+def test_attn_ranges_cut_with_64_bit_arithmetic(R, oracle_mod, T, Hq, monkeypatch):
+    # the kernel cuts its ranges in 32-bit arithmetic when the host can show that nothing
+    # overflows, else in 64-bit: force the second path on a ragged batch
+    monkeypatch.setenv("READER_ATTN_AXIS64", "1")
+    w = W.make_custom("axis64", B=5, Hq=Hq, Hkv=4, D=128, T=T, seq_lens=[1, 900, 64, 2051, 130], tree="trie",
+                      depth=5, seed=406)
+    check_attn(R, oracle_mod, w)
+
+
 def test_attn_custom_scale_and_peaked_scores(R, oracle_mod):
     w = W.make_custom("peaked", B=1, Hq=8, Hkv=2, D=128, T=16, seq_lens=[700], tree="trie", depth=5,
                       k_outlier_frac=0.05, seed=402)
