@@ -177,3 +177,50 @@ def target_argmax(logits):
         raise ValueError("oracle_target_argmax failed (rc=%d)" % rc)
     return out.reshape(logits.shape[:-1])
 
+
+
+def _bf16_bits_to_f64(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def target_sample(logits, parents, uniforms, temperature=1.0, with_cdf=False):
+    """The base model's tokens under a sampling policy (Appendix C, randomized decoding):
+    the policy is a map F(distribution, u) with one uniform u per decoding position, and the
+    speculative run uses the same uniforms as the plain run.  Here F is inverse-CDF sampling
+    of softmax(logits / temperature): the token is the lowest index k whose cumulative
+    probability exceeds u.  Node n of sequence b stands for the position depth(n) behind the
+    root, so every node of one depth draws with the same uniform: u = uniforms[b, depth(n)].
+
+    logits: uint16 (bf16 bits) [B, T, V]; parents: int32 [B, T]; uniforms: float [B, T] in
+    [0, 1).  A NaN logit carries no probability.  Returns int32 [B, T]; with_cdf=True also
+    returns, per node, (threshold, total) = (u * sum of weights, sum of weights) and the row's
+    cumulative weights are recomputable from them (used by tolerance checks in tests).
+    Plain numpy in double precision, one row at a time, nothing blocked or fused."""
+    B, T, V = logits.shape
+    assert parents.shape == (B, T) and uniforms.shape == (B, T) and temperature > 0
+    out = np.zeros((B, T), dtype=np.int32)
+    thr = np.zeros((B, T), dtype=np.float64)
+    tot = np.zeros((B, T), dtype=np.float64)
+    for b in range(B):
+        _, depth = ancestor_mask(np.ascontiguousarray(parents[b], dtype=np.int32))
+        for n in range(T):
+            x = _bf16_bits_to_f64(logits[b, n])
+            x = np.where(np.isnan(x), -np.inf, x)
+            m = x.max()
+            w = np.exp((x - m) / temperature) if np.isfinite(m) else np.zeros(V)
+            cdf = np.cumsum(w)
+            t = float(uniforms[b, depth[n]]) * cdf[-1]
+            k = int(np.searchsorted(cdf, t, side="right"))      # first index with cdf > t
+            if k >= V:                                            # u * total rounded up to the total
+                k = int(np.flatnonzero(w > 0)[-1]) if cdf[-1] > 0 else 0
+            out[b, n], thr[b, n], tot[b, n] = k, t, cdf[-1]
+    return (out, thr, tot) if with_cdf else out
+
+
+def target_sample_weights(logits_row, temperature=1.0):
+    """Cumulative weights of one row as target_sample forms them (double precision)."""
+    x = _bf16_bits_to_f64(logits_row)
+    x = np.where(np.isnan(x), -np.inf, x)
+    m = x.max()
+    w = np.exp((x - m) / temperature) if np.isfinite(m) else np.zeros(x.shape[0])
+    return np.cumsum(w)
