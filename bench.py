@@ -263,32 +263,36 @@ def time_rearrange(R, torch, W, reps=10):
             "ms_per_step_amortised_over_25": ms / 25}
 
 
-def time_argmax(R, torch, reps=20):
-    """Greedy target tokens from base-model logits (vocabulary 128256) for the rows of one step of the
-    headline preset (B*T = 512) and of the large-batch preset (4096); the logits are filled on the device."""
-    import numpy as np
-    out = {}
-    V = 128256
+def time_target_tokens(R, torch, reps=20):
+    """Target tokens from base-model logits (vocabulary 128256) for the rows of one step of the headline
+    preset (B*T = 512) and of the large-batch preset (4096): the greedy arg max, and the sampling policy with
+    coupled uniforms (temperature 1, a chain of 32 nodes per sequence).  The logits are filled on the device."""
+    greedy, sampled = {}, {}
+    V, T = 128256, 32
     for name, rows in (("rows_512", 512), ("rows_4096", 4096)):
         n_buf = max(2, -(-ROTATE_BYTES // (rows * V * 2)))         # rotate so that the 256 MB cache cannot serve it
-        logits = [torch.randn((rows, V), device="cuda", dtype=torch.bfloat16) for _ in range(n_buf)]
-        tok = torch.zeros(rows, dtype=torch.int32, device="cuda")
-        for l in logits[:2]:
-            R.reader_target_argmax(l, tok)
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for k in range(reps):
-            R.reader_target_argmax(logits[k % n_buf], tok)
-        b.record()
-        torch.cuda.synchronize()
-        ms = a.elapsed_time(b) / reps
+        logits = [torch.randn((rows // T, T, V), device="cuda", dtype=torch.bfloat16) for _ in range(n_buf)]
+        tok = torch.zeros((rows // T, T), dtype=torch.int32, device="cuda")
+        parents = (torch.arange(T, dtype=torch.int32, device="cuda") - 1).repeat(rows // T, 1).contiguous()
+        uniforms = torch.rand((rows // T, T), device="cuda", dtype=torch.float32).clamp_(max=1.0 - 2.0 ** -24)
         nbytes = rows * V * 2
-        out[name] = {"ms": ms, "bytes": nbytes, "hbm_gbs": nbytes / (ms * 1e-3) / 1e9,
-                     "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        for label, res, call in (("argmax", greedy, lambda l: R.reader_target_argmax(l, tok)),
+                                 ("sample", sampled, lambda l: R.reader_target_sample(l, parents, uniforms, 1.0, tok))):
+            for l in logits[:2]:
+                call(l)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for k in range(reps):
+                call(logits[k % n_buf])
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / reps
+            res[name] = {"ms": ms, "bytes": nbytes, "hbm_gbs": nbytes / (ms * 1e-3) / 1e9,
+                         "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         del logits
         torch.cuda.empty_cache()
-    return out
+    return greedy, sampled
 
 
 def main():
@@ -376,7 +380,7 @@ def main():
         log("timing the periodic rearrangement pass")
         line["kv_rearrange"] = time_rearrange(R, torch, W)
         log("timing the arg max over logits")
-        line["target_argmax"] = time_argmax(R, torch)
+        line["target_argmax"], line["target_sample"] = time_target_tokens(R, torch)
     print(json.dumps(line), flush=True)
 
 

@@ -240,6 +240,36 @@ int reader_kv_rearrange(int32_t NL, int32_t B, int32_t S, int32_t Hkv, int32_t D
 int reader_target_argmax(int32_t rows, int32_t V, const void *logits, int32_t *target_tokens, void *stream);
 
 /*
+ * The base model's tokens under a sampling policy (Appendix C, randomized decoding).  The
+ * policy is a map F(distribution, u) fed with one uniform per decoding position, and the
+ * speculative run draws with the same uniforms as the plain run, which makes the two runs
+ * emit the same tokens.  F is inverse-CDF sampling of softmax(logits / temperature):
+ *   target_tokens[b][n] = lowest k with  sum_{v <= k} w_v  >  u * sum_v w_v,
+ *   w_v = exp((logits[b][n][v] - max_v logits[b][n][v]) / temperature),
+ *   u = uniforms[b][depth(n)]   (the root has depth 0; every node of one depth stands for the
+ *                                same position and therefore draws with the same uniform).
+ * The result is the target_tokens input of reader_accept_path, whose bonus token is then the
+ * policy's own draw at the first position the draft does not cover.  Top-k / top-p filtering
+ * is not applied.
+ *
+ *   logits         bf16 [B, T, V]  in    a NaN carries no probability; +inf is not allowed
+ *   parents        i32  [B, T]     in    as for reader_tree_attn; a pointer that does not lead
+ *                                        towards the root ends the depth walk there
+ *   uniforms       f32  [B, T]     in    values in [0, 1); entry d serves depth d
+ *   temperature    > 0, finite
+ *   target_tokens  i32  [B, T]     out   a token of zero weight is never returned; a row
+ *                                        without any weight gives 0
+ * Sums are formed in fp32 (blocks of 512 tokens, then over the blocks): where u * total lies
+ * within rounding (about 1e-5 of the total) of a boundary between two tokens' cumulative
+ * weights, either of them may be returned.
+ * Returns READER_OK or READER_EINVAL (B < 0, T outside 1..READER_MAX_T, V outside
+ * 1..READER_MAX_SAMPLE_V, temperature not positive and finite, null pointer).
+ */
+#define READER_MAX_SAMPLE_V 4194304
+int reader_target_sample(int32_t B, int32_t T, int32_t V, const void *logits, const int32_t *parents,
+                         const float *uniforms, float temperature, int32_t *target_tokens, void *stream);
+
+/*
  * Measurement hooks for benchmarks (not operations of the method).  While enabled,
  * every reader_tree_attn / reader_verify_step call launches its main streaming kernel
  * with a HIP event pair that takes the kernel's own start and end time stamps (the

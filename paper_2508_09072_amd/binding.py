@@ -27,7 +27,7 @@ STATUS_BAD_PATH = 4
 EXPORTS = (
     "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",
     "reader_tree_attn", "reader_accept_path", "reader_kv_compact", "reader_verify_step",
-    "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax",
+    "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax", "reader_target_sample",
     "reader_profile_enable", "reader_profile_collect",
 )
 
@@ -85,6 +85,8 @@ def load():
     lib.reader_kv_rearrange.argtypes = [i32] * 5 + [vp] * 5 + [ctypes.c_size_t, vp]
     lib.reader_target_argmax.restype = ctypes.c_int
     lib.reader_target_argmax.argtypes = [i32, i32, vp, vp, vp]
+    lib.reader_target_sample.restype = ctypes.c_int
+    lib.reader_target_sample.argtypes = [i32, i32, i32, vp, vp, vp, ctypes.c_float, vp, vp]
     lib.reader_profile_enable.restype = ctypes.c_int
     lib.reader_profile_enable.argtypes = [i32]
     lib.reader_profile_collect.restype = ctypes.c_int
@@ -214,6 +216,17 @@ def reader_target_argmax(logits, target_tokens):
     assert target_tokens.numel() == rows
     code = load().reader_target_argmax(rows, V, _dev(logits, torch.bfloat16), _dev(target_tokens, torch.int32), _stream())
     _check(code, "reader_target_argmax")
+
+
+def reader_target_sample(logits, parents, uniforms, temperature, target_tokens):
+    """logits: bf16 [B, T, V]; parents: int32 [B, T]; uniforms: float32 [B, T]; target_tokens: int32 [B, T]."""
+    import torch
+    B, T, V = logits.shape
+    assert tuple(parents.shape) == (B, T) and tuple(uniforms.shape) == (B, T) and tuple(target_tokens.shape) == (B, T)
+    code = load().reader_target_sample(B, T, V, _dev(logits, torch.bfloat16), _dev(parents, torch.int32),
+                                       _dev(uniforms, torch.float32), float(temperature),
+                                       _dev(target_tokens, torch.int32), _stream())
+    _check(code, "reader_target_sample")
 
 
 def reader_profile_enable(on: bool) -> None:

@@ -401,3 +401,26 @@ def make_padded_cache(name: str, NL: int, B: int, Hkv: int, D: int, prompt_lens:
     k = np.where(hole, np.uint16(0), k).astype(np.uint16)
     v = np.where(hole, np.uint16(0), v).astype(np.uint16)
     return PaddedCache(name=name, k_pad=np.ascontiguousarray(k), v_pad=np.ascontiguousarray(v), valid=valid)
+
+
+# ---------------------------------------------------------------------------------------------
+# Base-model logits for the target-token step (Algorithm 5; Appendix C for the sampling policy)
+
+def make_logits(B: int, T: int, V: int, rng: np.random.Generator, peaked: bool = True) -> np.ndarray:
+    """bf16 bit patterns [B, T, V] shaped like a language model's output: a broad body of
+    unlikely tokens (normal, sigma 2) and, when `peaked`, a handful of candidates per row that
+    carry most of the probability (raised by 6..12), as trained models produce."""
+    x = rng.standard_normal((B, T, V), dtype=np.float32) * 2.0
+    if peaked and V >= 8:
+        n_top = min(6, V // 2)
+        for b in range(B):
+            for t in range(T):
+                idx = rng.choice(V, size=n_top, replace=False)
+                x[b, t, idx] += rng.uniform(6.0, 12.0, size=n_top).astype(np.float32)
+    return to_bf16_bits(x)
+
+
+def make_uniforms(B: int, T: int, rng: np.random.Generator) -> np.ndarray:
+    """One uniform in [0, 1) per (sequence, depth), float32."""
+    u = rng.random((B, T), dtype=np.float32)
+    return np.minimum(u, np.float32(1.0 - 2.0 ** -24))

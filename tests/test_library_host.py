@@ -125,3 +125,23 @@ def test_rearrange_arguments_are_checked_on_the_host(R):
     assert lib.reader_kv_rearrange(1, 2, 8, 2, 128, one, one, one, one, one, 16, None) == R.READER_EWORKSPACE
     assert lib.reader_kv_rearrange(1, 0, 8, 2, 128, None, None, None, None, None, 0, None) == R.READER_OK   # empty batch
 
+
+
+def test_target_token_arguments_are_checked_on_the_host(R):
+    lib = R.load()
+    one = ctypes.c_void_p(256)
+    assert lib.reader_target_argmax(-1, 10, one, one, None) == R.READER_EINVAL
+    assert lib.reader_target_argmax(4, 0, one, one, None) == R.READER_EINVAL
+    assert lib.reader_target_argmax(4, 10, None, one, None) == R.READER_EINVAL
+    assert lib.reader_target_argmax(0, 10, None, None, None) == R.READER_OK
+    s = lib.reader_target_sample
+    assert s(-1, 4, 10, one, one, one, 1.0, one, None) == R.READER_EINVAL
+    assert s(2, 0, 10, one, one, one, 1.0, one, None) == R.READER_EINVAL
+    assert s(2, 129, 10, one, one, one, 1.0, one, None) == R.READER_EINVAL          # more nodes than a tree may have
+    assert s(2, 4, 0, one, one, one, 1.0, one, None) == R.READER_EINVAL
+    assert s(2, 4, (1 << 22) + 1, one, one, one, 1.0, one, None) == R.READER_EINVAL  # vocabulary beyond the limit
+    for bad in (0.0, -1.0, float("inf"), float("nan")):
+        assert s(2, 4, 10, one, one, one, bad, one, None) == R.READER_EINVAL
+    assert s(2, 4, 10, None, one, one, 1.0, one, None) == R.READER_EINVAL
+    assert s(2, 4, 10, one, one, None, 1.0, one, None) == R.READER_EINVAL
+    assert s(0, 4, 10, None, None, None, 1.0, None, None) == R.READER_OK             # empty batch
