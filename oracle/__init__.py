@@ -224,3 +224,33 @@ def target_sample_weights(logits_row, temperature=1.0):
     m = x.max()
     w = np.exp((x - m) / temperature) if np.isfinite(m) else np.zeros(x.shape[0])
     return np.cumsum(w)
+
+
+def kv_compact_layers(k_cache, v_cache, path, accept_len, page_table, seq_lens):
+    """Compaction for the in-cache layout, all layers at once, IN PLACE (Section 4.3 /
+    Algorithm 4 applied every step).  During the step every layer wrote the K/V rows of the
+    draft tree behind the sequence: node n of sequence b sits at position seq_lens[b] + n.
+    Afterwards the accepted path becomes the sequence's next rows: for j = 0..accept_len[b]
+    position seq_lens[b] + j receives what position seq_lens[b] + path[b][j] held BEFORE the
+    pass, in every layer, K and V, all heads; then seq_lens[b] += accept_len[b] + 1.  Rows
+    behind the new length keep whatever they held (the next step overwrites them).
+
+    k_cache, v_cache: uint16 (bf16 bits) [NL, num_pages, Hkv, page_size, D]; path int32
+    [B, max_path]; accept_len int32 [B]; page_table int32 [B, max_pages]; seq_lens int32 [B].
+    The definition written out with numpy indexing: gather the old rows, then scatter."""
+    NL, num_pages, Hkv, page_size, D = k_cache.shape
+    assert v_cache.shape == k_cache.shape
+    B = path.shape[0]
+    for b in range(B):
+        L, n = int(seq_lens[b]), int(accept_len[b])
+        nodes = path[b, : n + 1].astype(np.int64)
+        assert nodes[0] == 0 and np.all(np.diff(nodes) > 0), "a path runs from the root through increasing node ids"
+        src = L + nodes
+        dst = L + np.arange(n + 1)
+        sp, ss = page_table[b, src // page_size], src % page_size
+        dp, ds = page_table[b, dst // page_size], dst % page_size
+        assert sp.min() >= 0 and dp.min() >= 0 and max(sp.max(), dp.max()) < num_pages, "page table out of range"
+        for cache in (k_cache, v_cache):
+            old = cache[:, sp, :, ss, :].copy()          # [rows, NL, Hkv, D] (advanced indices first)
+            cache[:, dp, :, ds, :] = old
+        seq_lens[b] = L + n + 1

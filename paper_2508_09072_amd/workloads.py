@@ -424,3 +424,76 @@ def make_uniforms(B: int, T: int, rng: np.random.Generator) -> np.ndarray:
     """One uniform in [0, 1) per (sequence, depth), float32."""
     u = rng.random((B, T), dtype=np.float32)
     return np.minimum(u, np.float32(1.0 - 2.0 ** -24))
+
+
+# ---------------------------------------------------------------------------------------------
+# In-cache layout of a step, all layers (Section 4.3): the tree's K/V rows were written behind
+# each sequence by the forward pass; compaction moves the accepted path's rows forward in place.
+
+@dataclasses.dataclass
+class InCacheStep:
+    """k_cache, v_cache: uint16 (bf16 bits) [NL, num_pages, Hkv, page_size, D]; positions
+    [0, seq_lens[b] + T) of every sequence hold data (prefix, then tree node n at
+    seq_lens[b] + n), every other slot the canary.  path / accept_len: one root-to-node path
+    per sequence (node ids increase along a path because a parent precedes its children)."""
+    name: str
+    k_cache: np.ndarray
+    v_cache: np.ndarray
+    page_table: np.ndarray
+    seq_lens: np.ndarray
+    parents: np.ndarray
+    path: np.ndarray
+    accept_len: np.ndarray
+    T: int
+    max_path: int
+
+    def moved_bytes(self) -> int:
+        """Bytes the pass must move: every accepted row that is not already in place, read
+        and written once, K and V, all layers and heads."""
+        NL, _, Hkv, _, D = self.k_cache.shape
+        rows = 0
+        for b in range(self.path.shape[0]):
+            n = int(self.accept_len[b])
+            rows += int(np.sum(self.path[b, : n + 1] != np.arange(n + 1)))
+        return rows * NL * Hkv * D * 2 * 2 * 2
+
+
+def make_incache_step(name: str, B: int, T: int, Hkv: int, D: int, num_layers: int, seq_lens: Sequence[int],
+                      max_path: int = 0, seed: int = 0, page_size: int = PAGE_SIZE,
+                      accept_bias: float = 0.5) -> InCacheStep:
+    rng = np.random.Generator(np.random.PCG64(seed))
+    max_path = max_path or min(T, 16)
+    seq = np.asarray(seq_lens, dtype=np.int32)
+    n_pages_b = [(int(seq[b]) + T + page_size - 1) // page_size for b in range(B)]
+    max_pages = max(n_pages_b) if B else 1
+    num_pages = int(sum(n_pages_b)) + 3
+    perm = rng.permutation(num_pages)
+    page_table = np.full((B, max_pages), -1, dtype=np.int32)
+    k_cache = np.full((num_layers, num_pages, Hkv, page_size, D), CANARY, dtype=np.uint16)
+    v_cache = np.full((num_layers, num_pages, Hkv, page_size, D), CANARY, dtype=np.uint16)
+    parents = np.full((B, T), -1, dtype=np.int32)
+    path = np.full((B, max_path), -1, dtype=np.int32)
+    accept_len = np.zeros(B, dtype=np.int32)
+    cursor = 0
+    for b in range(B):
+        pages = perm[cursor: cursor + n_pages_b[b]]
+        cursor += n_pages_b[b]
+        page_table[b, : n_pages_b[b]] = pages
+        n_pos = int(seq[b]) + T
+        for cache in (k_cache, v_cache):
+            rows = to_bf16_bits(rng.standard_normal((num_layers, n_pos, Hkv, D), dtype=np.float32))
+            pos = np.arange(n_pos)
+            cache[:, pages[pos // page_size], :, pos % page_size, :] = rows.transpose(1, 0, 2, 3)
+        # a tree: mostly deep (a parent close behind), so that paths are long
+        for n in range(1, T):
+            parents[b, n] = n - 1 if rng.random() < accept_bias else rng.integers(0, n)
+        # a path: from a random node up to the root, cut to the deepest max_path - 1 non-root nodes
+        node = int(rng.integers(0, T))
+        chain = []
+        while node >= 0:
+            chain.append(node)
+            node = int(parents[b, node])
+        chain = chain[::-1][:max_path]
+        path[b, : len(chain)] = chain
+        accept_len[b] = len(chain) - 1
+    return InCacheStep(name, k_cache, v_cache, page_table, seq, parents, path, accept_len, T, max_path)
