@@ -263,6 +263,40 @@ def time_rearrange(R, torch, W, reps=10):
             "ms_per_step_amortised_over_25": ms / 25}
 
 
+def time_compact_layers(R, torch, W, reps=20):
+    """Compaction in the in-cache layout over the 32 layers of an 8B-class model, for the 16 sequences and
+    32-node trees of the headline preset (lengths scaled down: a full-length cache of 32 layers does not
+    change what the pass touches, only what sits beside it).  Each call moves the same accepted paths
+    again (the lengths are reset between calls, not timed)."""
+    import numpy as np
+    rng = np.random.Generator(np.random.PCG64(W.SEED_BASE + 78))
+    s = W.make_incache_step("bench", B=16, T=32, Hkv=8, D=128, num_layers=32,
+                            seq_lens=[int(x) for x in rng.integers(64, 257, size=16)], max_path=9, seed=W.SEED_BASE + 79)
+    NL, num_pages, Hkv, _, D = s.k_cache.shape
+    dims = R.make_dims(16, 32, 32, Hkv, D, s.page_table.shape[1], s.max_path, num_pages)
+    k = torch.from_numpy(s.k_cache.view(np.int16)).cuda().view(torch.bfloat16)
+    v = torch.from_numpy(s.v_cache.view(np.int16)).cuda().view(torch.bfloat16)
+    L0 = torch.from_numpy(s.seq_lens.copy()).cuda()
+    L = L0.clone()
+    path, acc, table = torch.from_numpy(s.path).cuda(), torch.from_numpy(s.accept_len).cuda(), torch.from_numpy(s.page_table).cuda()
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    times = []
+    for rep in range(reps + 2):
+        L.copy_(L0)
+        a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        R.reader_kv_compact_layers(dims, path, acc, k, v, table, L, status)
+        b_.record()
+        torch.cuda.synchronize()
+        if rep >= 2:
+            times.append(a.elapsed_time(b_))
+    assert int(status.item()) == 0
+    ms = float(np.median(times))
+    return {"workload": "in-cache step B=16 T=32 layers=32 Hkv=8 D=128, accepted lengths %s" % s.accept_len.tolist(),
+            "ms_per_call": ms, "algorithmic_bytes": s.moved_bytes(), "hbm_gbs": s.moved_bytes() / (ms * 1e-3) / 1e9}
+
+
 def time_target_tokens(R, torch, reps=20):
     """Target tokens from base-model logits (vocabulary 128256) for the rows of one step of the headline
     preset (B*T = 512) and of the large-batch preset (4096): the greedy arg max, and the sampling policy with
@@ -380,6 +414,7 @@ def main():
         log("timing the periodic rearrangement pass")
         line["kv_rearrange"] = time_rearrange(R, torch, W)
         log("timing the arg max over logits")
+        line["kv_compact_layers"] = time_compact_layers(R, torch, W)
         line["target_argmax"], line["target_sample"] = time_target_tokens(R, torch)
     print(json.dumps(line), flush=True)
 

@@ -182,6 +182,36 @@ int reader_kv_compact(const reader_dims *dims,
                       int32_t *seq_lens, int32_t *status, void *stream);
 
 /*
+ * Compaction in the in-cache layout, all layers of the model in one call (Section 4.3;
+ * Algorithm 4 applied every step).  The step's forward pass wrote the draft tree's K/V rows
+ * behind each sequence in every layer's cache: node n of sequence b at position
+ * seq_lens[b] + n.  For every b, layer, kv head and j = 1..accept_len[b], position
+ * seq_lens[b] + j receives the row that position seq_lens[b] + path[b][j] held before the
+ * call (the root, j = 0, is in place); then seq_lens[b] += accept_len[b] + 1.  Rows behind the
+ * new length keep what they held.  The move is done in place: node ids increase along a path
+ * (a parent precedes its children), so path[b][j] >= j and no row is overwritten before it
+ * has been read.
+ *
+ *   num_layers       >= 0 (0: only the lengths are updated)
+ *   path             i32 [B, max_path], accept_len i32 [B]               in
+ *   k_cache, v_cache bf16 [num_layers, num_pages, Hkv, page_size, D]     in/out
+ *   page_table       i32 [B, max_pages_per_seq]   in   must map pages for every position
+ *                                                      the call touches
+ *   seq_lens         i32 [B]                      in/out
+ *   status           i32 [1] or NULL              in/out
+ *
+ * A sequence whose accept_len is out of range, whose path does not start at node 0 or does
+ * not increase strictly, or that would touch a position outside the page table or a page id
+ * out of range is left untouched (cache and seq_lens) and READER_STATUS_BAD_PATH /
+ * READER_STATUS_BAD_PAGE is set.  Bit-exact copy.  dims->Hq and dims->sm_scale are not used.
+ * Returns READER_OK, READER_EINVAL (bad dims, num_layers outside 0..65535, null pointer).
+ */
+int reader_kv_compact_layers(const reader_dims *dims, int32_t num_layers,
+                             const int32_t *path, const int32_t *accept_len,
+                             void *k_cache, void *v_cache, const int32_t *page_table,
+                             int32_t *seq_lens, int32_t *status, void *stream);
+
+/*
  * One whole verification step (Algorithm 5: base-model pass over the draft tree, longest
  * accepted path; Section 4.3 / Algorithm 4: the accepted rows join the cache), with the
  * arguments, layouts, results and status bits of

@@ -27,7 +27,7 @@ STATUS_BAD_PATH = 4
 EXPORTS = (
     "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",
     "reader_tree_attn", "reader_accept_path", "reader_kv_compact", "reader_verify_step",
-    "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax", "reader_target_sample",
+    "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax", "reader_target_sample", "reader_kv_compact_layers",
     "reader_profile_enable", "reader_profile_collect",
 )
 
@@ -85,6 +85,8 @@ def load():
     lib.reader_kv_rearrange.argtypes = [i32] * 5 + [vp] * 5 + [ctypes.c_size_t, vp]
     lib.reader_target_argmax.restype = ctypes.c_int
     lib.reader_target_argmax.argtypes = [i32, i32, vp, vp, vp]
+    lib.reader_kv_compact_layers.restype = ctypes.c_int
+    lib.reader_kv_compact_layers.argtypes = [ctypes.POINTER(ReaderDims), i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.reader_target_sample.restype = ctypes.c_int
     lib.reader_target_sample.argtypes = [i32, i32, i32, vp, vp, vp, ctypes.c_float, vp, vp]
     lib.reader_profile_enable.restype = ctypes.c_int
@@ -216,6 +218,18 @@ def reader_target_argmax(logits, target_tokens):
     assert target_tokens.numel() == rows
     code = load().reader_target_argmax(rows, V, _dev(logits, torch.bfloat16), _dev(target_tokens, torch.int32), _stream())
     _check(code, "reader_target_argmax")
+
+
+def reader_kv_compact_layers(dims, path, accept_len, k_cache, v_cache, page_table, seq_lens, status=None):
+    """k_cache, v_cache: bf16 [num_layers, num_pages, Hkv, page_size, D] device tensors (moved in place)."""
+    import torch
+    NL = k_cache.shape[0]
+    assert tuple(v_cache.shape) == tuple(k_cache.shape) and k_cache.dim() == 5
+    code = load().reader_kv_compact_layers(
+        ctypes.byref(dims), NL, _dev(path, torch.int32), _dev(accept_len, torch.int32), _dev(k_cache, torch.bfloat16),
+        _dev(v_cache, torch.bfloat16), _dev(page_table, torch.int32), _dev(seq_lens, torch.int32),
+        _dev(status, torch.int32, optional=True), _stream())
+    _check(code, "reader_kv_compact_layers")
 
 
 def reader_target_sample(logits, parents, uniforms, temperature, target_tokens):

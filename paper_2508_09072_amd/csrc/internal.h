@@ -86,6 +86,15 @@ struct CompactParams {
 };
 hipError_t launch_kv_compact(const CompactParams &p, hipStream_t stream);
 
+struct CompactLayersParams {
+    uint16_t *k_cache, *v_cache;   // [NL, num_pages, Hkv, page_size, D]
+    const int32_t *path, *accept_len, *page_table;
+    int32_t *seq_lens, *status;
+    int32_t B, T, Hkv, D, max_pages, max_path, NL;
+    int64_t num_pages;
+};
+hipError_t launch_kv_compact_layers(const CompactLayersParams &p, hipStream_t stream);
+
 struct RearrangeParams {
     uint16_t *k_pad, *v_pad;   // [NL, B, S, Hkv, D]
     uint8_t *valid;            // [B, S]

@@ -291,6 +291,26 @@ extern "C" int reader_kv_compact(const reader_dims *dims, const void *k_tree, co
     return launch_kv_compact(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }
 
+extern "C" int reader_kv_compact_layers(const reader_dims *dims, int32_t num_layers, const int32_t *path,
+                                        const int32_t *accept_len, void *k_cache, void *v_cache,
+                                        const int32_t *page_table, int32_t *seq_lens, int32_t *status,
+                                        void *stream) {
+    int err = 0;
+    if (!dims_ok(dims, &err)) return err;
+    if (num_layers < 0 || num_layers > 65535) return READER_EINVAL;
+    if (dims->B == 0) return READER_OK;
+    if (!path || !accept_len || !page_table || !seq_lens || (num_layers > 0 && (!k_cache || !v_cache)))
+        return READER_EINVAL;
+    CompactLayersParams p;
+    p.k_cache = (uint16_t *)k_cache; p.v_cache = (uint16_t *)v_cache;
+    p.path = path; p.accept_len = accept_len; p.page_table = page_table;
+    p.seq_lens = seq_lens; p.status = status;
+    p.B = dims->B; p.T = dims->T; p.Hkv = dims->Hkv; p.D = dims->D;
+    p.max_pages = dims->max_pages_per_seq; p.max_path = dims->max_path; p.NL = num_layers;
+    p.num_pages = dims->num_pages;
+    return launch_kv_compact_layers(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
+}
+
 extern "C" size_t reader_kv_rearrange_scratch_bytes(int32_t B, int32_t S) {
     if (B < 0 || S < 0) return 0;
     return (((size_t)B * (size_t)S + (size_t)B * 4) * sizeof(int32_t) + 255) & ~(size_t)255;

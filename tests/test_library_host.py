@@ -145,3 +145,16 @@ def test_target_token_arguments_are_checked_on_the_host(R):
     assert s(2, 4, 10, None, one, one, 1.0, one, None) == R.READER_EINVAL
     assert s(2, 4, 10, one, one, None, 1.0, one, None) == R.READER_EINVAL
     assert s(0, 4, 10, None, None, None, 1.0, None, None) == R.READER_OK             # empty batch
+
+
+def test_layered_compaction_arguments_are_checked_on_the_host(R):
+    lib = R.load()
+    one = ctypes.c_void_p(256)
+    dims = R.make_dims(2, 16, 8, 2, 128, 8, 8, 40)
+    f = lib.reader_kv_compact_layers
+    assert f(ctypes.byref(dims), -1, one, one, one, one, one, one, None, None) == R.READER_EINVAL
+    assert f(ctypes.byref(dims), 70000, one, one, one, one, one, one, None, None) == R.READER_EINVAL
+    assert f(ctypes.byref(dims), 2, None, one, one, one, one, one, None, None) == R.READER_EINVAL
+    assert f(ctypes.byref(dims), 2, one, one, None, one, one, one, None, None) == R.READER_EINVAL
+    empty = R.make_dims(0, 16, 8, 2, 128, 8, 8, 40)
+    assert f(ctypes.byref(empty), 2, None, None, None, None, None, None, None, None) == R.READER_OK
