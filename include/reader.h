@@ -300,6 +300,58 @@ int reader_target_sample(int32_t B, int32_t T, int32_t V, const void *logits, co
                          const float *uniforms, float temperature, int32_t *target_tokens, void *stream);
 
 /*
+ * Host-side retrieval drafter over the short-term context (Section 4.2; Algorithm 2 with the
+ * trie as its only structure).  Everything below runs on the CPU with HOST pointers; it makes
+ * the token and parent arrays a verification step takes.  Not thread-safe per trie.
+ *
+ * The trie holds every n-gram of up to max_depth tokens of the sequences inserted so far, with
+ * the number of times each was seen; inserting n tokens costs O(n * max_depth).
+ * Looking up a context: the longest tail of the context (at most max_depth - 1 tokens, at least
+ * one) that is in the trie and has a continuation; a tail that is not there loses its first
+ * token and is tried again.  Continuations are ranked by descending count, equal counts in the
+ * order they were first seen.
+ */
+typedef struct reader_trie reader_trie;
+/* max_depth in 2..4096; NULL on a bad argument or when memory runs out */
+reader_trie *reader_trie_create(int32_t max_depth);
+void reader_trie_destroy(reader_trie *trie);   /* NULL is allowed */
+/* number of nodes including the root, -1 for NULL */
+int64_t reader_trie_nodes(const reader_trie *trie);
+/* READER_OK, READER_EINVAL (NULL trie, n < 0, NULL tokens), READER_EUNSUPPORTED (out of memory) */
+int reader_trie_insert(reader_trie *trie, const int32_t *tokens, int64_t n);
+/*
+ * SearchPath (Algorithm 2): starting from the context `suffix`, up to `depth` times take the
+ * best-ranked continuation of the current context and append it to the context.  Writes the k
+ * tokens found to path_tokens[0..k) and returns k (0 <= k <= depth), or -1 on a bad argument.
+ */
+int32_t reader_trie_search_path(const reader_trie *trie, const int32_t *suffix, int32_t n_suffix, int32_t depth,
+                                int32_t *path_tokens);
+/*
+ * Draft tree by depth-first extraction (Section 4.2): the root (node 0) is the last token of
+ * `suffix`; below it the continuations of the context, most frequent first, depth-first, at
+ * most max_depth levels and `budget` nodes in all.  Nodes are numbered in the order they are
+ * visited, so a parent precedes its children.  tokens, parents: i32 [budget] out.
+ * Returns the number of nodes (>= 1), or -1 on a bad argument (n_suffix < 1, budget < 1, ...).
+ */
+int32_t reader_trie_extract_tree(const reader_trie *trie, const int32_t *suffix, int32_t n_suffix,
+                                 int32_t max_depth, int32_t budget, int32_t *tokens, int32_t *parents);
+/*
+ * Attaches a path as one chain below node at_node of a tree of n_nodes nodes stored in arrays
+ * of `capacity` entries (the widening and deepening of Section 4.2 attach one retrieved
+ * path at the root, or at a drafted node); tokens that do not fit are dropped.  Returns the
+ * new number of nodes, or -1 on a bad argument.
+ */
+int32_t reader_tree_attach_path(int32_t *tokens, int32_t *parents, int32_t n_nodes, int32_t capacity,
+                                int32_t at_node, const int32_t *path_tokens, int32_t k);
+/*
+ * Self-repetition metric (Section 4.1): a pointer walks the response; at each stop the longest
+ * run of tokens starting at the pointer that also occurs in the prompt or in the part of the
+ * response already walked (entirely inside it) is skipped, or one token if there is none.
+ * Returns response tokens / number of stops (0 for an empty response, -1 on a bad argument).
+ */
+double reader_self_repetition(const int32_t *prompt, int64_t n_prompt, const int32_t *response, int64_t n_response);
+
+/*
  * Measurement hooks for benchmarks (not operations of the method).  While enabled,
  * every reader_tree_attn / reader_verify_step call launches its main streaming kernel
  * with a HIP event pair that takes the kernel's own start and end time stamps (the

@@ -28,6 +28,8 @@ EXPORTS = (
     "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",
     "reader_tree_attn", "reader_accept_path", "reader_kv_compact", "reader_verify_step",
     "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax", "reader_target_sample", "reader_kv_compact_layers",
+    "reader_trie_create", "reader_trie_destroy", "reader_trie_nodes", "reader_trie_insert", "reader_trie_search_path",
+    "reader_trie_extract_tree", "reader_tree_attach_path", "reader_self_repetition",
     "reader_profile_enable", "reader_profile_collect",
 )
 
@@ -85,6 +87,23 @@ def load():
     lib.reader_kv_rearrange.argtypes = [i32] * 5 + [vp] * 5 + [ctypes.c_size_t, vp]
     lib.reader_target_argmax.restype = ctypes.c_int
     lib.reader_target_argmax.argtypes = [i32, i32, vp, vp, vp]
+    i64 = ctypes.c_int64
+    lib.reader_trie_create.restype = vp
+    lib.reader_trie_create.argtypes = [i32]
+    lib.reader_trie_destroy.restype = None
+    lib.reader_trie_destroy.argtypes = [vp]
+    lib.reader_trie_nodes.restype = i64
+    lib.reader_trie_nodes.argtypes = [vp]
+    lib.reader_trie_insert.restype = ctypes.c_int
+    lib.reader_trie_insert.argtypes = [vp, vp, i64]
+    lib.reader_trie_search_path.restype = i32
+    lib.reader_trie_search_path.argtypes = [vp, vp, i32, i32, vp]
+    lib.reader_trie_extract_tree.restype = i32
+    lib.reader_trie_extract_tree.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+    lib.reader_tree_attach_path.restype = i32
+    lib.reader_tree_attach_path.argtypes = [vp, vp, i32, i32, i32, vp, i32]
+    lib.reader_self_repetition.restype = ctypes.c_double
+    lib.reader_self_repetition.argtypes = [vp, i64, vp, i64]
     lib.reader_kv_compact_layers.restype = ctypes.c_int
     lib.reader_kv_compact_layers.argtypes = [ctypes.POINTER(ReaderDims), i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.reader_target_sample.restype = ctypes.c_int
@@ -241,6 +260,76 @@ def reader_target_sample(logits, parents, uniforms, temperature, target_tokens):
                                        _dev(uniforms, torch.float32), float(temperature),
                                        _dev(target_tokens, torch.int32), _stream())
     _check(code, "reader_target_sample")
+
+
+def _host_i32(a):
+    import numpy as np
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, ctypes.c_void_p(a.ctypes.data)
+
+
+class Trie:
+    """The host-side n-gram trie of the retrieval drafter (numpy int32 arrays in, numpy arrays out)."""
+
+    def __init__(self, max_depth: int):
+        self._h = load().reader_trie_create(int(max_depth))
+        if not self._h:
+            raise ValueError("reader_trie_create refused max_depth=%r" % (max_depth,))
+
+    def close(self):
+        if self._h:
+            load().reader_trie_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def __len__(self):
+        return int(load().reader_trie_nodes(self._h))
+
+    def insert(self, tokens):
+        a, p = _host_i32(tokens)
+        _check(load().reader_trie_insert(self._h, p, a.size), "reader_trie_insert")
+
+    def search_path(self, suffix, depth: int):
+        import numpy as np
+        a, p = _host_i32(suffix)
+        out = np.zeros(max(int(depth), 1), dtype=np.int32)
+        k = load().reader_trie_search_path(self._h, p, a.size, int(depth), ctypes.c_void_p(out.ctypes.data))
+        if k < 0:
+            raise ValueError("reader_trie_search_path: bad argument")
+        return out[:k].copy()
+
+    def extract_tree(self, suffix, max_depth: int, budget: int):
+        import numpy as np
+        a, p = _host_i32(suffix)
+        tokens = np.zeros(max(int(budget), 1), dtype=np.int32)
+        parents = np.zeros(max(int(budget), 1), dtype=np.int32)
+        n = load().reader_trie_extract_tree(self._h, p, a.size, int(max_depth), int(budget),
+                                            ctypes.c_void_p(tokens.ctypes.data), ctypes.c_void_p(parents.ctypes.data))
+        if n < 0:
+            raise ValueError("reader_trie_extract_tree: bad argument")
+        return tokens[:n].copy(), parents[:n].copy()
+
+
+def reader_tree_attach_path(tokens, parents, n_nodes: int, at_node: int, path_tokens) -> int:
+    """tokens, parents: writable numpy int32 arrays of equal capacity; returns the new node count."""
+    import numpy as np
+    assert tokens.dtype == np.int32 and parents.dtype == np.int32 and tokens.size == parents.size
+    a, p = _host_i32(path_tokens)
+    n = load().reader_tree_attach_path(ctypes.c_void_p(tokens.ctypes.data), ctypes.c_void_p(parents.ctypes.data),
+                                       int(n_nodes), tokens.size, int(at_node), p, a.size)
+    if n < 0:
+        raise ValueError("reader_tree_attach_path: bad argument")
+    return int(n)
+
+
+def reader_self_repetition(prompt, response) -> float:
+    a, pa = _host_i32(prompt)
+    b, pb = _host_i32(response)
+    r = load().reader_self_repetition(pa, a.size, pb, b.size)
+    if r < 0:
+        raise ValueError("reader_self_repetition: bad argument")
+    return float(r)
 
 
 def reader_profile_enable(on: bool) -> None:
