@@ -9,7 +9,7 @@ instead), all on one stream, inputs resident in HBM before the clock starts.  Th
 second (B * T draft-tree nodes verified per step) together with the achieved HBM
 bandwidth of the attention kernel, which streams the K/V cache and dominates.
 
-    python bench.py --gpus 1 --steps 200 --warmup 20
+    python bench.py --gpus 1 --steps 500 --warmup 1000
 
 prints ONE JSON line.  The headline workload is the batched ragged serving preset
 (B=16, L in [1024,4096], T=32), the HBM-bound shape the 70 %-of-peak target is
@@ -332,8 +332,9 @@ def time_target_tokens(R, torch, reps=20):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=1000,
+                    help="untimed steps first; the GPU needs some tens of milliseconds of load to settle at its clocks")
     ap.add_argument("--config", type=int, default=2, help="headline preset (0..4)")
     ap.add_argument("--others", type=str, default="0,1,3,4", help="presets also timed (comma list, '' for none)")
     ap.add_argument("--other-steps", type=int, default=30)
@@ -399,7 +400,7 @@ def main():
             continue
         log("generating", W.CONFIG_NAMES[idx])
         wo = W.make_config(idx)
-        r = time_workload(R, torch, wo, args.other_steps, min(args.warmup, 5), use_graph=not args.no_graph,
+        r = time_workload(R, torch, wo, args.other_steps, min(args.warmup, 50), use_graph=not args.no_graph,
                           fused=not args.separate_calls)
         others[wo.name] = {"tree_tokens_per_s": r["tree_tokens_per_s"], "ms_per_step": r["ms_per_step"],
                            "launch_mode": r["launch_mode"], "steps": args.other_steps,
