@@ -1132,27 +1132,40 @@ __device__ inline void merge_body(const AttnParams &p, int pair, int block_y) {
     float acc[8];
 #pragma unroll
     for (int d = 0; d < 8; ++d) acc[d] = 0.f;
-#pragma unroll 2
-    for (int w = w_first; w <= w_last; ++w) {
-        // a range that holds no tile (more workgroups than tiles) wrote no record
-        if (p.range_tiles[w] == 0) continue;
-        const size_t slot = ((size_t)(2 * w + (w == w_first ? 1 : 0)) * p.n_row_chunks + row_chunk);
-        const float *rec = p.workspace + slot * rec_floats;
-        const float mw = rec[rows * (D / 2) + row_local];
-        const float lw = rec[rows * (D / 2 + 1) + row_local];
-        const uint4 v = reinterpret_cast<const uint4 *>(rec)[(size_t)c * rows + row_local];
-        if (mw == -INFINITY) continue;   // this row saw no key of that part
-        const float m_new = fmaxf(m_all, mw);
-        const float fa = __builtin_amdgcn_exp2f(m_all - m_new);      // 0 for the first part
-        const float fb = __builtin_amdgcn_exp2f(mw - m_new) * lw;
-        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+    // Records are fetched eight at a time (all their loads in flight together: a pair of a single
+    // long sequence is cut into dozens of parts) and folded in in range order.
+    constexpr int kBatch = 8;
+    for (int w0 = w_first; w0 <= w_last; w0 += kBatch) {
+        float mw[kBatch], lw[kBatch];
+        uint4 v[kBatch];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            acc[2 * e] = acc[2 * e] * fa + fb * __uint_as_float(u[e] << 16);
-            acc[2 * e + 1] = acc[2 * e + 1] * fa + fb * __uint_as_float(u[e] & 0xffff0000u);
+        for (int j = 0; j < kBatch; ++j) {
+            const int w = w0 + j;
+            mw[j] = -INFINITY;
+            // a range that holds no tile (more workgroups than tiles) wrote no record
+            if (w <= w_last && p.range_tiles[w] != 0) {
+                const size_t slot = ((size_t)(2 * w + (w == w_first ? 1 : 0)) * p.n_row_chunks + row_chunk);
+                const float *rec = p.workspace + slot * rec_floats;
+                mw[j] = rec[rows * (D / 2) + row_local];
+                lw[j] = rec[rows * (D / 2 + 1) + row_local];
+                v[j] = reinterpret_cast<const uint4 *>(rec)[(size_t)c * rows + row_local];
+            }
         }
-        l_all = l_all * fa + fb;
-        m_all = m_new;
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            if (mw[j] == -INFINITY) continue;   // no record, or this row saw no key of that part
+            const float m_new = fmaxf(m_all, mw[j]);
+            const float fa = __builtin_amdgcn_exp2f(m_all - m_new);      // 0 for the first part
+            const float fb = __builtin_amdgcn_exp2f(mw[j] - m_new) * lw[j];
+            const uint32_t u[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[2 * e] = acc[2 * e] * fa + fb * __uint_as_float(u[e] << 16);
+                acc[2 * e + 1] = acc[2 * e + 1] * fa + fb * __uint_as_float(u[e] & 0xffff0000u);
+            }
+            l_all = l_all * fa + fb;
+            m_all = m_new;
+        }
     }
     // l_all > 0: every query row sees at least its own tree node
     const float inv = 1.f / l_all;
