@@ -147,10 +147,13 @@ def draw_targets(rng: np.random.Generator, parents: np.ndarray, draft: np.ndarra
             target[i] = draft[kids[i][int(rng.integers(0, len(kids[i])))]]
         else:
             taken = {int(draft[c]) for c in kids[i]}
-            while True:
-                t = int(rng.integers(0, vocab))
-                if t not in taken:
-                    break
+            if len(taken) >= vocab:
+                t = vocab          # the children use up the vocabulary: a token none of them drafted
+            else:
+                while True:
+                    t = int(rng.integers(0, vocab))
+                    if t not in taken:
+                        break
             target[i] = t
     return target
 

@@ -115,6 +115,31 @@ def test_attn_ranges_cut_with_64_bit_arithmetic(R, oracle_mod, T, Hq, monkeypatc
     check_attn(R, oracle_mod, w)
 
 
+@pytest.mark.parametrize("case", range(16))
+def test_attn_seeded_random_shapes(R, oracle_mod, case):
+    # a seeded sweep over batch, tree size, head layout and length mix (empty sequences included), both
+    # kernel flavours (up to 128 query rows per kv head, and more)
+    rng = np.random.Generator(np.random.PCG64(9000 + case))
+    D = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    T = int(rng.choice([1, 3, 16, 33, 64, 100, 128]))
+    B = int(rng.integers(1, 10))
+    kind = case % 4
+    if kind == 0:
+        L = rng.integers(0, 40, size=B)                    # very short, some empty
+    elif kind == 1:
+        L = rng.integers(0, 700, size=B)
+    elif kind == 2:
+        L = np.where(rng.random(B) < 0.3, 0, rng.integers(60, 70, size=B))   # around one tile, or nothing
+    else:
+        L = rng.integers(900, 1400, size=B) if B <= 3 else rng.integers(100, 300, size=B)
+    w = W.make_custom("rand%d" % case, B=B, Hq=Hkv * G, Hkv=Hkv, D=D, T=T, seq_lens=[int(x) for x in L],
+                      tree=str(rng.choice(["trie", "uniform", "chain", "star"])), depth=int(rng.integers(2, 12)),
+                      branch=int(rng.integers(1, 6)), seed=9100 + case)
+    check_attn(R, oracle_mod, w, variants=(0,))
+
+
 def test_attn_custom_scale_and_peaked_scores(R, oracle_mod):
     w = W.make_custom("peaked", B=1, Hq=8, Hkv=2, D=128, T=16, seq_lens=[700], tree="trie", depth=5,
                       k_outlier_frac=0.05, seed=402)
@@ -305,10 +330,23 @@ def test_whole_step_then_next_step_attention(R, oracle_mod, index, scale):
 
 # ---------------------------------------------------------------- fused step (two launches)
 
-@pytest.mark.parametrize("index,scale", [(0, 1.0), (1, 0.1), (2, 0.1), (2, 1.0), (3, 0.02), (4, 0.05)])
+def random_step_workload(case):
+    rng = np.random.Generator(np.random.PCG64(9500 + case))
+    Hkv, G = int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 4, 8]))
+    B, T = int(rng.integers(1, 8)), int(rng.choice([1, 5, 16, 40, 64, 128]))
+    L = [int(x) for x in rng.integers(0, 400, size=B)]
+    return W.make_custom("randstep%d" % case, B=B, Hq=Hkv * G, Hkv=Hkv, D=int(rng.choice([64, 128])), T=T, seq_lens=L,
+                         tree=str(rng.choice(["trie", "uniform", "chain"])), depth=int(rng.integers(2, 14)),
+                         branch=int(rng.integers(1, 5)), vocab=int(rng.choice([3, 50])), p_match=float(rng.uniform(0.3, 0.95)),
+                         seed=9600 + case)
+
+
+@pytest.mark.parametrize("index,scale", [(0, 1.0), (1, 0.1), (2, 0.1), (2, 1.0), (3, 0.02), (4, 0.05)] +
+                         [(-1 - c, 1.0) for c in range(10)])
 def test_verify_step_equals_the_three_calls_and_the_oracle(R, oracle_mod, index, scale):
     import torch
-    w = W.make_config(index, length_scale=scale)
+    # the presets, and a seeded sweep of random shapes (negative index)
+    w = W.make_config(index, length_scale=scale) if index >= 0 else random_step_workload(-1 - index)
     # the three entry points, one after the other
     dw3 = run_step(R, w)
     # the fused entry point on a fresh upload of the same workload
