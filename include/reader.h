@@ -7,11 +7,17 @@
  * (Section 3.2) and, once per step, a greedy acceptance of the longest draft path
  * that agrees with the base model (Algorithm 5, Appendix C) followed by the
  * append of that path's K/V rows to each sample's cache so that it stays tight
- * (Section 4.3, Algorithm 4).  This library is those three operations.
+ * (Section 4.3, Algorithm 4).  This library is those three operations, the steps
+ * right next to them (the base model's tokens from its logits, greedy or sampled
+ * with coupled uniforms; the paper's periodic rearrangement of a padded cache;
+ * compaction when the tree rows already sit in every layer's cache), and the
+ * host-side retrieval drafter that makes draft trees from the short-term context.
  *
  * Conventions
- *  - Every pointer is a DEVICE pointer unless its name ends in `_host`.  All
- *    buffers are borrowed: the caller allocates, owns and frees them.  The library
+ *  - Every pointer is a DEVICE pointer unless its name ends in `_host` or the
+ *    comment of the entry point says otherwise (the drafter works on host memory).  All
+ *    device buffers are borrowed: the caller allocates, owns and frees them.  On the
+ *    device side the library
  *    allocates nothing, frees nothing and never synchronises; each call enqueues
  *    its kernels on `stream` (a hipStream_t passed as void*, NULL = default
  *    stream) and returns.  Results are valid once the stream reaches that point.

@@ -1,7 +1,9 @@
 """CPU oracle for READER's draft-tree verification step -- TEST INFRASTRUCTURE ONLY.
 
 Thin ctypes loader around ``reader_oracle.c`` (plain C, IEEE double arithmetic, no
-tiling, explicit masks).  Only the tests, ``__graft_entry__.smoke()`` and the
+tiling, explicit masks), plus the functions written directly in numpy at the end of this
+file (``target_sample``, ``kv_compact_layers``) and the brute-force drafter oracle in
+``oracle/drafter.py``.  Only the tests, ``__graft_entry__.smoke()`` and the
 ``cpu_baseline`` leg of ``bench.py`` may import this package; the product package
 never does, and this package never imports the product package.
 
