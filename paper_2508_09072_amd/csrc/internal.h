@@ -23,7 +23,8 @@ constexpr int kMaxBatchScan = 4096;  // sequences the in-kernel prefix scan is s
 
 // Query rows (tree node, grouped head) one attention workgroup carries: 4 row blocks of 32
 // with the tile's keys split between two wave groups, or 8 row blocks when T*G > 128.
-__host__ __device__ inline int attn_rows_per_wg(int M) { return M <= 128 ? 128 : 256; }
+
+int attn_rows_per_wg(const reader_dims &d, int32_t max_seq_len);   // host: 128 or 256 query rows per workgroup (reader_api.hip)
 
 // Everything the attention kernels need, passed by value as the kernel argument.
 struct AttnParams {
@@ -40,7 +41,7 @@ struct AttnParams {
     int32_t B, T, Hq, Hkv, D, G, M;       // G = Hq/Hkv, M = T*G query rows per (sequence, kv head)
     int32_t max_pages, max_seq_len;
     int32_t n_tree_tiles;                  // ceil(T / kTile)
-    int32_t rows_per_wg;                   // attn_rows_per_wg(M)
+    int32_t rows_per_wg;                   // attn_rows_per_wg(dims, max_seq_len)
     int32_t n_row_chunks;                  // ceil(M / rows_per_wg)
     int32_t n_ranges;                      // workgroups along the flattened (pair, tile) axis
     int64_t num_pages;

@@ -33,6 +33,23 @@ static bool dims_ok(const reader_dims *d, int *err) {
     return true;
 }
 
+// Query rows a workgroup carries: 128 (four computing wavefronts, four that move data) or 256
+// (all eight compute and copy).  Up to 128 rows per (sequence, kv head) there is nothing to
+// choose.  Beyond that 256-row workgroups do more matrix work per byte they fetch and win as
+// soon as a workgroup has a few tiles to stream; a small problem (a single prompt of a few
+// thousand tokens) is over sooner when it is cut into more, lighter workgroups (measured
+// crossover: about 1100 workgroup-tiles).  READER_ATTN_ROWS (experiments) forces one of them.
+int attn_rows_per_wg(const reader_dims &d, int32_t max_seq_len) {
+    const char *env = getenv("READER_ATTN_ROWS");
+    const int forced = env ? atoi(env) : 0;
+    if (forced == 128 || forced == 256) return forced;
+    const int M = d.T * (d.Hq / d.Hkv);
+    if (M <= 128) return 128;
+    const long long tiles_per_pair = (max_seq_len + kTile - 1) / kTile + (d.T + kTile - 1) / kTile;
+    const long long units = (long long)d.B * d.Hkv * tiles_per_pair;
+    return units * ((M + 127) / 128) <= 1100 ? 128 : 256;
+}
+
 int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len) {
     // One range workgroup streams a contiguous run of 64-key tiles of the flattened
     // (sequence, kv head, tile) axis.  One workgroup (8 waves, ~100 KB of LDS) occupies a
@@ -75,9 +92,9 @@ static bool profile_next(hipEvent_t *a, hipEvent_t *b) {
     return true;
 }
 
-static int row_chunks(const reader_dims &d) {
+static int row_chunks(const reader_dims &d, int32_t max_seq_len) {
     int M = d.T * (d.Hq / d.Hkv);
-    int rows = attn_rows_per_wg(M);
+    int rows = attn_rows_per_wg(d, max_seq_len);
     return (M + rows - 1) / rows;
 }
 
@@ -115,8 +132,8 @@ extern "C" size_t reader_workspace_bytes(const reader_dims *dims, int32_t max_se
     int err = 0;
     if (!dims_ok(dims, &err) || max_seq_len < 0) return 0;
     if (dims->B == 0) return 256;
-    size_t slots = 2 * (size_t)attn_plan_ranges(*dims, max_seq_len) * (size_t)row_chunks(*dims);
-    size_t bytes = slots * attn_slot_floats(dims->D, attn_rows_per_wg(dims->T * (dims->Hq / dims->Hkv))) * sizeof(float);
+    size_t slots = 2 * (size_t)attn_plan_ranges(*dims, max_seq_len) * (size_t)row_chunks(*dims, max_seq_len);
+    size_t bytes = slots * attn_slot_floats(dims->D, attn_rows_per_wg(*dims, max_seq_len)) * sizeof(float);
     return attn_header_bytes(dims->B, dims->Hkv) + ((bytes + 255) & ~(size_t)255);
 }
 
@@ -149,8 +166,8 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     p.G = dims->Hq / dims->Hkv; p.M = p.T * p.G;
     p.max_pages = dims->max_pages_per_seq; p.max_seq_len = max_seq_len;
     p.n_tree_tiles = (dims->T + kTile - 1) / kTile;
-    p.rows_per_wg = attn_rows_per_wg(p.M);
-    p.n_row_chunks = row_chunks(*dims);
+    p.rows_per_wg = attn_rows_per_wg(*dims, max_seq_len);
+    p.n_row_chunks = row_chunks(*dims, max_seq_len);
     p.n_ranges = attn_plan_ranges(*dims, max_seq_len);
     {
         // A pair that starts inside a range costs its workgroup extra (query rows to fetch, a

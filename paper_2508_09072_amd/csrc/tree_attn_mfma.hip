@@ -636,8 +636,9 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         for (int i = 0; i < kCopiesPerTile; ++i) {
             const int r = (cw * kCopiesPerTile + i) * G::kRowsPerCopy + lane / G::kChunks;
             const int c = (lane % G::kChunks) ^ swizzle_k<D>(r);
-            const int nd = r / p.G, gr = r - nd * p.G;
-            const char *src = r < p.M ? qbase + ((size_t)nd * p.Hq + gr) * (D * 2) + c * 16 : zeros;
+            const int m = chunk_base + r;                  // query row inside the pair
+            const int nd = m / p.G, gr = m - nd * p.G;
+            const char *src = m < p.M ? qbase + ((size_t)nd * p.Hq + gr) * (D * 2) + c * 16 : zeros;
             copy16_lane(src, stage_lds + (cw * kCopiesPerTile + i) * 1024);
         }
     };

@@ -140,6 +140,17 @@ def test_attn_seeded_random_shapes(R, oracle_mod, case):
     check_attn(R, oracle_mod, w, variants=(0,))
 
 
+@pytest.mark.parametrize("rows", ["128", "256"])
+@pytest.mark.parametrize("T,Hq", [(64, 16), (128, 16), (100, 32)])
+def test_attn_more_than_128_query_rows_both_decompositions(R, oracle_mod, rows, T, Hq, monkeypatch):
+    # more than 128 query rows per kv head: workgroups of 128 rows (several row chunks per key range) and of
+    # 256 rows must agree with the oracle; the library picks between them by problem size
+    monkeypatch.setenv("READER_ATTN_ROWS", rows)
+    w = W.make_custom("rows%s_T%d" % (rows, T), B=3, Hq=Hq, Hkv=4, D=128, T=T, seq_lens=[700, 0, 131], tree="trie",
+                      depth=7, seed=407)
+    check_attn(R, oracle_mod, w, variants=(0,))
+
+
 def test_attn_custom_scale_and_peaked_scores(R, oracle_mod):
     w = W.make_custom("peaked", B=1, Hq=8, Hkv=2, D=128, T=16, seq_lens=[700], tree="trie", depth=5,
                       k_outlier_frac=0.05, seed=402)
