@@ -52,16 +52,23 @@ int attn_rows_per_wg(const reader_dims &d, int32_t max_seq_len) {
 
 int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len) {
     // One range workgroup streams a contiguous run of 64-key tiles of the flattened
-    // (sequence, kv head, tile) axis.  One workgroup (8 waves, ~100 KB of LDS) occupies a
+    // (sequence, kv head, tile) axis.  One workgroup (8 waves, ~150 KB of LDS) occupies a
     // compute unit, so at most 256 ranges; short problems get fewer so that a range holds
-    // a few tiles.
+    // at least two tiles (what a workgroup spends before its first tile arrives is worth
+    // several tiles, so tiny problems want many short ranges; measured), and when the rows
+    // are cut into 128-row chunks (small problems only) all workgroups fit the chip at once.
     // READER_ATTN_RANGES (tests, experiments): ask for this many ranges instead; read at every call
     const char *env = getenv("READER_ATTN_RANGES");
     const int forced = env ? atoi(env) : 0;
     long long tiles_per_pair = (max_seq_len + kTile - 1) / kTile + (d.T + kTile - 1) / kTile;
     long long units = (long long)d.B * d.Hkv * tiles_per_pair;
-    long long n = forced > 0 ? forced : units / 4;
+    long long n = forced > 0 ? forced : units / 2;
     if (n > kNumCU) n = kNumCU;
+    const int M = d.T * (d.Hq / d.Hkv);
+    if (forced <= 0 && M > 128 && attn_rows_per_wg(d, max_seq_len) == 128) {
+        const int chunks = (M + 127) / 128;
+        if (n > kNumCU / chunks) n = kNumCU / chunks;
+    }
     if (n > units) n = units;
     if (n < 1) n = 1;
     if (n >= kNumXCD) n -= n % kNumXCD;  // row chunks of one key range then share an XCD's L2
