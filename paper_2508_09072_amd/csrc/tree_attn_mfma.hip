@@ -1143,13 +1143,17 @@ __device__ inline void merge_body(const AttnParams &p, int pair, int block_y) {
         for (int j = 0; j < kBatch; ++j) {
             const int w = w0 + j;
             mw[j] = -INFINITY;
-            // a range that holds no tile (more workgroups than tiles) wrote no record
-            if (w <= w_last && p.range_tiles[w] != 0) {
+            if (w <= w_last) {
+                // A range that holds no tile (more workgroups than tiles) wrote no record: its slot
+                // holds stale bytes.  The slot is read all the same, next to the range's tile count and
+                // not behind it (one round trip less), and dropped afterwards.
+                const int n_here = p.range_tiles[w];
                 const size_t slot = ((size_t)(2 * w + (w == w_first ? 1 : 0)) * p.n_row_chunks + row_chunk);
                 const float *rec = p.workspace + slot * rec_floats;
-                mw[j] = rec[rows * (D / 2) + row_local];
+                const float m_rec = rec[rows * (D / 2) + row_local];
                 lw[j] = rec[rows * (D / 2 + 1) + row_local];
                 v[j] = reinterpret_cast<const uint4 *>(rec)[(size_t)c * rows + row_local];
+                mw[j] = n_here != 0 ? m_rec : -INFINITY;
             }
         }
 #pragma unroll
