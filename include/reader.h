@@ -288,20 +288,24 @@ int reader_target_argmax(int32_t rows, int32_t V, const void *logits, int32_t *t
  * policy's own draw at the first position the draft does not cover.  Top-k / top-p filtering
  * is not applied.
  *
- *   logits         bf16 [B, T, V]  in    a NaN carries no probability; +inf is not allowed
+ *   logits         bf16 [B, T, V]  in    a NaN carries no probability; a +inf logit takes all of
+ *                                        it (shared equally among the +inf tokens of the row)
  *   parents        i32  [B, T]     in    as for reader_tree_attn; a pointer that does not lead
  *                                        towards the root ends the depth walk there
  *   uniforms       f32  [B, T]     in    values in [0, 1); entry d serves depth d
- *   temperature    > 0, finite
+ *   temperature    in [READER_MIN_TEMPERATURE, READER_MAX_TEMPERATURE] (below the lower end the
+ *                  policy is the arg max in all but name: use reader_target_argmax)
  *   target_tokens  i32  [B, T]     out   a token of zero weight is never returned; a row
  *                                        without any weight gives 0
  * Sums are formed in fp32 (blocks of 512 tokens, then over the blocks): where u * total lies
  * within rounding (about 1e-5 of the total) of a boundary between two tokens' cumulative
  * weights, either of them may be returned.
  * Returns READER_OK or READER_EINVAL (B < 0, T outside 1..READER_MAX_T, V outside
- * 1..READER_MAX_SAMPLE_V, temperature not positive and finite, null pointer).
+ * 1..READER_MAX_SAMPLE_V, temperature outside its range or not a number, null pointer).
  */
 #define READER_MAX_SAMPLE_V 4194304
+#define READER_MIN_TEMPERATURE 1e-6f
+#define READER_MAX_TEMPERATURE 1e6f
 int reader_target_sample(int32_t B, int32_t T, int32_t V, const void *logits, const int32_t *parents,
                          const float *uniforms, float temperature, int32_t *target_tokens, void *stream);
 

@@ -185,6 +185,17 @@ def _bf16_bits_to_f64(bits):
     return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
+def _softmax_weights(x, temperature):
+    """exp((x - max) / temperature) for a row without NaNs.  A row of nothing but -inf has no
+    weight anywhere; +inf logits take all the weight, one unit each (the limit of the softmax)."""
+    m = x.max()
+    if m == np.inf:
+        return (x == np.inf).astype(np.float64)
+    if m == -np.inf:
+        return np.zeros(x.shape[0])
+    return np.exp((x - m) / temperature)
+
+
 def target_sample(logits, parents, uniforms, temperature=1.0, with_cdf=False):
     """The base model's tokens under a sampling policy (Appendix C, randomized decoding):
     the policy is a map F(distribution, u) with one uniform u per decoding position, and the
@@ -208,8 +219,7 @@ def target_sample(logits, parents, uniforms, temperature=1.0, with_cdf=False):
         for n in range(T):
             x = _bf16_bits_to_f64(logits[b, n])
             x = np.where(np.isnan(x), -np.inf, x)
-            m = x.max()
-            w = np.exp((x - m) / temperature) if np.isfinite(m) else np.zeros(V)
+            w = _softmax_weights(x, temperature)
             cdf = np.cumsum(w)
             t = float(uniforms[b, depth[n]]) * cdf[-1]
             k = int(np.searchsorted(cdf, t, side="right"))      # first index with cdf > t
@@ -223,9 +233,7 @@ def target_sample_weights(logits_row, temperature=1.0):
     """Cumulative weights of one row as target_sample forms them (double precision)."""
     x = _bf16_bits_to_f64(logits_row)
     x = np.where(np.isnan(x), -np.inf, x)
-    m = x.max()
-    w = np.exp((x - m) / temperature) if np.isfinite(m) else np.zeros(x.shape[0])
-    return np.cumsum(w)
+    return np.cumsum(_softmax_weights(x, temperature))
 
 
 def kv_compact_layers(k_cache, v_cache, path, accept_len, page_table, seq_lens):

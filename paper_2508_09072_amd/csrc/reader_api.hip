@@ -369,7 +369,7 @@ extern "C" int reader_target_argmax(int32_t rows, int32_t V, const void *logits,
 extern "C" int reader_target_sample(int32_t B, int32_t T, int32_t V, const void *logits, const int32_t *parents,
                                     const float *uniforms, float temperature, int32_t *target_tokens, void *stream) {
     if (B < 0 || T < 1 || T > READER_MAX_T || V < 1 || V > READER_MAX_SAMPLE_V) return READER_EINVAL;
-    if (!(temperature > 0.f) || !(temperature < INFINITY)) return READER_EINVAL;
+    if (!(temperature >= READER_MIN_TEMPERATURE) || !(temperature <= READER_MAX_TEMPERATURE)) return READER_EINVAL;
     if ((long long)B * T > 0x7fffffffLL) return READER_EINVAL;
     if (B == 0) return READER_OK;
     if (!logits || !parents || !uniforms || !target_tokens) return READER_EINVAL;

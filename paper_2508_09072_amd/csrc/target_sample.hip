@@ -47,10 +47,13 @@ __device__ inline float wave_sum(float v) {
     v += dpp_from<0x143, 0xc>(0.f, v);
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
+// Scaled logits never exceed this: a +inf logit (or a product that overflows) sits exactly
+// there, so that it takes all the probability, shared among equals, instead of producing NaNs.
+constexpr float kCeil = 0x1p127f;
 // bf16 bits -> logit * c as fp32; a NaN carries no probability
 __device__ inline float scaled(uint32_t bits16_hi, float c) {
     const float x = __uint_as_float(bits16_hi);
-    return x != x ? -INFINITY : x * c;
+    return x != x ? -INFINITY : fminf(x * c, kCeil);
 }
 __device__ inline void unpack8(const uint4 &w, float c, float y[8]) {
     const uint32_t u[4] = {w.x, w.y, w.z, w.w};
@@ -105,12 +108,23 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
         }
         float m = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
         m = wave_max(m);
-        const float mc = fmaxf(m, -0x1p126f) * c;     // a block of nothing but -inf: every weight becomes exp2(-inf) = 0
-        float s = 0.f;
+        float s = 0.f, m_store;
+        if (m * c < kCeil) {                              // (wavefront-uniform)
+            const float mc = fmaxf(m, -0x1p126f) * c;     // a block of nothing but -inf: every weight becomes exp2(-inf) = 0
 #pragma unroll
-        for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -mc));
+            for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -mc));
+            m_store = m * c;
+        } else {
+            // a +inf logit, or one so large that scaling overflows: go through the clamped values
+            float y[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = fminf(x[e] * c, kCeil);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(y[e] - kCeil);
+            m_store = kCeil;                              // some token of the block sits at the ceiling
+        }
         s = wave_sum(s);
-        if (lane == 0) s_stat[1 + blk] = make_float2(m * c, s);
+        if (lane == 0) s_stat[1 + blk] = make_float2(m_store, s);
     };
     const uint4 nothing = make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);
     for (int blk0 = wave * 4; blk0 < n_blocks; blk0 += kSampleWaves * 4) {
@@ -203,6 +217,10 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
     }
     __syncthreads();
     const int slot = s_pick[0] != 0x7fffffff ? s_pick[0] : s_pick[1];   // >= 0: the first slot with weight starts at 0
+    if (slot < 0 || slot >= n_slots) {   // only if the weights were not numbers at all: never index with it
+        if (tid == 0) out[row] = 0;
+        return;
+    }
     {
         float cum = before;
         for (int i = tid * per; i < min(n_slots, (tid + 1) * per); ++i) {

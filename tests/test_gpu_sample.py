@@ -108,6 +108,24 @@ def test_specials_edges_of_u_and_rows_without_weight(R, oracle_mod):
     assert got[0, 3] == 0 and got[0, 4] == 0 and got[0, 5] == V - 1 and got[0, 6] == 0
 
 
+def test_infinite_and_huge_logits(R, oracle_mod):
+    rng = np.random.Generator(np.random.PCG64(82))
+    B, T, V = 1, 8, 2000
+    bits = W.make_logits(B, T, V, rng, peaked=True)
+    bits[0, 0, [3, 700, 1999]] = 0x7F80          # +inf in the head block, a middle block, the last block
+    bits[0, 1, 1500] = 0x7F80                    # a single +inf
+    bits[0, 2, 100:110] = 0x7F7F                 # the largest finite bf16 (3.4e38): scaling overflows
+    bits[0, 3, :] = 0x7F80                       # everything +inf: uniform over the vocabulary
+    parents = np.arange(-1, T - 1, dtype=np.int32)[None]
+    u = W.make_uniforms(B, T, rng)
+    got = check(R, oracle_mod, bits, parents, u, 1.0)
+    assert got[0, 0] in (3, 700, 1999) and got[0, 1] == 1500 and 100 <= got[0, 2] < 110
+    # the lowest temperature the entry point takes: the greedy token
+    small = W.make_logits(1, 4, 1000, rng, peaked=True)
+    got = check(R, oracle_mod, small, parents[:, :4], u[:, :4] * np.float32(0.99), 1e-6, min_exact=1.0)
+    assert np.array_equal(got, oracle_mod.target_argmax(small))
+
+
 def test_nodes_of_one_depth_draw_the_same_token(R, oracle_mod):
     rng = np.random.Generator(np.random.PCG64(80))
     parents = np.array([[-1, 0, 0, 1, 1, 2, 3, 5, 0]], dtype=np.int32)

@@ -140,7 +140,7 @@ def test_target_token_arguments_are_checked_on_the_host(R):
     assert s(2, 129, 10, one, one, one, 1.0, one, None) == R.READER_EINVAL          # more nodes than a tree may have
     assert s(2, 4, 0, one, one, one, 1.0, one, None) == R.READER_EINVAL
     assert s(2, 4, (1 << 22) + 1, one, one, one, 1.0, one, None) == R.READER_EINVAL  # vocabulary beyond the limit
-    for bad in (0.0, -1.0, float("inf"), float("nan")):
+    for bad in (0.0, -1.0, 1e-9, 1e9, float("inf"), float("nan")):
         assert s(2, 4, 10, one, one, one, bad, one, None) == R.READER_EINVAL
     assert s(2, 4, 10, None, one, one, 1.0, one, None) == R.READER_EINVAL
     assert s(2, 4, 10, one, one, None, 1.0, one, None) == R.READER_EINVAL

@@ -59,6 +59,17 @@ def test_token_is_monotone_in_u_and_zero_weight_tokens_never_come_out(oracle_mod
     assert last[0, 0] == 62                        # u next to 1: the last token that has weight
 
 
+def test_infinite_logits_take_everything_and_share_it(oracle_mod):
+    # the limit of the softmax when some logits go to +inf: those tokens, equally
+    V, T = 12, 6
+    row = np.linspace(-1.0, 1.0, V).astype(np.float32)
+    row[[2, 5, 9]] = np.inf
+    bits = W.to_bf16_bits(np.tile(row, (1, T, 1)))
+    u = np.array([[0.0, 0.3, 0.34, 0.6, 0.67, 0.99]])
+    got = oracle_mod.target_sample(bits, chain(T)[None], u)[0]
+    assert got.tolist() == [2, 2, 5, 5, 9, 9]
+
+
 def test_frequencies_follow_the_softmax(oracle_mod):
     rng = np.random.Generator(np.random.PCG64(13))
     V, n, tau = 12, 40000, 1.3
