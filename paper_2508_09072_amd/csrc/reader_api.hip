@@ -178,10 +178,10 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     p.n_ranges = attn_plan_ranges(*dims, max_seq_len);
     {
         // A pair that starts inside a range costs its workgroup extra (query rows to fetch, a
-        // segment to finish): about three tiles' time when dedicated wavefronts copy, one otherwise.
+        // segment to finish): about four tiles' time when dedicated wavefronts copy, one otherwise.
         // READER_ATTN_PAIR_COST (experiments) overrides it.
         const char *env = getenv("READER_ATTN_PAIR_COST");
-        p.pair_cost = env ? atoi(env) : (p.rows_per_wg == 128 ? 3 : 1);
+        p.pair_cost = env ? atoi(env) : (p.rows_per_wg == 128 ? 4 : 1);
         if (p.pair_cost < 0 || p.pair_cost > 64) p.pair_cost = 0;
         // the kernel cuts the ranges with 32-bit arithmetic when nothing on the cost axis can overflow it
         const long long axis_max = (long long)p.Hkv * p.B * ((max_seq_len + kTile - 1) / kTile + p.n_tree_tiles + p.pair_cost);
