@@ -4,28 +4,30 @@
 //   A "pair" is (sequence b, kv head).  Its keys are cut into 64-key tiles: first the
 //   prefix tiles (paged cache, mask-free except for the ragged last one), then the
 //   tree tiles (the T tree rows, masked by ancestor-or-self bit masks held in LDS).
-//   All tiles of all pairs form one flat axis of U units.  The grid has n_ranges
-//   workgroups along x, one per compute unit; workgroup w streams the contiguous unit
-//   range [w*U/n_ranges, (w+1)*U/n_ranges), so every workgroup moves the same number of
-//   K/V bytes whatever the ragged sequence lengths are.  A range may cover several
+//   All tiles of all pairs form one flat axis.  The grid has n_ranges workgroups per
+//   chunk of query rows, one per compute unit; a workgroup streams a contiguous range of
+//   the axis, cut so that every range costs the same (a tile counts one, the start of a
+//   pair a few more), whatever the ragged sequence lengths are.  A range may cover several
 //   whole pairs and at most one pair at each end in part.  Whole pairs are finished
 //   in place; a pair cut between workgroups leaves one partial record (bf16 output
 //   normalised by its own sum, running max, running sum) per workgroup and a second
 //   kernel merges them.  When T*G exceeds what a workgroup carries, the query rows are cut
-//   into chunks, one workgroup per (range, chunk).
+//   into chunks, one workgroup per (range, chunk); the chunks of a range run at the same
+//   time on one XCD, so that only the first of them fetches the range's tiles from HBM.
 //   Each workgroup first writes the list of its items (page ids, row counts, segment
 //   flags) into LDS, from a copy of the page table it fetched while the sequence lengths
 //   were on their way, so the main loop does no bookkeeping.
 //
 // One workgroup = 8 wavefronts.  A query row is a (tree node, grouped query head) pair, so
 // one K/V tile serves all heads of the group and all tree nodes.
-//   T*G <= 128: wavefronts 0..3 compute one block of 32 query rows each, wavefronts 4..7
+//   128 rows per workgroup (T*G <= 128, or a small problem with more rows, cut into
+//               128-row chunks): wavefronts 0..3 compute one block of 32 query rows each, wavefronts 4..7
 //               only move data, always ahead of the computation: the tiles, the query
 //               rows of every segment (a list item of their own that travels through the
 //               ring like a tile), parent pointers and the ancestor masks made from them,
 //               the list itself.  A computing wavefront never issues a memory instruction
 //               inside the loop except to store finished rows.
-//   T*G  > 128: 8 row blocks of 32 rows, every wavefront computes and copies; the two
+//   256 rows per workgroup (T*G > 128): 8 row blocks of 32 rows, every wavefront computes and copies; the two
 //               wavefronts of a SIMD copy at opposite ends of the tile so that they run
 //               out of step.
 // Per tile a computing wavefront runs
@@ -37,12 +39,13 @@
 //   The S^T accumulator registers of a lane are, eight at a time, exactly the B
 //   operand of the second product, so the softmax weights never leave the registers.
 //   V^T fragments come out of the row-major V tile through the transposing LDS load
-//   (ds_read_b64_tr_b16), K fragments through plain 128-bit LDS loads.  (A wavefront's
-//   own vector instructions do not run under its own matrix instructions on this part,
-//   only another wavefront's do; the tile code is a plain sequence.)
+//   (ds_read_b64_tr_b16), K fragments through plain 128-bit LDS loads.  (Matrix and vector
+//   instructions overlap little on this part, within a wavefront or between the two
+//   wavefronts of a SIMD, whatever their order; the tile code is a plain sequence.)
 //
-// K/V tiles go HBM -> LDS directly (global_load_lds_dwordx4: each wavefront instruction
-// moves 1 KB, no staging registers) into a ring of four (three for T*G > 128) tile
+// K/V tiles go HBM -> LDS directly (global_load_lds_dwordx4 with the non-temporal hint: each
+// wavefront instruction moves 1 KB, no staging registers) into a ring of four (three with
+// 256-row workgroups) tile
 // buffers; one barrier per item.  16-byte chunks are XOR-swizzled inside a tile row
 // (applied on the global-address side of the copy) so that operand reads hit every LDS
 // bank once.
