@@ -2,7 +2,8 @@
 // drafted tokens"): target_tokens[r] = argmax_v logits[r][v] for the B*T rows of one
 // verification step.  The logits of a step are as large as its KV stream (vocabulary 128256:
 // 256 KB per row), so this is a plain streaming reduction: one workgroup per row, 128-bit
-// loads, a running (value, index) per thread, then a wavefront and a workgroup reduction.
+// loads (eight in flight per thread), a running (value, index) per thread, then a wavefront
+// and a workgroup reduction.
 // Ties go to the lowest index; a NaN is never larger than anything (a row of NaNs gives 0).
 #include "internal.h"
 
@@ -40,11 +41,13 @@ __global__ __launch_bounds__(256) void target_argmax_kernel(const uint16_t *__re
         }
     };
     int c = tid;
-    for (; c + 3 * 256 < n_vec; c += 4 * 256) {      // four loads in flight per thread
+    for (; c + 7 * 256 < n_vec; c += 8 * 256) {      // eight loads in flight per thread
         // read once: streamed past the caches (about a sixth more bandwidth out of HBM than plain loads)
-        const uint4 w0 = load_stream16(vec + c), w1 = load_stream16(vec + c + 256),
-                    w2 = load_stream16(vec + c + 512), w3 = load_stream16(vec + c + 768);
-        scan(w0, c); scan(w1, c + 256); scan(w2, c + 512); scan(w3, c + 768);
+        uint4 w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w[j] = load_stream16(vec + c + j * 256);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) scan(w[j], c + j * 256);
     }
     for (; c < n_vec; c += 256) scan(load_stream16(vec + c), c);
     for (int j = head + n_vec * 8 + tid; j < V; j += 256) take(best, __uint_as_float((uint32_t)src[j] << 16), j);
