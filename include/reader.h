@@ -116,7 +116,10 @@ size_t reader_workspace_bytes(const reader_dims *dims, int32_t max_seq_len);
  * and over the tree nodes that are i itself or an ancestor of i.
  *
  *   q            bf16 [B, T, Hq, D]                     in
- *   k_tree,v_tree bf16 [B, T, Hkv, D]                   in   K/V rows of the tree nodes
+ *   k_tree,v_tree bf16 [B, T, Hkv, D]                   in   K/V rows of the tree nodes; or both NULL:
+ *                the in-cache layout (Section 4.3), where the forward pass wrote the row of node n
+ *                of sequence b at cache position seq_lens[b] + n; page_table must then map pages
+ *                for [0, seq_lens[b] + T) and max_pages_per_seq * page_size >= max_seq_len + T
  *   k_cache,v_cache bf16 [num_pages, Hkv, page_size, D] in   paged prefix cache
  *   page_table   i32 [B, max_pages_per_seq]             in   must map pages for [0, seq_lens[b])
  *   seq_lens     i32 [B]                                in   prefix length L_b, tree rows excluded

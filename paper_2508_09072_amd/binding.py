@@ -172,7 +172,8 @@ def reader_tree_attn(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_
     import torch
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     code = load().reader_tree_attn(
-        ctypes.byref(dims), _dev(q, torch.bfloat16), _dev(k_tree, torch.bfloat16), _dev(v_tree, torch.bfloat16),
+        ctypes.byref(dims), _dev(q, torch.bfloat16), _dev(k_tree, torch.bfloat16, optional=True),
+        _dev(v_tree, torch.bfloat16, optional=True),
         _dev(k_cache, torch.bfloat16), _dev(v_cache, torch.bfloat16), _dev(page_table, torch.int32),
         _dev(seq_lens, torch.int32), _dev(parents, torch.int32), _dev(out, torch.bfloat16),
         _dev(lse, torch.float32, optional=True), int(max_seq_len), _dev(workspace, optional=True),

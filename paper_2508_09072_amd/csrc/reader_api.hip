@@ -156,10 +156,12 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     if (!dims_ok(dims, &err)) return err;
     if (max_seq_len < 0) return READER_EINVAL;
     if (dims->B == 0) { *empty = true; return READER_OK; }
-    if (!q || !k_tree || !v_tree || !k_cache || !v_cache || !page_table || !seq_lens || !parents || !out)
+    if (!q || !k_cache || !v_cache || !page_table || !seq_lens || !parents || !out) return READER_EINVAL;
+    if ((k_tree == nullptr) != (v_tree == nullptr)) return READER_EINVAL;
+    const bool tree_in_cache = k_tree == nullptr;     // the tree rows sit behind each sequence in the cache
+    if ((long long)dims->max_pages_per_seq * dims->page_size < (long long)max_seq_len + (tree_in_cache ? dims->T : 0))
         return READER_EINVAL;
-    if ((long long)dims->max_pages_per_seq * dims->page_size < max_seq_len) return READER_EINVAL;
-    if (max_seq_len > 0 && (dims->num_pages < 1 || dims->max_pages_per_seq < 1)) return READER_EINVAL;
+    if ((max_seq_len > 0 || tree_in_cache) && (dims->num_pages < 1 || dims->max_pages_per_seq < 1)) return READER_EINVAL;
     if (dims->variant != 0 && dims->variant != 1) return READER_EINVAL;
 
     p.q = (const uint16_t *)q; p.k_tree = (const uint16_t *)k_tree; p.v_tree = (const uint16_t *)v_tree;
@@ -189,6 +191,7 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
         if (getenv("READER_ATTN_AXIS64")) p.axis32 = 0;   // tests: force the 64-bit path
     }
     p.num_pages = dims->num_pages;
+    p.tree_in_cache = tree_in_cache ? 1 : 0;
     float scale = dims->sm_scale > 0.f ? dims->sm_scale : 1.0f / sqrtf((float)dims->D);
     p.scale_log2 = scale * 1.44269504088896340736f;
     return READER_OK;
@@ -248,6 +251,8 @@ extern "C" int reader_verify_step(const reader_dims *dims, const void *q, const 
     const int rc = attn_prepare(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, out, lse,
                                 max_seq_len, workspace, status, p, &empty);
     if (rc != READER_OK || empty) return rc;
+    // the fused step appends from the tree tensors: the in-cache layout is reader_tree_attn + reader_kv_compact_layers
+    if (!k_tree || !v_tree) return READER_EINVAL;
     if (!draft_tokens || !target_tokens || !accept_len || !path || !bonus_token) return READER_EINVAL;
     if (dims->variant != 0) return READER_EINVAL;   // the fused step exists for the matrix-core kernel only
     if (!workspace || ((uintptr_t)workspace & 255) != 0) return READER_EWORKSPACE;

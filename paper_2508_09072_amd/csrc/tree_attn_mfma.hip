@@ -256,7 +256,8 @@ __device__ inline void write_tile_desc(const AttnParams &p, const int32_t *table
         const int tt = idx - n_pre;
         n_valid = min(kTile, p.T - tt * kTile);
         flags = kDescTree | (tt << 8);
-        blk[0] = blk[1] = blk[2] = blk[3] = (b * p.T + tt * kTile) * p.Hkv + hkv;
+        // rows of the tree tensors from (b, first node) on; with the tree in the cache: the pair
+        blk[0] = blk[1] = blk[2] = blk[3] = p.tree_in_cache ? b * p.Hkv + hkv : (b * p.T + tt * kTile) * p.Hkv + hkv;
     }
     if (idx == 0) {
         flags |= kDescPairStart;
@@ -685,6 +686,32 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     // (the per-lane copy constants are made where they are used, so that they occupy registers
     // only in the wavefronts and loops that copy)
     auto issue_tile = [&](const CopyLane<D, CW> &cl, int blk, int nv, int fl, unsigned stage_lds) {
+        if (p.tree_in_cache && (fl & kDescTree)) {
+            // Tree rows that live in the cache: row r of tree tile tt is position L + 64 tt + r of
+            // the sequence.  The positions are not aligned to pages, so every lane looks up the
+            // page of its row (the table is small and sits in the caches) and gathers from there;
+            // rows past the last node and rows behind a bad page id come from the block of zeros.
+            const int sb = blk / p.Hkv, shkv = blk - sb * p.Hkv;
+            const int pos0 = (s_len ? s_len[sb] : clamp_len(p, seq_lens, sb)) + (fl >> 8) * kTile;
+            const char *zeros = reinterpret_cast<const char *>(kZeroRow) + (lane & 15) * 16;
+#pragma unroll
+            for (int i = 0; i < G::kCopies; ++i) {
+                const int row = cl.row[i], pos = pos0 + row;
+                bool ok = row < nv;
+                long long page = 0;
+                if (ok) {
+                    page = page_table[(size_t)sb * p.max_pages + (pos >> 4)];   // pos < 16 max_pages: checked on the host
+                    if (page < 0 || page >= p.num_pages) { bad |= READER_STATUS_BAD_PAGE; ok = false; }
+                }
+                const size_t row_off = ((size_t)(page * p.Hkv + shkv) * READER_PAGE_SIZE + (pos & 15)) * G::kRowBytes;
+                const unsigned in_row = (unsigned)(row & 15) * G::kRowBytes;      // the lane's offsets are relative to a 16-row block
+                const unsigned dst = stage_lds + cw * G::kRowsPerWave * G::kRowBytes + i * 1024;
+                copy16_lane(ok ? reinterpret_cast<const char *>(p.k_cache) + row_off + (cl.k_cache_off[i] - in_row) : zeros, dst);
+                copy16_lane(ok ? reinterpret_cast<const char *>(p.v_cache) + row_off + (cl.v_cache_off[i] - in_row) : zeros,
+                            dst + G::kTileBytes);
+            }
+            return;
+        }
         const CopyPlan cp = plan_copy<D, CW>(p, blk, nv, fl, cw);
 #pragma unroll
         for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D, CW>(cp, cl, stage_lds, cw, j);

@@ -67,9 +67,18 @@ __global__ __launch_bounds__(256) void tree_attn_scalar_kernel(AttnParams p) {
         } else {
             const int t = j - L;
             if (!((s_anc[t >> 5] >> (t & 31)) & 1u)) continue;
-            const size_t off = (((size_t)b * T + t) * p.Hkv + hkv) * (size_t)D;
-            krow = p.k_tree + off;
-            vrow = p.v_tree + off;
+            if (p.tree_in_cache) {
+                const int pos = L + t;      // below max_pages * 16: checked on the host
+                const long long page = p.page_table[(size_t)b * p.max_pages + (pos >> 4)];
+                if (page < 0 || page >= p.num_pages) { bad |= READER_STATUS_BAD_PAGE; continue; }
+                const size_t off = ((page * p.Hkv + hkv) * READER_PAGE_SIZE + (pos & 15)) * (size_t)D;
+                krow = p.k_cache + off;
+                vrow = p.v_cache + off;
+            } else {
+                const size_t off = (((size_t)b * T + t) * p.Hkv + hkv) * (size_t)D;
+                krow = p.k_tree + off;
+                vrow = p.v_tree + off;
+            }
         }
         float s = 0.f;
 #pragma unroll

@@ -500,3 +500,32 @@ def make_incache_step(name: str, B: int, T: int, Hkv: int, D: int, num_layers: i
         path[b, : len(chain)] = chain
         accept_len[b] = len(chain) - 1
     return InCacheStep(name, k_cache, v_cache, page_table, seq, parents, path, accept_len, T, max_path)
+
+
+def place_tree_in_cache(w: Workload, seed: int = 0):
+    """The same step in the in-cache layout: a fresh page pool whose pages cover
+    [0, seq_lens[b] + T) of every sequence, holding the prefix rows of `w` and, behind them,
+    the tree rows (node n at position seq_lens[b] + n).  Returns (k_cache, v_cache, page_table)
+    as numpy arrays (bf16 bits, int32); unused slots hold the canary."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    ps = w.page_size
+    n_pages_b = [(int(w.seq_lens[b]) + w.T + ps - 1) // ps for b in range(w.B)]
+    max_pages = max(n_pages_b) if w.B else 1
+    num_pages = int(sum(n_pages_b)) + 2
+    perm = rng.permutation(num_pages)
+    table = np.full((w.B, max_pages), -1, dtype=np.int32)
+    kc = np.full((num_pages, w.Hkv, ps, w.D), CANARY, dtype=np.uint16)
+    vc = np.full((num_pages, w.Hkv, ps, w.D), CANARY, dtype=np.uint16)
+    cursor = 0
+    for b in range(w.B):
+        pages = perm[cursor: cursor + n_pages_b[b]]
+        cursor += n_pages_b[b]
+        table[b, : n_pages_b[b]] = pages
+        L = int(w.seq_lens[b])
+        pos = np.arange(L)
+        old = w.page_table[b, pos // ps]
+        for src, tree, dst in ((w.k_cache, w.k_tree, kc), (w.v_cache, w.v_tree, vc)):
+            dst[pages[pos // ps], :, pos % ps, :] = src[old, :, pos % ps, :]
+            tpos = L + np.arange(w.T)
+            dst[pages[tpos // ps], :, tpos % ps, :] = tree[b]
+    return kc, vc, table

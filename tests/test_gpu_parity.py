@@ -151,6 +151,42 @@ def test_attn_more_than_128_query_rows_both_decompositions(R, oracle_mod, rows, 
     check_attn(R, oracle_mod, w, variants=(0,))
 
 
+@pytest.mark.parametrize("T,Hq,D,lens", [(16, 8, 128, [0, 1, 15, 16, 200]), (32, 32, 128, [333, 1024, 77]),
+                                         (64, 16, 128, [500, 31]), (128, 16, 128, [260]), (100, 32, 128, [64, 129]),
+                                         (16, 8, 64, [5, 700]), (1, 8, 128, [40, 0])])
+def test_attn_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens):
+    # the in-cache layout: no tree tensors, node n of sequence b sits at cache position L_b + n (any alignment
+    # to the 16-position pages); the result must be what the oracle gives for the separate-tensor layout
+    import torch
+    w = W.make_custom("incache_T%d" % T, B=len(lens), Hq=Hq, Hkv=4, D=D, T=T, seq_lens=lens, tree="trie", depth=6,
+                      seed=408 + T)
+    ref, ref_lse = oracle_mod.tree_attn(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table, w.seq_lens,
+                                        w.parents)
+    kc, vc, table = W.place_tree_in_cache(w, seed=5)
+    dw = R.to_device(w)
+    bf16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    dims = R.make_dims(w.B, w.T, w.Hq, w.Hkv, w.D, table.shape[1], w.max_path, kc.shape[0])
+    bound = int(max(lens))
+    ws = torch.empty(max(R.reader_workspace_bytes(dims, bound), 256), dtype=torch.uint8, device="cuda")
+    for variant in (0, 1):
+        dims.variant = variant
+        dw.out.fill_(float("nan"))
+        dw.status.zero_()
+        R.reader_tree_attn(dims, dw.q, None, None, bf16(kc), bf16(vc), torch.from_numpy(table).cuda(), dw.seq_lens,
+                           dw.parents, dw.out, dw.lse, bound, ws, dw.status)
+        torch.cuda.synchronize()
+        assert int(dw.status.item()) == 0
+        assert_close(bf16_to_np(dw.out), ref, what="in-cache variant %d" % variant)
+        assert_close(dw.lse.cpu().numpy().astype(np.float64), ref_lse, what="in-cache lse variant %d" % variant)
+    # one tree tensor without the other, or a page table too short for the tree rows, is refused
+    with pytest.raises(R.ReaderError):
+        R.reader_tree_attn(dims, dw.q, dw.k_tree, None, bf16(kc), bf16(vc), torch.from_numpy(table).cuda(), dw.seq_lens,
+                           dw.parents, dw.out, dw.lse, bound, ws, dw.status)
+    with pytest.raises(R.ReaderError):
+        R.reader_tree_attn(dims, dw.q, None, None, bf16(kc), bf16(vc), torch.from_numpy(table).cuda(), dw.seq_lens,
+                           dw.parents, dw.out, dw.lse, table.shape[1] * 16, ws, dw.status)
+
+
 def test_attn_custom_scale_and_peaked_scores(R, oracle_mod):
     w = W.make_custom("peaked", B=1, Hq=8, Hkv=2, D=128, T=16, seq_lens=[700], tree="trie", depth=5,
                       k_outlier_frac=0.05, seed=402)
