@@ -231,6 +231,12 @@ int reader_kv_compact_layers(const reader_dims *dims, int32_t num_layers,
  * this library), so the attention output is not consulted by the acceptance.
  * k_cache, v_cache and seq_lens are read by the attention and then updated by the
  * compaction.  dims->variant must be 0.  Errors as for the three calls.
+ *
+ * k_tree and v_tree both NULL: the in-cache layout of reader_tree_attn, one layer.  The step
+ * is then reader_tree_attn -> reader_accept_path -> reader_kv_compact_layers(num_layers = 1)
+ * on k_cache, v_cache [num_pages, Hkv, page_size, D]: the accepted rows move in place (two
+ * more small launches).  A model with several layers runs the attention of each layer, and
+ * after the last one reader_accept_path and one reader_kv_compact_layers over all of them.
  */
 int reader_verify_step(const reader_dims *dims,
                        const void *q, const void *k_tree, const void *v_tree,

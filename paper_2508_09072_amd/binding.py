@@ -205,7 +205,8 @@ def reader_verify_step(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, se
     import torch
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     code = load().reader_verify_step(
-        ctypes.byref(dims), _dev(q, torch.bfloat16), _dev(k_tree, torch.bfloat16), _dev(v_tree, torch.bfloat16),
+        ctypes.byref(dims), _dev(q, torch.bfloat16), _dev(k_tree, torch.bfloat16, optional=True),
+        _dev(v_tree, torch.bfloat16, optional=True),
         _dev(k_cache, torch.bfloat16), _dev(v_cache, torch.bfloat16), _dev(page_table, torch.int32),
         _dev(seq_lens, torch.int32), _dev(parents, torch.int32), _dev(draft_tokens, torch.int32),
         _dev(target_tokens, torch.int32), _dev(out, torch.bfloat16), _dev(lse, torch.float32, optional=True),

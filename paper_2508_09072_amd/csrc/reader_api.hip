@@ -216,6 +216,17 @@ static void compact_fill(const reader_dims *dims, const void *k_tree, const void
     p.max_pages = dims->max_pages_per_seq; p.max_path = dims->max_path; p.num_pages = dims->num_pages;
 }
 
+static void compact_layers_fill(const reader_dims *dims, int32_t num_layers, const int32_t *path,
+                                const int32_t *accept_len, void *k_cache, void *v_cache, const int32_t *page_table,
+                                int32_t *seq_lens, int32_t *status, CompactLayersParams &p) {
+    p.k_cache = (uint16_t *)k_cache; p.v_cache = (uint16_t *)v_cache;
+    p.path = path; p.accept_len = accept_len; p.page_table = page_table;
+    p.seq_lens = seq_lens; p.status = status;
+    p.B = dims->B; p.T = dims->T; p.Hkv = dims->Hkv; p.D = dims->D;
+    p.max_pages = dims->max_pages_per_seq; p.max_path = dims->max_path; p.NL = num_layers;
+    p.num_pages = dims->num_pages;
+}
+
 extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const void *k_tree,
                                 const void *v_tree, const void *k_cache, const void *v_cache,
                                 const int32_t *page_table, const int32_t *seq_lens,
@@ -251,8 +262,6 @@ extern "C" int reader_verify_step(const reader_dims *dims, const void *q, const 
     const int rc = attn_prepare(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, out, lse,
                                 max_seq_len, workspace, status, p, &empty);
     if (rc != READER_OK || empty) return rc;
-    // the fused step appends from the tree tensors: the in-cache layout is reader_tree_attn + reader_kv_compact_layers
-    if (!k_tree || !v_tree) return READER_EINVAL;
     if (!draft_tokens || !target_tokens || !accept_len || !path || !bonus_token) return READER_EINVAL;
     if (dims->variant != 0) return READER_EINVAL;   // the fused step exists for the matrix-core kernel only
     if (!workspace || ((uintptr_t)workspace & 255) != 0) return READER_EWORKSPACE;
@@ -263,7 +272,14 @@ extern "C" int reader_verify_step(const reader_dims *dims, const void *q, const 
     compact_fill(dims, k_tree, v_tree, path, accept_len, k_cache, v_cache, page_table, seq_lens, status, cp);
     hipEvent_t ev_a, ev_b;
     profile_next(&ev_a, &ev_b);
-    return launch_tree_attn_mfma(p, (hipStream_t)stream, ev_a, ev_b, &ap, &cp) == hipSuccess ? READER_OK : READER_EHIP;
+    if (launch_tree_attn_mfma(p, (hipStream_t)stream, ev_a, ev_b, &ap, &cp) != hipSuccess) return READER_EHIP;
+    if (p.tree_in_cache) {
+        // the tree rows are in the cache already: the accepted ones move in place (this layer's cache)
+        CompactLayersParams lp;
+        compact_layers_fill(dims, 1, path, accept_len, k_cache, v_cache, page_table, seq_lens, status, lp);
+        if (launch_kv_compact_layers(lp, (hipStream_t)stream) != hipSuccess) return READER_EHIP;
+    }
+    return READER_OK;
 }
 
 extern "C" int reader_profile_enable(int32_t on) {
@@ -331,12 +347,7 @@ extern "C" int reader_kv_compact_layers(const reader_dims *dims, int32_t num_lay
     if (!path || !accept_len || !page_table || !seq_lens || (num_layers > 0 && (!k_cache || !v_cache)))
         return READER_EINVAL;
     CompactLayersParams p;
-    p.k_cache = (uint16_t *)k_cache; p.v_cache = (uint16_t *)v_cache;
-    p.path = path; p.accept_len = accept_len; p.page_table = page_table;
-    p.seq_lens = seq_lens; p.status = status;
-    p.B = dims->B; p.T = dims->T; p.Hkv = dims->Hkv; p.D = dims->D;
-    p.max_pages = dims->max_pages_per_seq; p.max_path = dims->max_path; p.NL = num_layers;
-    p.num_pages = dims->num_pages;
+    compact_layers_fill(dims, num_layers, path, accept_len, k_cache, v_cache, page_table, seq_lens, status, p);
     return launch_kv_compact_layers(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }
 

@@ -1237,8 +1237,11 @@ __global__ __launch_bounds__(256) void verify_tail_kernel(AttnParams p, AcceptPa
     __shared__ AcceptShared sh;
     __shared__ CompactShared cs;
     const int b = blockIdx.x, tid = threadIdx.x;
-    kv_compact_prefetch(cp, b, tid, cs);   // on its way while the path is being chosen
+    // (in-cache layout, no tree tensors: the in-place move of the accepted rows follows as a launch of its own)
+    const bool append = cp.k_tree != nullptr;
+    if (append) kv_compact_prefetch(cp, b, tid, cs);   // on its way while the path is being chosen
     accept_path_body(ap, b, tid, tid < 64, sh);
+    if (!append) return;
     __syncthreads();
     kv_compact_body(cp, b, tid, sh.accept_len, sh.path, cs);
 }

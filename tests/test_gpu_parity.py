@@ -418,6 +418,47 @@ def test_verify_step_equals_the_three_calls_and_the_oracle(R, oracle_mod, index,
     assert np.array_equal(cache_bits(dw.k_cache), kc) and np.array_equal(cache_bits(dw.v_cache), vc)
 
 
+@pytest.mark.parametrize("T,Hq,D,lens", [(16, 8, 128, [0, 1, 15, 16, 200]), (40, 16, 64, [333, 1024, 77, 5]),
+                                         (128, 16, 128, [50, 700])])
+def test_verify_step_with_the_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens):
+    # in-cache layout, one layer: attention over the cache, acceptance, the accepted rows move in place
+    import torch
+    w = W.make_custom("incache_step_T%d" % T, B=len(lens), Hq=Hq, Hkv=4, D=D, T=T, seq_lens=lens, tree="trie", depth=7,
+                      p_match=0.8, seed=418 + T)
+    ref, ref_lse = oracle_mod.tree_attn(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table, w.seq_lens,
+                                        w.parents)
+    kc, vc, table = W.place_tree_in_cache(w, seed=6)
+    al, path, bonus = oracle_mod.accept_path(w.draft_tokens, w.target_tokens, w.parents, w.max_path)
+    kc_ref, vc_ref, sl_ref = kc[None].copy(), vc[None].copy(), w.seq_lens.copy()
+    oracle_mod.kv_compact_layers(kc_ref, vc_ref, path, al, table, sl_ref)
+    assert al.max() >= 1   # something moves
+
+    dw = R.to_device(w)
+    bf16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    dims = R.make_dims(w.B, w.T, w.Hq, w.Hkv, w.D, table.shape[1], w.max_path, kc.shape[0])
+    bound = int(max(lens))
+    ws = torch.empty(max(R.reader_workspace_bytes(dims, bound), 256), dtype=torch.uint8, device="cuda")
+    d_kc, d_vc, d_table = bf16(kc), bf16(vc), torch.from_numpy(table).cuda()
+    dw.out.fill_(float("nan"))
+    R.reader_verify_step(dims, dw.q, None, None, d_kc, d_vc, d_table, dw.seq_lens, dw.parents, dw.draft_tokens,
+                         dw.target_tokens, dw.out, dw.lse, dw.accept_len, dw.path, dw.bonus, bound, ws, dw.status)
+    torch.cuda.synchronize()
+    assert int(dw.status.item()) == 0
+    assert_close(bf16_to_np(dw.out), ref, what="in-cache step attention")
+    assert_close(dw.lse.cpu().numpy().astype(np.float64), ref_lse, what="in-cache step lse")
+    assert np.array_equal(dw.accept_len.cpu().numpy(), al) and np.array_equal(dw.bonus.cpu().numpy(), bonus)
+    assert np.array_equal(dw.path.cpu().numpy(), path)
+    assert np.array_equal(dw.seq_lens.cpu().numpy(), sl_ref)
+    assert np.array_equal(cache_bits(d_kc), kc_ref[0]) and np.array_equal(cache_bits(d_vc), vc_ref[0])
+    # one tree tensor without the other is refused, nothing changes
+    with pytest.raises(R.ReaderError):
+        R.reader_verify_step(dims, dw.q, dw.k_tree, None, d_kc, d_vc, d_table, dw.seq_lens, dw.parents,
+                             dw.draft_tokens, dw.target_tokens, dw.out, dw.lse, dw.accept_len, dw.path, dw.bonus,
+                             bound, ws, dw.status)
+    torch.cuda.synchronize()
+    assert np.array_equal(dw.seq_lens.cpu().numpy(), sl_ref)
+
+
 def test_verify_step_rejects_bad_arguments(R):
     import torch
     w = W.make_config(0)
