@@ -329,6 +329,37 @@ def time_target_tokens(R, torch, reps=20):
     return greedy, sampled
 
 
+def time_drafter(R, W, n_tokens=65536, n_trees=2000):
+    """The host-side retrieval drafter (plain C++ on the host cores, one thread): n-gram trie of depth 8
+    over a self-repetitive token stream, then one draft tree of at most 32 nodes (5 levels) and a search
+    path of 8 tokens per context of 3 tokens, for contexts taken along the stream."""
+    import numpy as np
+    text = W.make_token_stream(n_tokens, seed=W.SEED_BASE + 95)
+    trie = R.Trie(8)
+    t0 = time.perf_counter()
+    for lo in range(0, n_tokens, 4096):            # appended piece by piece, as decoding does
+        trie.insert(text[lo:lo + 4096])
+    t_insert = time.perf_counter() - t0
+    rng = np.random.Generator(np.random.PCG64(W.SEED_BASE + 96))
+    ends = rng.integers(8, n_tokens, size=n_trees)
+    nodes = 0
+    t0 = time.perf_counter()
+    for e in ends:
+        tokens, _ = trie.extract_tree(text[e - 3:e], 5, 32)
+        nodes += len(tokens)
+    t_tree = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for e in ends:
+        trie.search_path(text[e - 3:e], 8)
+    t_path = time.perf_counter() - t0
+    res = {"stream_tokens": n_tokens, "trie_nodes": len(trie), "insert_tokens_per_s": n_tokens / t_insert,
+           "extract_tree_us": t_tree / n_trees * 1e6, "mean_tree_nodes": nodes / n_trees,
+           "search_path_us": t_path / n_trees * 1e6, "threads": 1,
+           "note": "per-call times include the Python binding"}
+    trie.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -439,6 +470,8 @@ def main():
         log("timing the arg max over logits")
         line["kv_compact_layers"] = time_compact_layers(R, torch, W)
         line["target_argmax"], line["target_sample"] = time_target_tokens(R, torch)
+        log("timing the host drafter")
+        line["drafter"] = time_drafter(R, W)
     print(json.dumps(line), flush=True)
 
 

@@ -529,3 +529,20 @@ def place_tree_in_cache(w: Workload, seed: int = 0):
             tpos = L + np.arange(w.T)
             dst[pages[tpos // ps], :, tpos % ps, :] = tree[b]
     return kc, vc, table
+
+
+def make_token_stream(n: int, vocab: int = 128256, n_phrases: int = 64, p_phrase: float = 0.5, seed: int = 0):
+    """Token ids with phrases that come back, as in generated text with self-repetition (Section
+    4.1): with probability p_phrase one of n_phrases fixed phrases of 3..11 tokens follows, else
+    one token with a Zipf-like distribution over the vocabulary.  int32 [n]."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    phrases = [rng.integers(0, vocab, size=int(rng.integers(3, 12))) for _ in range(n_phrases)]
+    out, have = [], 0
+    while have < n:
+        if rng.random() < p_phrase:
+            piece = phrases[int(rng.integers(0, n_phrases))]
+        else:
+            piece = np.minimum(vocab - 1, rng.zipf(1.5, size=1) - 1)
+        out.append(np.asarray(piece, dtype=np.int64))
+        have += len(piece)
+    return np.concatenate(out)[:n].astype(np.int32)
