@@ -189,6 +189,9 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
         const long long axis_max = (long long)p.Hkv * p.B * ((max_seq_len + kTile - 1) / kTile + p.n_tree_tiles + p.pair_cost);
         p.axis32 = (axis_max + 2) * (p.n_ranges + 1) < 0x7fffffffLL ? 1 : 0;
         if (getenv("READER_ATTN_AXIS64")) p.axis32 = 0;   // tests: force the 64-bit path
+        p.ranges_shift = -1;
+        for (int sh = 0; sh < 16; ++sh)
+            if (p.n_ranges == (1 << sh)) p.ranges_shift = sh;
     }
     p.num_pages = dims->num_pages;
     p.tree_in_cache = tree_in_cache ? 1 : 0;

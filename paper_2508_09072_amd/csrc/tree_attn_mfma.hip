@@ -146,6 +146,19 @@ __device__ inline I cost_pos_of_tile(const AttnParams &p, const int *s_pref, int
     return (I)p.Hkv * (s_pref[b] + (I)b * p.pair_cost) + (I)hkv * (n_b + p.pair_cost) + p.pair_cost + t;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves:
+// four shifted adds inside each row of 16 lanes (lanes shifted in from outside the row read 0),
+// then lane 15 of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.
+__device__ inline int wave_inclusive_scan(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // A place on the tile axis: tile t of pair (b, hkv); `flat` counts the tiles in front of it.
 // The end of the axis is (B, 0, 0).
 struct TilePos {
@@ -233,22 +246,36 @@ enum {
 constexpr int kDescSlots = 256;
 
 // Descriptor of tile idx of pair (b, hkv); it is tile i_tile of a range of n_tiles tiles.
-// `table` is the page table or a copy of it; `s_len` the clamped lengths in LDS, or null.
-__device__ inline void write_tile_desc(const AttnParams &p, const int32_t *table, const int32_t *__restrict__ seq_lens,
-                                       const int *s_len, const int *s_pref, int b, int hkv, int idx, int i_tile,
-                                       int n_tiles, TileDesc *slot, int &bad, int range_id) {
+// `table` is the page table or a copy of it in LDS (table_in_lds); `s_len` the clamped lengths in LDS, or null.
+__device__ inline void write_tile_desc(const AttnParams &p, const int32_t *table, bool table_in_lds,
+                                       const int32_t *__restrict__ seq_lens, const int *s_len, int b, int hkv, int idx,
+                                       int i_tile, int n_tiles, TileDesc *slot, int &bad) {
     const int L = s_len ? s_len[b] : clamp_len(p, seq_lens, b);
     const int n_pre = (L + kTile - 1) / kTile, n_units = n_pre + p.n_tree_tiles;
     int blk[4], n_valid, flags = 0;
     if (idx < n_pre) {
         n_valid = min(kTile, L - idx * kTile);
-        const int32_t *row = table + (size_t)b * p.max_pages + idx * 4;
+        // The page ids of the quarters that hold rows, asked for together (one wait, not four) and
+        // from the address space the table is in; position idx*64 + j*16 < L <= 16 * max_pages for
+        // every quarter j <= j_last, so the reads stay inside the sequence's row of the table.
+        const int j_last = (n_valid - 1) >> 4;
+        const size_t at = (size_t)b * p.max_pages + idx * 4;
+        int page[4];
+        if (table_in_lds) {
+            typedef __attribute__((address_space(3))) const int32_t lds_i32;
+            lds_i32 *row = (lds_i32 *)table + at;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) page[j] = j <= j_last ? row[j] : -1;
+        } else {
+            const int32_t *row = table + at;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) page[j] = j <= j_last ? row[j] : -1;
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             blk[j] = -1;
-            if (j * 16 < n_valid) {   // position idx*64 + j*16 < L <= 16 * max_pages: inside the row
-                const int page = row[j];
-                if (page >= 0 && page < p.num_pages) blk[j] = page * p.Hkv + hkv;
+            if (j <= j_last) {
+                if (page[j] >= 0 && page[j] < p.num_pages) blk[j] = page[j] * p.Hkv + hkv;
                 else bad |= READER_STATUS_BAD_PAGE;
             }
         }
@@ -259,17 +286,7 @@ __device__ inline void write_tile_desc(const AttnParams &p, const int32_t *table
         // rows of the tree tensors from (b, first node) on; with the tree in the cache: the pair
         blk[0] = blk[1] = blk[2] = blk[3] = p.tree_in_cache ? b * p.Hkv + hkv : (b * p.T + tt * kTile) * p.Hkv + hkv;
     }
-    if (idx == 0) {
-        flags |= kDescPairStart;
-        // for the merge kernel: which workgroups hold tiles of this pair
-        int2 *info = reinterpret_cast<int2 *>(p.pair_info) + (b * p.Hkv + hkv);
-        const int w_last =
-            p.axis32 ? range_of_position<int>(cost_pos_of_tile<int>(p, s_pref, b, hkv, n_units - 1),
-                                              cost_total<int>(p, s_pref), p.n_ranges)
-                     : range_of_position<long long>(cost_pos_of_tile<long long>(p, s_pref, b, hkv, n_units - 1),
-                                                    cost_total<long long>(p, s_pref), p.n_ranges);
-        *info = make_int2(range_id, w_last);
-    }
+    if (idx == 0) flags |= kDescPairStart;
     if (idx + 1 == n_units) flags |= kDescPairEnd;
     if (idx == 0 || i_tile == 0) {
         flags |= kDescFresh;
@@ -286,9 +303,9 @@ __device__ inline void write_tile_desc(const AttnParams &p, const int32_t *table
 // tile.  The item is found by walking the pairs from the start of the range (a range holds
 // few pairs unless the sequences are very short); i must be below the number of items.
 template <bool kWithQ>
-__device__ inline void build_item(const AttnParams &p, const int32_t *table, const int32_t *__restrict__ seq_lens,
-                                  const int *s_len, const int *s_pref, const TilePos &start, int n_tiles, int i,
-                                  TileDesc *slot, int &bad, int range_id) {
+__device__ inline void build_item(const AttnParams &p, const int32_t *table, bool table_in_lds,
+                                  const int32_t *__restrict__ seq_lens, const int *s_len, const int *s_pref,
+                                  const TilePos &start, int n_tiles, int i, TileDesc *slot, int &bad) {
     int b = start.b, hkv = start.hkv, t = start.t, pos = i, tiles_before = 0;
     while (b < p.B) {
         if (kWithQ) {
@@ -302,8 +319,7 @@ __device__ inline void build_item(const AttnParams &p, const int32_t *table, con
         }
         const int avail = s_pref[b + 1] - s_pref[b] - t;   // tiles of this pair from t on
         if (pos < avail) {
-            write_tile_desc(p, table, seq_lens, s_len, s_pref, b, hkv, t + pos, tiles_before + pos, n_tiles, slot, bad,
-                            range_id);
+            write_tile_desc(p, table, table_in_lds, seq_lens, s_len, b, hkv, t + pos, tiles_before + pos, n_tiles, slot, bad);
             return;
         }
         pos -= avail;
@@ -523,20 +539,16 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             s_len[lane] = L;
             units = (L + kTile - 1) / kTile + p.n_tree_tiles;
         }
-        int v = units;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int t = __shfl_up(v, off);
-            if (lane >= off) v += t;
-        }
+        const int v = wave_inclusive_scan(units);
         if (lane < p.B) s_pref[lane + 1] = v;
         if (lane == 0) s_pref[0] = 0;
         // This workgroup's tiles: [lo, hi) of the tile axis, an even share of the cost axis.  Lane b
         // holds sequence b's tile count and the tiles in front of it, so a place on the cost axis
-        // is found with two votes (which sequence, which kv head) instead of searches and divisions.
+        // is found with two votes (which sequence, which kv head) instead of searches and divisions;
+        // what the chosen lane holds is read with a scalar lane index.
         const int excl = v - units;
         const int base = p.Hkv * (excl + lane * p.pair_cost);   // where sequence `lane` starts on the cost axis
-        const int total = __shfl(v, p.B - 1);
+        const int total = __builtin_amdgcn_readlane(v, 63);      // (lanes past the last sequence add nothing)
         const int cost_all = p.Hkv * (total + p.B * p.pair_cost);
         auto locate_by_vote = [&](int pos) {
             TilePos r;
@@ -544,17 +556,21 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                 r.b = p.B; r.hkv = 0; r.t = 0; r.flat = p.Hkv * total;
                 return r;
             }
-            const int b = __popcll(__ballot(lane < p.B && base <= pos)) - 1;   // pos >= 0 = base of sequence 0
-            const int span = __shfl(units, b) + p.pair_cost;                    // cost positions per pair
-            const int rel = pos - __shfl(base, b);
+            const int b = __builtin_amdgcn_readfirstlane(__popcll(__ballot(lane < p.B && base <= pos)) - 1);   // pos >= 0 = base of sequence 0
+            const int span = __builtin_amdgcn_readlane(units, b) + p.pair_cost;   // cost positions per pair
+            const int rel = pos - __builtin_amdgcn_readlane(base, b);
             const int hkv = __popcll(__ballot(lane < p.Hkv && lane * span <= rel)) - 1;
             const int rr = rel - hkv * span - p.pair_cost;
             r.b = b; r.hkv = hkv; r.t = rr > 0 ? rr : 0;
-            r.flat = p.Hkv * __shfl(excl, b) + hkv * (span - p.pair_cost) + r.t;
+            r.flat = p.Hkv * __builtin_amdgcn_readlane(excl, b) + hkv * (span - p.pair_cost) + r.t;
             return r;
         };
-        lo = locate_by_vote(range_begin<int>(range_id, cost_all, p.n_ranges));
-        hi = locate_by_vote(range_begin<int>(range_id + 1, cost_all, p.n_ranges));
+        auto cut = [&](int w) {   // where range w starts on the cost axis
+            return p.ranges_shift >= 0 ? (int)(((unsigned)w * (unsigned)cost_all) >> p.ranges_shift)
+                                       : range_begin<int>(w, cost_all, p.n_ranges);
+        };
+        lo = locate_by_vote(cut(range_id));
+        hi = locate_by_vote(cut(range_id + 1));
     } else {
         if (p.B <= 64) {
             int v = 0;
@@ -602,12 +618,30 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
 
     int bad = 0;
     auto write_item = [&](int i) {
-        build_item<kDma>(p, i < kDescSlots ? table : page_table, seq_lens, s_len, s_pref, lo, n_tiles, i,
-                         s_desc + (i & (kDescSlots - 1)), bad, range_id);
+        const bool from_lds = table_in_lds && i < kDescSlots;   // (the stage that held the copy is in use later)
+        build_item<kDma>(p, from_lds ? table : page_table, from_lds, seq_lens, s_len, s_pref, lo, n_tiles, i,
+                         s_desc + (i & (kDescSlots - 1)), bad);
     };
     if (htid >= 0)
         for (int i = htid; i < min(n_iter, kDescSlots); i += kHelpers) write_item(i);
     __syncthreads();   // the list is written
+
+    // For the merge kernel: which workgroups hold tiles of each pair that starts in this range
+    // (first = this one, last from the position of the pair's last tile).  Off the path to the
+    // first copy: with dedicated copy wavefronts the computing ones do it, which wait anyway.
+    {
+        const int first = lo.b * p.Hkv + lo.hkv + (lo.t > 0 ? 1 : 0);
+        const int last = hi.b * p.Hkv + hi.hkv - (hi.t > 0 ? 0 : 1);
+        for (int q = first + tid; q <= last && tid < 256; q += 256) {
+            const int b = q / p.Hkv, hkv = q - b * p.Hkv, n_units = s_pref[b + 1] - s_pref[b];
+            const int w_last =
+                p.axis32 ? range_of_position<int>(cost_pos_of_tile<int>(p, s_pref, b, hkv, n_units - 1),
+                                                  cost_total<int>(p, s_pref), p.n_ranges)
+                         : range_of_position<long long>(cost_pos_of_tile<long long>(p, s_pref, b, hkv, n_units - 1),
+                                                        cost_total<long long>(p, s_pref), p.n_ranges);
+            reinterpret_cast<int2 *>(p.pair_info)[q] = make_int2(range_id, w_last);
+        }
+    }
 
     auto desc_of = [&](int i) -> const TileDesc * { return s_desc + (i & (kDescSlots - 1)); };
     auto desc_b = [&](int i) { return __builtin_amdgcn_readfirstlane(desc_of(i)->b); };
