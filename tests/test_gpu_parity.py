@@ -459,6 +459,34 @@ def test_verify_step_with_the_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, le
     assert np.array_equal(dw.seq_lens.cpu().numpy(), sl_ref)
 
 
+@pytest.mark.parametrize("index", [3, 4])
+def test_verify_step_full_size_sampled_rows(R, oracle_mod, index):
+    # the fused step exactly as the benchmark launches it, at the presets' full sizes: sampled attention rows
+    # against the oracle; acceptance, appended rows and new lengths bit for bit (the oracle does those at any size)
+    import torch
+    w = W.make_config(index)
+    print("full-size fused step:", w.name, flush=True)
+    dw = R.to_device(w)
+    R.reader_verify_step(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table, dw.seq_lens,
+                         dw.parents, dw.draft_tokens, dw.target_tokens, dw.out, dw.lse, dw.accept_len, dw.path,
+                         dw.bonus, dw.max_seq_len, dw.workspace, dw.status)
+    torch.cuda.synchronize()
+    assert int(dw.status.item()) == 0
+    out, lse = bf16_to_np(dw.out), dw.lse.cpu().numpy().astype(np.float64)
+    rng = np.random.Generator(np.random.PCG64(950 + index))
+    n = 64
+    rows = np.stack([rng.integers(0, w.B, n), rng.integers(0, w.Hq, n), rng.integers(0, w.T, n)], axis=1).astype(np.int32)
+    ref, ref_lse = oracle_mod.tree_attn_rows(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table,
+                                             w.seq_lens, w.parents, rows)
+    assert_close(np.stack([out[b, i, hq] for b, hq, i in rows]), ref, what=w.name + " fused step, sampled rows")
+    assert_close(np.asarray([lse[b, hq, i] for b, hq, i in rows]), ref_lse, what=w.name + " fused step, sampled lse")
+    assert np.isfinite(out).all()
+    al, path, bonus, kc, vc, sl = oracle_step(oracle_mod, w)
+    assert np.array_equal(dw.accept_len.cpu().numpy(), al) and np.array_equal(dw.bonus.cpu().numpy(), bonus)
+    assert np.array_equal(dw.path.cpu().numpy(), path) and np.array_equal(dw.seq_lens.cpu().numpy(), sl)
+    assert np.array_equal(cache_bits(dw.k_cache), kc) and np.array_equal(cache_bits(dw.v_cache), vc)
+
+
 def test_verify_step_rejects_bad_arguments(R):
     import torch
     w = W.make_config(0)
