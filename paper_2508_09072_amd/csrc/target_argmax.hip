@@ -3,8 +3,12 @@
 // verification step.  The logits of a step are as large as its KV stream (vocabulary 128256:
 // 256 KB per row), so this is a plain streaming reduction: one workgroup per row, 128-bit
 // loads (eight in flight per thread), a running (value, index) per thread, then a wavefront
-// and a workgroup reduction.
+// and a workgroup reduction.  The workgroup is 512 threads wide, 1024 when there are few rows
+// (measured: 512 rows take 31 us with 1024 threads and 39 us with 256; from 1024 rows on 512
+// threads are the fastest).
 // Ties go to the lowest index; a NaN is never larger than anything (a row of NaNs gives 0).
+#include <stdlib.h>
+
 #include "internal.h"
 
 namespace reader {
@@ -21,8 +25,9 @@ __device__ inline void take(Best &b, float v, int i) {
     if (v > b.v || (v == b.v && i < b.i)) { b.v = v; b.i = i; }
 }
 
-__global__ __launch_bounds__(256) void target_argmax_kernel(const uint16_t *__restrict__ logits, int32_t *__restrict__ out,
-                                                            int V) {
+template <int NT, int NL>
+__global__ __launch_bounds__(NT) void target_argmax_kernel(const uint16_t *__restrict__ logits, int32_t *__restrict__ out,
+                                                           int V) {
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint16_t *src = logits + (size_t)row * V;
     Best best = {-INFINITY, 0x7fffffff};
@@ -40,17 +45,17 @@ __global__ __launch_bounds__(256) void target_argmax_kernel(const uint16_t *__re
             take(best, __uint_as_float(u[e] & 0xffff0000u), base + 2 * e + 1);
         }
     };
-    int c = tid;
-    for (; c + 7 * 256 < n_vec; c += 8 * 256) {      // eight loads in flight per thread
+    for (int c = tid; c < n_vec; c += NL * NT) {      // NL loads in flight per thread, also in the last round
         // read once: streamed past the caches (about a sixth more bandwidth out of HBM than plain loads)
-        uint4 w[8];
+        uint4 w[NL];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) w[j] = load_stream16(vec + c + j * 256);
+        for (int j = 0; j < NL; ++j)
+            if (c + j * NT < n_vec) w[j] = load_stream16(vec + c + j * NT);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) scan(w[j], c + j * 256);
+        for (int j = 0; j < NL; ++j)
+            if (c + j * NT < n_vec) scan(w[j], c + j * NT);
     }
-    for (; c < n_vec; c += 256) scan(load_stream16(vec + c), c);
-    for (int j = head + n_vec * 8 + tid; j < V; j += 256) take(best, __uint_as_float((uint32_t)src[j] << 16), j);
+    for (int j = head + n_vec * 8 + tid; j < V; j += NT) take(best, __uint_as_float((uint32_t)src[j] << 16), j);
 
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -58,13 +63,13 @@ __global__ __launch_bounds__(256) void target_argmax_kernel(const uint16_t *__re
         const int oi = __shfl_xor(best.i, off);
         take(best, ov, oi);
     }
-    __shared__ float s_v[4];
-    __shared__ int s_i[4];
+    __shared__ float s_v[NT / 64];
+    __shared__ int s_i[NT / 64];
     if (lane == 0) { s_v[wave] = best.v; s_i[wave] = best.i; }
     __syncthreads();
     if (tid == 0) {
         Best b = {s_v[0], s_i[0]};
-        for (int w = 1; w < 4; ++w) take(b, s_v[w], s_i[w]);
+        for (int w = 1; w < NT / 64; ++w) take(b, s_v[w], s_i[w]);
         out[row] = b.i == 0x7fffffff ? 0 : b.i;
     }
 }
@@ -72,7 +77,13 @@ __global__ __launch_bounds__(256) void target_argmax_kernel(const uint16_t *__re
 }  // namespace
 
 hipError_t launch_target_argmax(const uint16_t *logits, int32_t *out, int rows, int V, hipStream_t stream) {
-    hipLaunchKernelGGL(target_argmax_kernel, dim3(rows), dim3(256), 0, stream, logits, out, V);
+    // threads per row so that the rows of the launch fill the chip's 256 x 2048 thread slots
+    const char *env = getenv("READER_ARGMAX_THREADS");      // experiments: 256, 512 or 1024
+    const int forced = env ? atoi(env) : 0;
+    const int nt = forced ? forced : rows <= 768 ? 1024 : 512;
+    if (nt == 1024) hipLaunchKernelGGL((target_argmax_kernel<1024, 8>), dim3(rows), dim3(1024), 0, stream, logits, out, V);
+    else if (nt == 512) hipLaunchKernelGGL((target_argmax_kernel<512, 8>), dim3(rows), dim3(512), 0, stream, logits, out, V);
+    else hipLaunchKernelGGL((target_argmax_kernel<256, 8>), dim3(rows), dim3(256), 0, stream, logits, out, V);
     return note_hip_error("launch target_argmax_kernel", hipGetLastError());
 }
 

@@ -12,14 +12,14 @@
 // find the block that crosses u * total, and only that block (1 KB, still in cache) is read
 // again to find the token.  All sums are fp32: where u * total falls within rounding of a
 // token boundary the neighbouring token may come out.
+#include <stdlib.h>
+
 #include "internal.h"
 
 namespace reader {
 
 namespace {
 
-constexpr int kSampleThreads = 512;
-constexpr int kSampleWaves = kSampleThreads / 64;
 constexpr int kBlockTokens = 512;   // 64 lanes x 8 tokens
 
 // Wavefront reductions on the vector ALU's lane-crossing paths (no LDS traffic): four shifts
@@ -67,10 +67,13 @@ __device__ inline void unpack8(const uint4 &w, float c, float y[8]) {
 // Row layout: `head` tokens in front of the first 16-byte boundary, n_vec groups of 8 tokens,
 // a tail of fewer than 8.  Statistics slot 0 is the head, slot 1 + k block k of the aligned
 // part, the last slot the tail.
+// kSampleThreads: 512, or 1024 when the launch has few rows (more loads in flight per row).
+template <int kSampleThreads>
 __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uint16_t *__restrict__ logits,
                                                                        const int32_t *__restrict__ parents,
                                                                        const float *__restrict__ uniforms,
                                                                        int32_t *__restrict__ out, int T, int V, float c) {
+    constexpr int kSampleWaves = kSampleThreads / 64;
     extern __shared__ float2 s_stat[];        // (maximum, sum) per slot
     __shared__ int s_par[READER_MAX_T];
     __shared__ float s_wsum[kSampleWaves];
@@ -291,8 +294,15 @@ hipError_t launch_target_sample(const uint16_t *logits, const int32_t *parents, 
                                 int B, int T, int V, float temperature, hipStream_t stream) {
     const int n_slots = (V / 8 + 63) / 64 + 3;
     const float c = 1.44269504088896340736f / temperature;
-    hipLaunchKernelGGL(target_sample_kernel, dim3(B * T), dim3(kSampleThreads), (size_t)n_slots * sizeof(float2), stream,
-                       logits, parents, uniforms, out, T, V, c);
+    const char *env = getenv("READER_SAMPLE_THREADS");      // experiments: 512 or 1024
+    const int forced = env ? atoi(env) : 0;
+    const int nt = forced ? forced : (long long)B * T <= 768 ? 1024 : 512;
+    if (nt == 1024)
+        hipLaunchKernelGGL(target_sample_kernel<1024>, dim3(B * T), dim3(1024), (size_t)n_slots * sizeof(float2), stream,
+                           logits, parents, uniforms, out, T, V, c);
+    else
+        hipLaunchKernelGGL(target_sample_kernel<512>, dim3(B * T), dim3(512), (size_t)n_slots * sizeof(float2), stream,
+                           logits, parents, uniforms, out, T, V, c);
     return note_hip_error("launch target_sample_kernel", hipGetLastError());
 }
 
