@@ -37,6 +37,13 @@
  *  - Grouped-query attention: query head hq reads kv head hq / (Hq / Hkv).
  *  - Paged cache: position j of sequence b lives in physical page
  *    page_table[b][j / page_size], slot j % page_size.
+ *  - Threads: the compute entry points keep no state between calls and may be called
+ *    from several host threads, each on its own stream and with its own workspace,
+ *    outputs and status word; calls that share a workspace or write the same cache
+ *    pages or lengths must be ordered by the caller (one stream, or events).
+ *    reader_last_error_detail and the reader_profile_* hooks share one process-wide
+ *    buffer and are meant for one thread.  The READER_ATTN_* / READER_*_THREADS
+ *    environment variables the host code reads are for experiments and tests only.
  */
 #ifndef READER_H
 #define READER_H

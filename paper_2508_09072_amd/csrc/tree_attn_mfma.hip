@@ -52,6 +52,8 @@
 #include <hip/hip_ext.h>
 
 #include "accept_compact.h"
+#include <mutex>
+
 #include "internal.h"
 
 namespace reader {
@@ -1291,12 +1293,16 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
                             (p.B <= kMaxLensInLds ? (size_t)p.B * sizeof(int) + 16 : 0);
     // More than 64 KB of LDS per workgroup has to be asked for; the limit counts the
     // kernel's static LDS too, so ask for exactly what this launch needs.
-    static size_t lds_allowed = 0;
-    if (main_lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_mfma_kernel<D, RB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)main_lds);
-        if (e != hipSuccess) { (void)hipGetLastError(); return note_hip_error("hipFuncSetAttribute(attention LDS size)", e); }
-        lds_allowed = main_lds;
+    {
+        static std::mutex guard;             // host threads may call in at the same time
+        static size_t lds_allowed = 0;
+        std::lock_guard<std::mutex> lock(guard);
+        if (main_lds > lds_allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tree_attn_mfma_kernel<D, RB>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)main_lds);
+            if (e != hipSuccess) { (void)hipGetLastError(); return note_hip_error("hipFuncSetAttribute(attention LDS size)", e); }
+            lds_allowed = main_lds;
+        }
     }
     // with events: they take the kernel's own start and end time stamps
     if (ev_start && ev_stop)

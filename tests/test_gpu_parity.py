@@ -487,6 +487,48 @@ def test_verify_step_full_size_sampled_rows(R, oracle_mod, index):
     assert np.array_equal(cache_bits(dw.k_cache), kc) and np.array_equal(cache_bits(dw.v_cache), vc)
 
 
+def test_two_host_threads_on_their_own_streams(R, oracle_mod):
+    # the entry points keep no state between calls: two host threads, each with its own stream, workspace and
+    # outputs, run whole steps of different shapes at the same time and get what a single thread gets
+    import threading
+    import torch
+    shapes = [W.make_custom("thr_a", B=3, Hq=8, Hkv=2, D=128, T=24, seq_lens=[700, 65, 1300], tree="trie", depth=6,
+                            seed=431),
+              W.make_custom("thr_b", B=2, Hq=16, Hkv=2, D=64, T=64, seq_lens=[2000, 900], tree="uniform", depth=5,
+                            seed=432)]
+    single = [run_step(R, w) for w in shapes]
+    results, errors = [None, None], []
+
+    def work(k):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for _ in range(20):
+                    dw = R.to_device(shapes[k])
+                    R.reader_verify_step(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table,
+                                         dw.seq_lens, dw.parents, dw.draft_tokens, dw.target_tokens, dw.out, dw.lse,
+                                         dw.accept_len, dw.path, dw.bonus, dw.max_seq_len, dw.workspace, dw.status)
+                    stream.synchronize()
+                    results[k] = dw
+        except Exception as e:      # reported by the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for k in range(2):
+        assert int(results[k].status.item()) == 0
+        for name in ("out", "lse", "accept_len", "path", "bonus", "seq_lens"):
+            assert torch.equal(getattr(results[k], name), getattr(single[k], name)), (k, name)
+        for name in ("k_cache", "v_cache"):
+            assert np.array_equal(cache_bits(getattr(results[k], name)), cache_bits(getattr(single[k], name))), (k, name)
+
+
 def test_verify_step_rejects_bad_arguments(R):
     import torch
     w = W.make_config(0)
