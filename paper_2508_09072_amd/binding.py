@@ -61,6 +61,11 @@ def load():
         return _lib
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("HIP library missing: %s (run `python -m paper_2508_09072_amd.build`)" % LIB_PATH)
+    # PyTorch first: it brings its own copy of the HIP runtime, and the tensors and streams handed to
+    # the library belong to that one.  Loaded the other way round the process ends up with the
+    # library's kernels registered in a runtime that PyTorch's streams do not belong to, and every
+    # launch fails with hipErrorNoDevice.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, dp = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ReaderDims)
     lib.reader_version.restype = ctypes.c_char_p

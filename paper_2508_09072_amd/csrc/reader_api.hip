@@ -13,6 +13,10 @@ namespace reader {
 
 static char g_error_detail[256] = "";
 
+// The runtime keeps the last error of the calling thread until somebody reads it, whoever caused
+// it: an error another library left behind must not be taken for a failed launch of ours.
+static void forget_stale_error() { (void)hipGetLastError(); }
+
 hipError_t note_hip_error(const char *where, hipError_t e) {
     if (e != hipSuccess) snprintf(g_error_detail, sizeof g_error_detail, "%s: %s", where, hipGetErrorName(e));
     return e;
@@ -243,12 +247,14 @@ extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const vo
     if (rc != READER_OK || empty) return rc;
     hipError_t e;
     if (dims->variant == 1) {
+        forget_stale_error();
         e = launch_tree_attn_scalar(p, (hipStream_t)stream);
     } else {
         if (!workspace || ((uintptr_t)workspace & 255) != 0) return READER_EWORKSPACE;
         if (workspace_bytes < reader_workspace_bytes(dims, max_seq_len)) return READER_EWORKSPACE;
         hipEvent_t ev_a, ev_b;
         profile_next(&ev_a, &ev_b);
+        forget_stale_error();
         e = launch_tree_attn_mfma(p, (hipStream_t)stream, ev_a, ev_b);
     }
     return e == hipSuccess ? READER_OK : READER_EHIP;
@@ -275,6 +281,7 @@ extern "C" int reader_verify_step(const reader_dims *dims, const void *q, const 
     compact_fill(dims, k_tree, v_tree, path, accept_len, k_cache, v_cache, page_table, seq_lens, status, cp);
     hipEvent_t ev_a, ev_b;
     profile_next(&ev_a, &ev_b);
+    forget_stale_error();
     if (launch_tree_attn_mfma(p, (hipStream_t)stream, ev_a, ev_b, &ap, &cp) != hipSuccess) return READER_EHIP;
     if (p.tree_in_cache) {
         // the tree rows are in the cache already: the accepted ones move in place (this layer's cache)
@@ -322,6 +329,7 @@ extern "C" int reader_accept_path(const reader_dims *dims, const int32_t *draft_
         return READER_EINVAL;
     AcceptParams p;
     accept_fill(dims, draft_tokens, target_tokens, parents, accept_len, path, bonus_token, status, p);
+    forget_stale_error();
     return launch_accept_path(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }
 
@@ -336,6 +344,7 @@ extern "C" int reader_kv_compact(const reader_dims *dims, const void *k_tree, co
         return READER_EINVAL;
     CompactParams p;
     compact_fill(dims, k_tree, v_tree, path, accept_len, k_cache, v_cache, page_table, seq_lens, status, p);
+    forget_stale_error();
     return launch_kv_compact(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }
 
@@ -351,6 +360,7 @@ extern "C" int reader_kv_compact_layers(const reader_dims *dims, int32_t num_lay
         return READER_EINVAL;
     CompactLayersParams p;
     compact_layers_fill(dims, num_layers, path, accept_len, k_cache, v_cache, page_table, seq_lens, status, p);
+    forget_stale_error();
     return launch_kv_compact_layers(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }
 
@@ -373,6 +383,7 @@ extern "C" int reader_kv_rearrange(int32_t NL, int32_t B, int32_t S, int32_t Hkv
     p.k_pad = (uint16_t *)k_pad; p.v_pad = (uint16_t *)v_pad; p.valid = valid; p.new_len = new_len;
     p.dest = (int32_t *)scratch;
     p.NL = NL; p.B = B; p.S = S; p.Hkv = Hkv; p.D = D;
+    forget_stale_error();
     return launch_kv_rearrange(p, (hipStream_t)stream) == hipSuccess ? READER_OK : READER_EHIP;
 }
 
@@ -381,6 +392,7 @@ extern "C" int reader_target_argmax(int32_t rows, int32_t V, const void *logits,
     if (rows < 0 || V < 1) return READER_EINVAL;
     if (rows == 0) return READER_OK;
     if (!logits || !target_tokens) return READER_EINVAL;
+    forget_stale_error();
     return launch_target_argmax((const uint16_t *)logits, target_tokens, rows, V, (hipStream_t)stream) == hipSuccess
                ? READER_OK : READER_EHIP;
 }
@@ -392,6 +404,7 @@ extern "C" int reader_target_sample(int32_t B, int32_t T, int32_t V, const void 
     if ((long long)B * T > 0x7fffffffLL) return READER_EINVAL;
     if (B == 0) return READER_OK;
     if (!logits || !parents || !uniforms || !target_tokens) return READER_EINVAL;
+    forget_stale_error();
     return launch_target_sample((const uint16_t *)logits, parents, uniforms, target_tokens, B, T, V, temperature,
                                 (hipStream_t)stream) == hipSuccess
                ? READER_OK : READER_EHIP;
