@@ -6,11 +6,11 @@
 // depth draw with the same uniform, uniforms[b][depth(n)].
 //
 // One workgroup per (sequence, node) row, one pass over the row (256 KB at vocabulary 128256,
-// as large as the step's KV stream): the row is cut into blocks of 512 consecutive tokens, a
-// wavefront reduces a block to (maximum, sum of exp relative to that maximum) and leaves the
-// pair in LDS; the blocks' sums, brought to the row maximum, are scanned in index order to
-// find the block that crosses u * total, and only that block (1 KB, still in cache) is read
-// again to find the token.  All sums are fp32: where u * total falls within rounding of a
+// as large as the step's KV stream): the row is cut into slots of 2048 consecutive tokens (four
+// 16-byte loads per lane), a wavefront reduces a slot to (maximum, sum of exp relative to that
+// maximum) and leaves the pair in LDS; the slots' sums, brought to the row maximum, are scanned
+// in index order to find the slot that crosses u * total, and only that slot (4 KB, still in
+// cache) is read again to find the token.  All sums are fp32: where u * total falls within rounding of a
 // token boundary the neighbouring token may come out.
 #include <stdlib.h>
 
@@ -20,7 +20,7 @@ namespace reader {
 
 namespace {
 
-constexpr int kBlockTokens = 512;   // 64 lanes x 8 tokens
+constexpr int kGroup = 4;            // 512-token blocks (64 lanes x 8 tokens) per slot
 
 // Wavefront reductions on the vector ALU's lane-crossing paths (no LDS traffic): four shifts
 // inside each row of 16 lanes leave the row's result in its last lane, two row broadcasts
@@ -86,8 +86,8 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
 
     const int head = min(V, (int)(((16 - ((uintptr_t)src & 15)) & 15) >> 1));
     const int n_vec = (V - head) / 8;
-    const int n_blocks = (n_vec + 63) / 64;
-    const int tail_at = head + n_vec * 8, n_slots = n_blocks + 2;
+    const int n_blocks = (n_vec + 63) / 64, n_groups = (n_blocks + kGroup - 1) / kGroup;
+    const int tail_at = head + n_vec * 8, n_slots = n_groups + 2;
     const uint4 *vec = reinterpret_cast<const uint4 *>(src + head);
 
     // head and tail: at most 7 tokens each, wavefront 0 and 1
@@ -98,48 +98,52 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
         const float s = wave_sum(m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(y - m));
         if (lane == 0) s_stat[wave == 0 ? 0 : n_slots - 1] = make_float2(m, s);
     }
-    // blocks: four per wavefront in flight.  Per token: widen, squash a NaN to -inf (the maximum
-    // of a NaN and a number is the number), block maximum, one fused multiply-add, exp2, add.
-    // Lanes past the end of the row hold -inf bit patterns, so nothing is selected per token.
-    auto block_stat = [&](const uint4 &w, int blk) {
-        const uint32_t u[4] = {w.x, w.y, w.z, w.w};
-        float x[8];
+    // slots: a wavefront takes the four blocks of a slot at once.  Per token: widen, squash a NaN to
+    // -inf (the maximum of a NaN and a number is the number), one fused multiply-add, exp2, add;
+    // per slot: one maximum and one sum across the wavefront.  Lanes past the end of the row hold
+    // -inf bit patterns, so nothing is selected per token.
+    const uint4 nothing = make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);
+    for (int grp = wave; grp < n_groups; grp += kSampleWaves) {
+        uint4 w[kGroup];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            x[2 * e] = fmaxf(__uint_as_float(u[e] << 16), -INFINITY);
-            x[2 * e + 1] = fmaxf(__uint_as_float(u[e] & 0xffff0000u), -INFINITY);
+        for (int j = 0; j < kGroup; ++j) {
+            const int g = (grp * kGroup + j) * 64 + lane;
+            w[j] = g < n_vec ? load_stream16(vec + g) : nothing;
         }
-        float m = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        m = wave_max(m);
-        float s = 0.f, m_store;
-        if (m * c < kCeil) {                              // (wavefront-uniform)
-            const float mc = fmaxf(m, -0x1p126f) * c;     // a block of nothing but -inf: every weight becomes exp2(-inf) = 0
+        float x[8 * kGroup];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -mc));
+        for (int j = 0; j < kGroup; ++j) {
+            const uint32_t u[4] = {w[j].x, w[j].y, w[j].z, w[j].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[8 * j + 2 * e] = fmaxf(__uint_as_float(u[e] << 16), -INFINITY);
+                x[8 * j + 2 * e + 1] = fmaxf(__uint_as_float(u[e] & 0xffff0000u), -INFINITY);
+            }
+        }
+        float m = x[0];
+#pragma unroll
+        for (int e = 1; e < 8 * kGroup; ++e) m = fmaxf(m, x[e]);
+        m = wave_max(m);
+        float s0 = 0.f, s1 = 0.f, m_store;
+        if (m * c < kCeil) {                              // (wavefront-uniform)
+            const float mc = fmaxf(m, -0x1p126f) * c;     // a slot of nothing but -inf: every weight becomes exp2(-inf) = 0
+#pragma unroll
+            for (int e = 0; e < 8 * kGroup; e += 2) {
+                s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -mc));
+                s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 1], c, -mc));
+            }
             m_store = m * c;
         } else {
             // a +inf logit, or one so large that scaling overflows: go through the clamped values
-            float y[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) y[e] = fminf(x[e] * c, kCeil);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s += __builtin_amdgcn_exp2f(y[e] - kCeil);
-            m_store = kCeil;                              // some token of the block sits at the ceiling
+            for (int e = 0; e < 8 * kGroup; e += 2) {
+                s0 += __builtin_amdgcn_exp2f(fminf(x[e] * c, kCeil) - kCeil);
+                s1 += __builtin_amdgcn_exp2f(fminf(x[e + 1] * c, kCeil) - kCeil);
+            }
+            m_store = kCeil;                              // some token of the slot sits at the ceiling
         }
-        s = wave_sum(s);
-        if (lane == 0) s_stat[1 + blk] = make_float2(m_store, s);
-    };
-    const uint4 nothing = make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);
-    for (int blk0 = wave * 4; blk0 < n_blocks; blk0 += kSampleWaves * 4) {
-        uint4 w[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int g = (blk0 + j) * 64 + lane;
-            w[j] = g < n_vec ? load_stream16(vec + g) : nothing;
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (blk0 + j < n_blocks) block_stat(w[j], blk0 + j);
+        const float s = wave_sum(s0 + s1);
+        if (lane == 0) s_stat[1 + grp] = make_float2(m_store, s);
     }
     __syncthreads();
 
@@ -234,56 +238,62 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
     __syncthreads();
     const float front = s_front;
 
-    // inside the slot: wavefront 0 reads its tokens again, scans their weights in index order
+    // inside the slot: wavefront 0 reads its tokens again and scans their weights in index order,
+    // block by block (a lane's 8 tokens are consecutive, the lanes of a block follow each other)
     if (wave == 0) {
-        float y[8];
-        int first, cnt;                  // this lane's tokens: indices first .. first + cnt - 1
-        if (slot == 0 || slot == n_slots - 1) {
-            const int at = slot == 0 ? 0 : tail_at, n_here = slot == 0 ? head : V - tail_at;
-            first = at + lane;
-            cnt = lane < n_here ? 1 : 0;
-            y[0] = cnt ? scaled((uint32_t)src[first] << 16, c) : -INFINITY;
-#pragma unroll
-            for (int e = 1; e < 8; ++e) y[e] = -INFINITY;
-        } else {
-            const int g = (slot - 1) * 64 + lane;
-            cnt = g < n_vec ? 8 : 0;
-            first = head + g * 8;
-            const uint4 w = cnt ? vec[g] : nothing;
-            unpack8(w, c, y);
-            if (!cnt) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) y[e] = -INFINITY;
-            }
-        }
-        float wgt[8], lane_sum = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            wgt[e] = y[e] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(y[e] - m_row);
-            lane_sum += wgt[e];
-        }
-        float incl_l = lane_sum;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const float t = __shfl_up(incl_l, off);
-            if (lane >= off) incl_l += t;
-        }
-        float cum = front + (incl_l - lane_sum);
+        const bool edge = slot == 0 || slot == n_slots - 1;      // head or tail: up to 7 tokens, one per lane
+        float carry = front;
         int pick = 0x7fffffff, last_pos = -1;
+        for (int j = 0; j < (edge ? 1 : kGroup); ++j) {
+            float y[8];
+            int first, cnt;              // this lane's tokens: indices first .. first + cnt - 1
+            if (edge) {
+                const int at = slot == 0 ? 0 : tail_at, n_here = slot == 0 ? head : V - tail_at;
+                first = at + lane;
+                cnt = lane < n_here ? 1 : 0;
+                y[0] = cnt ? scaled((uint32_t)src[first] << 16, c) : -INFINITY;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            if (e < cnt && wgt[e] > 0.f) {
-                if (pick == 0x7fffffff && thr < cum + wgt[e]) pick = first + e;
-                last_pos = first + e;
+                for (int e = 1; e < 8; ++e) y[e] = -INFINITY;
+            } else {
+                const int g = ((slot - 1) * kGroup + j) * 64 + lane;
+                cnt = g < n_vec ? 8 : 0;
+                first = head + g * 8;
+                const uint4 w = cnt ? vec[g] : nothing;
+                unpack8(w, c, y);
+                if (!cnt) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) y[e] = -INFINITY;
+                }
             }
-            cum += wgt[e];
+            float wgt[8], lane_sum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                wgt[e] = y[e] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(y[e] - m_row);
+                lane_sum += wgt[e];
+            }
+            float incl_l = lane_sum;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const float t = __shfl_up(incl_l, off);
+                if (lane >= off) incl_l += t;
+            }
+            float cum = carry + (incl_l - lane_sum);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (e < cnt && wgt[e] > 0.f) {
+                    if (pick == 0x7fffffff && thr < cum + wgt[e]) pick = first + e;
+                    last_pos = first + e;
+                }
+                cum += wgt[e];
+            }
+            carry += __shfl(incl_l, 63);
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
             pick = min(pick, __shfl_xor(pick, off));
             last_pos = max(last_pos, __shfl_xor(last_pos, off));
         }
-        // the block's own sum, added up in another order, may stop just short of the threshold
+        // the slot's own sum, added up in another order, may stop just short of the threshold
         if (lane == 0) out[row] = pick != 0x7fffffff ? pick : (last_pos >= 0 ? last_pos : 0);
     }
 }
@@ -296,7 +306,7 @@ hipError_t launch_target_sample(const uint16_t *logits, const int32_t *parents, 
     const float c = 1.44269504088896340736f / temperature;
     const char *env = getenv("READER_SAMPLE_THREADS");      // experiments: 512 or 1024
     const int forced = env ? atoi(env) : 0;
-    const int nt = forced ? forced : (long long)B * T <= 768 ? 1024 : 512;
+    const int nt = forced ? forced : (long long)B * T <= 384 ? 1024 : 512;   // (measured: equal at 512 rows, 512 threads ahead beyond)
     if (nt == 1024)
         hipLaunchKernelGGL(target_sample_kernel<1024>, dim3(B * T), dim3(1024), (size_t)n_slots * sizeof(float2), stream,
                            logits, parents, uniforms, out, T, V, c);
