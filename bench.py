@@ -44,13 +44,14 @@ def log(*a):
 class StepRunner:
     """Pre-marshalled C-ABI calls for K steps of one workload (no per-step Python marshalling)."""
 
-    def __init__(self, R, torch, w, n_steps, fused=True):
+    def __init__(self, R, torch, w, n_steps, fused=True, rotate=True, attention_only=False):
         self.R, self.torch, self.w, self.fused = R, torch, w, fused
+        self.attention_only = attention_only
         self.lib = R.load()
         dw = R.to_device(w)
         self.dw = dw
         kv_bytes = 2 * w.k_cache.nbytes
-        self.n_copies = int(max(1, min(32, -(-ROTATE_BYTES // max(kv_bytes, 1)))))
+        self.n_copies = int(max(1, min(32, -(-ROTATE_BYTES // max(kv_bytes, 1))))) if rotate else 1
         self.kc = [dw.k_cache] + [dw.k_cache.clone() for _ in range(self.n_copies - 1)]
         self.vc = [dw.v_cache] + [dw.v_cache.clone() for _ in range(self.n_copies - 1)]
         # compaction grows seq_lens: every step gets its own fresh copy of the lengths
@@ -82,7 +83,9 @@ class StepRunner:
         lib = self.lib
         stream = ctypes.c_void_p(self.torch.cuda.current_stream().cuda_stream)
         for k in range(first, first + count):
-            if self.fused:
+            if self.attention_only:
+                rc = lib.reader_tree_attn(*self.attn_args[k], stream)
+            elif self.fused:
                 rc = lib.reader_verify_step(*self.step_args[k], stream)
             else:
                 rc = lib.reader_tree_attn(*self.attn_args[k], stream)
@@ -147,9 +150,10 @@ def time_workload(R, torch, w, steps, warmup, use_graph=True, fused=True):
     R.reader_profile_enable(True)
     run.run(warmup, steps)
     torch.cuda.synchronize()
-    ms_sum, n = R.reader_profile_collect()
+    each = R.reader_profile_collect_each()
     R.reader_profile_enable(False)
-    kernel_ms = ms_sum / max(n, 1)
+    n = len(each)
+    kernel_ms = float(each.sum()) / max(n, 1)
     alg_bytes = w.algorithmic_bytes()
     flops = w.attention_flops()
     gbs = alg_bytes / (kernel_ms * 1e-3) / 1e9
@@ -161,11 +165,50 @@ def time_workload(R, torch, w, steps, warmup, use_graph=True, fused=True):
     else:
         roof = {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": tflops / MFMA_BF16_PEAK_TFLOPS}
+    import numpy as np
     roof.update({"kernel": "tree_attn_mfma_kernel", "kernel_ms": kernel_ms, "launches_timed": n,
+                 "kernel_ms_median": float(np.median(each)) if n else None,
+                 "kernel_ms_min": float(each.min()) if n else None,
                  "algorithmic_bytes": alg_bytes, "algorithmic_flops": flops, "hbm_gbs": gbs,
                  "hbm_frac": gbs / HBM_PEAK_GBS, "mfma_tflops": tflops, "traffic": measured_traffic(w.name)})
     res["roofline"] = roof
     return res
+
+
+def time_steps_only(R, torch, w, steps, warmup, **runner_kw):
+    """Eager launches of `steps` steps after `warmup`, and the main kernel's own time: for the side figures
+    of the headline preset (attention alone; K/V not rotated)."""
+    total = warmup + steps
+    run = StepRunner(R, torch, w, total, **runner_kw)
+    run.run(0, warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run.run(warmup, steps)
+    torch.cuda.synchronize()
+    step_ms = (time.perf_counter() - t0) / steps * 1e3
+    run.reset()
+    torch.cuda.synchronize()
+    R.reader_profile_enable(True)
+    run.run(warmup, steps)
+    torch.cuda.synchronize()
+    each = R.reader_profile_collect_each()
+    R.reader_profile_enable(False)
+    kernel_ms = float(each.mean()) if len(each) else None
+    res = {"ms_per_step": step_ms, "kernel_ms": kernel_ms, "kv_copies_rotated": run.n_copies}
+    if kernel_ms:
+        res["algorithmic_gbs"] = w.algorithmic_bytes() / (kernel_ms * 1e-3) / 1e9
+    return res
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for ln in f:
+                if ln.startswith("model name"):
+                    return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def measured_traffic(workload_name):
@@ -216,6 +259,7 @@ def cpu_baseline(w, budget_s=12.0):
         if dt >= budget_s or reps >= 50:
             break
     return {"value": w.B * w.T * reps / dt, "unit": "tree tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "cpu_model": cpu_model(), "host_cpus": os.cpu_count(),
             "sample": "%d whole step(s) of %s (attention + acceptance + compaction), %.1f s" % (reps, w.name, dt)}
 
 
@@ -422,6 +466,14 @@ def main():
         "graph_ms_per_step": head.get("graph_ms_per_step"),
         "roofline": head["roofline"],
     }
+    if not args.no_scaled_shapes:
+        # side figures of the headline preset: the attention entry point alone (its two launches), and the
+        # step with K/V not rotated (one copy, small enough for the 256 MB Infinity Cache)
+        side_steps, side_warm = min(args.steps, 200), min(args.warmup, 300)
+        line["attention_only"] = time_steps_only(R, torch, w, side_steps, side_warm, attention_only=True)
+        line["cache_resident"] = time_steps_only(R, torch, w, side_steps, side_warm, rotate=False)
+        line["cache_resident"]["note"] = ("K/V not rotated: a single copy, which fits the 256 MB Infinity Cache where the "
+                                          "rotated copies cannot; the tile copies carry the non-temporal hint")
     if not args.no_cpu_baseline:
         log("timing the CPU oracle")
         line["cpu_baseline"] = cpu_baseline(w)

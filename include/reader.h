@@ -387,9 +387,13 @@ double reader_self_repetition(const int32_t *prompt, int64_t n_prompt, const int
  * *kernel_ms_sum, stores their count in *launches, and forgets them.  The event
  * objects are host-side handles owned by the library; at most 65536 pairs are kept
  * between collects (further launches are simply not timed).  Not thread-safe.
+ * reader_profile_collect_each does the same but hands out every pair's time: ms_each
+ * (host, float [capacity]) receives the first min(count, capacity) times in launch
+ * order, *launches the count; READER_EINVAL for a null pointer or capacity < 0.
  */
 int reader_profile_enable(int32_t on);
 int reader_profile_collect(double *kernel_ms_sum, int32_t *launches);
+int reader_profile_collect_each(float *ms_each, int32_t capacity, int32_t *launches);
 
 #ifdef __cplusplus
 }

@@ -30,7 +30,7 @@ EXPORTS = (
     "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax", "reader_target_sample", "reader_kv_compact_layers",
     "reader_trie_create", "reader_trie_destroy", "reader_trie_nodes", "reader_trie_insert", "reader_trie_search_path",
     "reader_trie_extract_tree", "reader_tree_attach_path", "reader_self_repetition",
-    "reader_profile_enable", "reader_profile_collect",
+    "reader_profile_enable", "reader_profile_collect", "reader_profile_collect_each",
 )
 
 
@@ -117,6 +117,8 @@ def load():
     lib.reader_profile_enable.argtypes = [i32]
     lib.reader_profile_collect.restype = ctypes.c_int
     lib.reader_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    lib.reader_profile_collect_each.restype = ctypes.c_int
+    lib.reader_profile_collect_each.argtypes = [vp, i32, ctypes.POINTER(i32)]
     _lib = lib
     return lib
 
@@ -341,6 +343,16 @@ def reader_self_repetition(prompt, response) -> float:
 
 def reader_profile_enable(on: bool) -> None:
     _check(load().reader_profile_enable(1 if on else 0), "reader_profile_enable")
+
+
+def reader_profile_collect_each(capacity: int = 65536):
+    """Times (ms) of the main attention kernel's launches since the last collect, in launch order (numpy float32)."""
+    import numpy as np
+    out = np.zeros(int(capacity), dtype=np.float32)
+    n = ctypes.c_int32(0)
+    _check(load().reader_profile_collect_each(ctypes.c_void_p(out.ctypes.data), int(capacity), ctypes.byref(n)),
+           "reader_profile_collect_each")
+    return out[:min(int(n.value), int(capacity))].copy()
 
 
 def reader_profile_collect():

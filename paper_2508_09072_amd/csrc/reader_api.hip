@@ -318,6 +318,25 @@ extern "C" int reader_profile_collect(double *kernel_ms_sum, int32_t *launches) 
     return rc;
 }
 
+extern "C" int reader_profile_collect_each(float *ms_each, int32_t capacity, int32_t *launches) {
+    if (!ms_each || !launches || capacity < 0) return READER_EINVAL;
+    int32_t n = 0;
+    int rc = READER_OK;
+    for (size_t i = 0; i < g_profile.used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_profile.pairs[i].second) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_profile.pairs[i].first, g_profile.pairs[i].second) != hipSuccess) {
+            rc = READER_EHIP;
+            continue;
+        }
+        if (n < capacity) ms_each[n] = ms;
+        ++n;
+    }
+    g_profile.used = 0;
+    *launches = n;
+    return rc;
+}
+
 extern "C" int reader_accept_path(const reader_dims *dims, const int32_t *draft_tokens,
                                   const int32_t *target_tokens, const int32_t *parents,
                                   int32_t *accept_len, int32_t *path, int32_t *bonus_token,
