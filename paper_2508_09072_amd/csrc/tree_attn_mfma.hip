@@ -73,7 +73,6 @@ __device__ __attribute__((aligned(256))) const unsigned int kZeroRow[64] = {0u};
 namespace {
 
 constexpr float kLn2 = 0.69314718055994530942f;
-constexpr int kWaves = kThreads / 64;
 // ring depth: 4 tile buffers when dedicated wavefronts copy (up to 128 query rows), else 3
 constexpr int ring_stages(int rb) { return rb == 4 ? 4 : 3; }
 constexpr int kMaxLensInLds = 1024;   // batches up to this size keep the clamped lengths in LDS
