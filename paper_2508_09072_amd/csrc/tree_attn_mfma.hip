@@ -240,7 +240,7 @@ enum {
     kDescTree = 1,        // keys are tree nodes (masked by ancestor sets), else prefix positions
     kDescFresh = 2,       // first tile of a segment: new pair, or start of the workgroup's range
     kDescPairEnd = 4,     // last tile of its pair
-    kDescMasks = 8,       // (on a fresh tile) the segment reaches the pair's tree tiles
+    kDescMasks = 8,       // (on a fresh tile) the segment reaches the pair's tree tiles and needs its sequence's masks built
     kDescPairStart = 16,  // first tile of its pair
     kDescQ = 32,          // not a tile: the query rows of the segment that starts with the next item
 };
@@ -291,7 +291,10 @@ __device__ inline void write_tile_desc(const AttnParams &p, const int32_t *table
     if (idx + 1 == n_units) flags |= kDescPairEnd;
     if (idx == 0 || i_tile == 0) {
         flags |= kDescFresh;
-        if (idx + (n_tiles - i_tile) > n_pre) flags |= kDescMasks;
+        // The ancestor masks belong to the sequence, not to the kv head: a segment that follows
+        // another one of the same sequence in this range finds them in place (the one before it
+        // ran to the end of its pair, through the tree tiles).
+        if (idx + (n_tiles - i_tile) > n_pre && (i_tile == 0 || hkv == 0)) flags |= kDescMasks;
     }
     int4 *dst = reinterpret_cast<int4 *>(slot);
     dst[0] = make_int4(blk[0], blk[1], blk[2], blk[3]);
