@@ -38,6 +38,7 @@ struct AttnParams {
     int32_t pair_cost;       // what the start of a pair costs a workgroup, in tiles, when the ranges are cut
     int32_t axis32;          // 1: every position of the cost axis times n_ranges fits in an int
     int32_t ranges_shift;    // log2(n_ranges) when it is a power of two (the even cut is then a shift), else -1
+    int32_t merge_groups;    // thread groups that share a query row's partial records in the merge: 1, or 4 when pairs are cut into many parts
     int32_t tree_in_cache;   // 1: k_tree / v_tree are null, tree node n of sequence b sits at cache position L_b + n
     int32_t *status;
     int32_t B, T, Hq, Hkv, D, G, M;       // G = Hq/Hkv, M = T*G query rows per (sequence, kv head)

@@ -198,6 +198,8 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
             if (p.n_ranges == (1 << sh)) p.ranges_shift = sh;
     }
     p.num_pages = dims->num_pages;
+    // few pairs, many ranges: a pair is cut into eight parts or more on average, the merge fetches them four abreast
+    p.merge_groups = (long long)dims->B * dims->Hkv * 8 <= p.n_ranges ? 4 : 1;
     p.tree_in_cache = tree_in_cache ? 1 : 0;
     float scale = dims->sm_scale > 0.f ? dims->sm_scale : 1.0f / sqrtf((float)dims->D);
     p.scale_log2 = scale * 1.44269504088896340736f;

@@ -1182,36 +1182,41 @@ __device__ inline void merge_body(const AttnParams &p, int pair, int block_y) {
     const int b = pair / p.Hkv, hkv = pair - b * p.Hkv;
     const int2 info = reinterpret_cast<const int2 *>(p.pair_info)[pair];
     const int w_first = info.x, w_last = info.y;
-    if (w_first == w_last) return;   // finished in place by one workgroup
+    if (w_first == w_last) return;   // finished in place by one workgroup (the whole workgroup leaves)
 
+    // p.merge_groups (1 or 4) thread groups share a query row's records: with few pairs and many
+    // ranges a pair is cut into dozens of parts, and the groups fetch theirs side by side.
     constexpr int kC = D / 8;                   // chunks (threads) per row
-    constexpr int kRowsPerBlock = 256 / kC;
-    const int tid = threadIdx.x;
-    const int blocks_per_chunk = p.rows_per_wg / kRowsPerBlock;
+    const int groups = p.merge_groups, group_threads = 256 / groups;
+    const int rows_per_block = group_threads / kC;
+    const int tid = threadIdx.x, grp = tid / group_threads, t2 = tid - grp * group_threads;
+    const int blocks_per_chunk = p.rows_per_wg / rows_per_block;
     const int row_chunk = block_y / blocks_per_chunk;
-    const int row_local = (block_y - row_chunk * blocks_per_chunk) * kRowsPerBlock + tid / kC, c = tid % kC;
+    const int row_local = (block_y - row_chunk * blocks_per_chunk) * rows_per_block + t2 / kC, c = t2 % kC;
     const int m_row = row_chunk * p.rows_per_wg + row_local;
-    if (m_row >= p.M) return;
-    const int node = m_row / p.G, group = m_row - node * p.G;
+    const bool live = m_row < p.M;
+    const int node = live ? m_row / p.G : 0, group = live ? m_row - node * p.G : 0;
     const size_t rows = p.rows_per_wg;
     const size_t rec_floats = attn_slot_floats(D, p.rows_per_wg);
+    // this group's share of the parts, in range order
+    const int n_parts = w_last - w_first + 1, share = (n_parts + groups - 1) / groups;
+    const int my_first = w_first + grp * share, my_last = min(w_last, my_first + share - 1);
 
     // online merge: every part's loads are independent of the other parts' values
     float m_all = -INFINITY, l_all = 0.f;
     float acc[8];
 #pragma unroll
     for (int d = 0; d < 8; ++d) acc[d] = 0.f;
-    // Records are fetched eight at a time (all their loads in flight together: a pair of a single
-    // long sequence is cut into dozens of parts) and folded in in range order.
+    // Records are fetched eight at a time (all their loads in flight together) and folded in in range order.
     constexpr int kBatch = 8;
-    for (int w0 = w_first; w0 <= w_last; w0 += kBatch) {
+    for (int w0 = my_first; w0 <= my_last && live; w0 += kBatch) {
         float mw[kBatch], lw[kBatch];
         uint4 v[kBatch];
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const int w = w0 + j;
             mw[j] = -INFINITY;
-            if (w <= w_last) {
+            if (w <= my_last) {
                 // A range that holds no tile (more workgroups than tiles) wrote no record: its slot
                 // holds stale bytes.  The slot is read all the same, next to the range's tile count and
                 // not behind it (one round trip less), and dropped afterwards.
@@ -1240,6 +1245,30 @@ __device__ inline void merge_body(const AttnParams &p, int pair, int block_y) {
             m_all = m_new;
         }
     }
+    if (groups > 1) {
+        // groups 1.. leave their state in LDS; group 0 folds them in, in range order
+        __shared__ float s_state[3][64][10];
+        if (grp > 0) {
+            float *st = s_state[grp - 1][t2];
+            st[0] = m_all; st[1] = l_all;
+#pragma unroll
+            for (int d = 0; d < 8; ++d) st[2 + d] = acc[d];
+        }
+        __syncthreads();
+        if (grp > 0) return;
+        for (int g = 0; g < groups - 1; ++g) {
+            const float *st = s_state[g][t2];
+            const float m_g = st[0];
+            if (m_g == -INFINITY) continue;
+            const float m_new = fmaxf(m_all, m_g);
+            const float fa = __builtin_amdgcn_exp2f(m_all - m_new), fb = __builtin_amdgcn_exp2f(m_g - m_new);
+#pragma unroll
+            for (int d = 0; d < 8; ++d) acc[d] = acc[d] * fa + st[2 + d] * fb;
+            l_all = l_all * fa + st[1] * fb;
+            m_all = m_new;
+        }
+    }
+    if (!live) return;
     // l_all > 0: every query row sees at least its own tree node
     const float inv = 1.f / l_all;
     uint16_t *orow = p.out + (((size_t)b * p.T + node) * p.Hq + hkv * p.G + group) * D + c * 8;
@@ -1315,7 +1344,7 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
                            main_lds, stream, p, p.page_table, p.seq_lens);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return note_hip_error("launch tree_attn_mfma_kernel", e);
-    const int merge_y = p.n_row_chunks * (p.rows_per_wg / (256 / (D / 8)));
+    const int merge_y = p.n_row_chunks * (p.rows_per_wg / (256 / p.merge_groups / (D / 8)));
     if (ap && cp) {
         const int n_merge = p.B * p.Hkv * merge_y;
         hipLaunchKernelGGL(verify_tail_kernel<D>, dim3(p.B + n_merge), dim3(256), 0, stream, p, *ap, *cp, merge_y);
