@@ -529,6 +529,38 @@ def test_two_host_threads_on_their_own_streams(R, oracle_mod):
             assert np.array_equal(cache_bits(getattr(results[k], name)), cache_bits(getattr(single[k], name))), (k, name)
 
 
+def test_status_word_is_optional(R, oracle_mod):
+    # every device entry point takes status = NULL: same results, and a malformed input is still skipped, not followed
+    import torch
+    w = W.make_custom("nostatus", B=3, Hq=8, Hkv=2, D=128, T=12, seq_lens=[40, 90, 300], tree="uniform", depth=4, seed=451)
+    ref = run_step(R, w)
+    dw = R.to_device(w)
+    R.reader_verify_step(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table, dw.seq_lens,
+                         dw.parents, dw.draft_tokens, dw.target_tokens, dw.out, dw.lse, dw.accept_len, dw.path,
+                         dw.bonus, dw.max_seq_len, dw.workspace, None)
+    torch.cuda.synchronize()
+    for name in ("out", "accept_len", "path", "bonus", "seq_lens"):
+        assert torch.equal(getattr(dw, name), getattr(ref, name)), name
+    # a page id outside the pool and a parent after its child, no status word: the other sequences come out right
+    w.page_table[1, 2] = w.num_pages + 5
+    w.parents[2, 5] = 7
+    good, _ = oracle_mod.tree_attn(w.q[:1], w.k_tree[:1], w.v_tree[:1], w.k_cache, w.v_cache, w.page_table[:1],
+                                   w.seq_lens[:1], w.parents[:1])
+    for variant in (0, 1):
+        dw = R.to_device(w)
+        dw.dims.variant = variant
+        R.reader_tree_attn(dw.dims, dw.q, dw.k_tree, dw.v_tree, dw.k_cache, dw.v_cache, dw.page_table, dw.seq_lens,
+                           dw.parents, dw.out, None, dw.max_seq_len, dw.workspace, None)
+        torch.cuda.synchronize()
+        assert_close(bf16_to_np(dw.out)[:1], good, what="sequence next to the bad ones, no status word")
+    dw = R.to_device(w)
+    R.reader_accept_path(dw.dims, dw.draft_tokens, dw.target_tokens, dw.parents, dw.accept_len, dw.path, dw.bonus, None)
+    R.reader_kv_compact(dw.dims, dw.k_tree, dw.v_tree, dw.path, dw.accept_len, dw.k_cache, dw.v_cache, dw.page_table,
+                        dw.seq_lens, None)
+    torch.cuda.synchronize()
+    assert int(dw.seq_lens[1].item()) == int(w.seq_lens[1]) or int(dw.seq_lens[1].item()) == int(w.seq_lens[1]) + int(dw.accept_len[1].item()) + 1
+
+
 def test_verify_step_rejects_bad_arguments(R):
     import torch
     w = W.make_config(0)
