@@ -29,7 +29,10 @@
  *  - Data-dependent problems that only the device can see (a malformed tree, a
  *    page id outside the pool, an accepted length that does not fit) never fault:
  *    the kernel skips the offending item and ORs a READER_STATUS_* bit into the
- *    optional device word `status`.
+ *    optional device word `status`.  In the attention a bad link of a tree counts as
+ *    a root link and the cached keys behind a bad page id are left out of the sums;
+ *    tree rows that live in the cache (in-cache layout) behind a bad page id leave
+ *    the outputs of their sequence unspecified (finite or NaN, never a fault).
  *  - Tree convention: node 0 is the root = the last committed token (it comes
  *    from the base model, acceptance rate 1, Section 3.3); parents[b][0] = -1 and
  *    0 <= parents[b][i] < i.  Trees may differ between sequences; the paper's
@@ -42,8 +45,10 @@
  *    outputs and status word; calls that share a workspace or write the same cache
  *    pages or lengths must be ordered by the caller (one stream, or events).
  *    reader_last_error_detail and the reader_profile_* hooks share one process-wide
- *    buffer and are meant for one thread.  The READER_ATTN_* / READER_*_THREADS
- *    environment variables the host code reads are for experiments and tests only.
+ *    buffer and are meant for one thread.  The library reads no environment variable.
+ *  - Size limits (a call beyond them returns READER_EUNSUPPORTED, nothing is enqueued):
+ *    T <= READER_MAX_T, D in {64, 128}, page_size == READER_PAGE_SIZE, Hq / Hkv <= 16,
+ *    B <= READER_MAX_B, num_pages * Hkv < 2^31, B * max_pages_per_seq < 2^31.
  */
 #ifndef READER_H
 #define READER_H
@@ -71,12 +76,13 @@ enum {
 
 enum {
     READER_MAX_T = 128,  /* draft-tree nodes per sequence */
-    READER_PAGE_SIZE = 16
+    READER_PAGE_SIZE = 16,
+    READER_MAX_B = 4096  /* sequences per call (what the in-kernel prefix scan over the lengths is sized for) */
 };
 
 /* Problem sizes; plain data, passed by const pointer (host memory). */
 typedef struct reader_dims {
-    int32_t B;                 /* sequences in the batch, >= 0 (0 = nothing to do) */
+    int32_t B;                 /* sequences in the batch, 0..READER_MAX_B (0 = nothing to do) */
     int32_t T;                 /* draft-tree nodes per sequence, 1..READER_MAX_T */
     int32_t Hq;                /* query heads */
     int32_t Hkv;               /* kv heads, Hq % Hkv == 0, Hq / Hkv <= 16 */
@@ -394,6 +400,30 @@ double reader_self_repetition(const int32_t *prompt, int64_t n_prompt, const int
 int reader_profile_enable(int32_t on);
 int reader_profile_collect(double *kernel_ms_sum, int32_t *launches);
 int reader_profile_collect_each(float *ms_each, int32_t capacity, int32_t *launches);
+
+/*
+ * Launch-planner overrides for tests and experiments (not operations of the method; a caller
+ * never needs them).  The planner of reader_tree_attn / reader_verify_step picks the number of
+ * query rows per workgroup, the number of key ranges, the cost it books for the start of a
+ * (sequence, kv head) pair when it cuts the ranges, and 32- or 64-bit arithmetic for the cut,
+ * all from the dims alone.  An override replaces one of these choices for every later call of
+ * the process (reader_workspace_bytes included, so sizes stay consistent) until it is cleared
+ * with a negative value.  Every choice gives the same results up to rounding; only the speed
+ * and the code path differ.  Stored atomically: a call sees the old or the new value.
+ *   READER_TUNE_ATTN_ROWS       128 or 256 query rows per workgroup (other values: planner decides)
+ *   READER_TUNE_ATTN_RANGES     >= 1 key ranges asked for (capped at the number of compute units)
+ *   READER_TUNE_ATTN_PAIR_COST  0..64 tile times booked per pair start
+ *   READER_TUNE_ATTN_AXIS64     1 = cut the ranges in 64-bit arithmetic even where 32 bits suffice
+ * Returns READER_OK, or READER_EINVAL for an unknown `which`.
+ */
+enum {
+    READER_TUNE_ATTN_ROWS = 0,
+    READER_TUNE_ATTN_RANGES = 1,
+    READER_TUNE_ATTN_PAIR_COST = 2,
+    READER_TUNE_ATTN_AXIS64 = 3,
+    READER_TUNE_COUNT_ = 4
+};
+int reader_tuning_override(int32_t which, int32_t value);
 
 #ifdef __cplusplus
 }

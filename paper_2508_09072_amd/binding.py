@@ -23,6 +23,7 @@ READER_EHIP = -4
 STATUS_BAD_TREE = 1
 STATUS_BAD_PAGE = 2
 STATUS_BAD_PATH = 4
+TUNE_ATTN_ROWS, TUNE_ATTN_RANGES, TUNE_ATTN_PAIR_COST, TUNE_ATTN_AXIS64 = 0, 1, 2, 3
 
 EXPORTS = (
     "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",
@@ -30,7 +31,7 @@ EXPORTS = (
     "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax", "reader_target_sample", "reader_kv_compact_layers",
     "reader_trie_create", "reader_trie_destroy", "reader_trie_nodes", "reader_trie_insert", "reader_trie_search_path",
     "reader_trie_extract_tree", "reader_tree_attach_path", "reader_self_repetition",
-    "reader_profile_enable", "reader_profile_collect", "reader_profile_collect_each",
+    "reader_profile_enable", "reader_profile_collect", "reader_profile_collect_each", "reader_tuning_override",
 )
 
 
@@ -119,6 +120,8 @@ def load():
     lib.reader_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.reader_profile_collect_each.restype = ctypes.c_int
     lib.reader_profile_collect_each.argtypes = [vp, i32, ctypes.POINTER(i32)]
+    lib.reader_tuning_override.restype = ctypes.c_int
+    lib.reader_tuning_override.argtypes = [i32, i32]
     _lib = lib
     return lib
 
@@ -339,6 +342,11 @@ def reader_self_repetition(prompt, response) -> float:
     if r < 0:
         raise ValueError("reader_self_repetition: bad argument")
     return float(r)
+
+
+def reader_tuning_override(which: int, value: int) -> None:
+    """Planner override for tests and experiments (a negative value clears it)."""
+    _check(load().reader_tuning_override(int(which), int(value)), "reader_tuning_override")
 
 
 def reader_profile_enable(on: bool) -> None:

@@ -19,7 +19,7 @@ constexpr int kNumXCD = 8;
 
 constexpr int kTile = 64;          // keys per tile of the attention main loop
 constexpr int kThreads = 512;      // 8 wavefronts per attention workgroup, one workgroup per compute unit
-constexpr int kMaxBatchScan = 4096;  // sequences the in-kernel prefix scan is sized for
+constexpr int kMaxBatchScan = READER_MAX_B;  // sequences the in-kernel prefix scan is sized for
 
 // Query rows (tree node, grouped head) one attention workgroup carries: 4 row blocks of 32
 // with the tile's keys split between two wave groups, or 8 row blocks when T*G > 128.

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <atomic>
 #include <utility>
 #include <vector>
 
@@ -12,6 +13,10 @@
 namespace reader {
 
 static char g_error_detail[256] = "";
+
+// Planner overrides set through reader_tuning_override (tests, experiments); -1 = the planner decides.
+static std::atomic<int32_t> g_tuning[READER_TUNE_COUNT_] = {{-1}, {-1}, {-1}, {-1}};
+static int tuning(int which) { return g_tuning[which].load(std::memory_order_relaxed); }
 
 // The runtime keeps the last error of the calling thread until somebody reads it, whoever caused
 // it: an error another library left behind must not be taken for a failed launch of ours.
@@ -30,7 +35,8 @@ static bool dims_ok(const reader_dims *d, int *err) {
         return false;
     }
     if (d->T > READER_MAX_T || (d->D != 64 && d->D != 128) || d->page_size != READER_PAGE_SIZE ||
-        d->Hq / d->Hkv > 16 || d->B > kMaxBatchScan || d->num_pages * d->Hkv > 0x7fffffffLL) {
+        d->Hq / d->Hkv > 16 || d->B > kMaxBatchScan || d->num_pages * d->Hkv > 0x7fffffffLL ||
+        (long long)d->B * d->max_pages_per_seq > 0x7fffffffLL) {
         *err = READER_EUNSUPPORTED;
         return false;
     }
@@ -42,10 +48,9 @@ static bool dims_ok(const reader_dims *d, int *err) {
 // choose.  Beyond that 256-row workgroups do more matrix work per byte they fetch and win as
 // soon as a workgroup has a few tiles to stream; a small problem (a single prompt of a few
 // thousand tokens) is over sooner when it is cut into more, lighter workgroups (measured
-// crossover: about 1100 workgroup-tiles).  READER_ATTN_ROWS (experiments) forces one of them.
+// crossover: about 1100 workgroup-tiles).
 int attn_rows_per_wg(const reader_dims &d, int32_t max_seq_len) {
-    const char *env = getenv("READER_ATTN_ROWS");
-    const int forced = env ? atoi(env) : 0;
+    const int forced = tuning(READER_TUNE_ATTN_ROWS);
     if (forced == 128 || forced == 256) return forced;
     const int M = d.T * (d.Hq / d.Hkv);
     if (M <= 128) return 128;
@@ -61,9 +66,7 @@ int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len) {
     // at least two tiles (what a workgroup spends before its first tile arrives is worth
     // several tiles, so tiny problems want many short ranges; measured), and when the rows
     // are cut into 128-row chunks (small problems only) all workgroups fit the chip at once.
-    // READER_ATTN_RANGES (tests, experiments): ask for this many ranges instead; read at every call
-    const char *env = getenv("READER_ATTN_RANGES");
-    const int forced = env ? atoi(env) : 0;
+    const int forced = tuning(READER_TUNE_ATTN_RANGES);
     long long tiles_per_pair = (max_seq_len + kTile - 1) / kTile + (d.T + kTile - 1) / kTile;
     long long units = (long long)d.B * d.Hkv * tiles_per_pair;
     long long n = forced > 0 ? forced : units / 2;
@@ -128,6 +131,12 @@ extern "C" const char *reader_strerror(int code) {
 
 extern "C" const char *reader_last_error_detail(void) { return g_error_detail; }
 
+extern "C" int reader_tuning_override(int32_t which, int32_t value) {
+    if (which < 0 || which >= READER_TUNE_COUNT_) return READER_EINVAL;
+    g_tuning[which].store(value < 0 ? -1 : value, std::memory_order_relaxed);
+    return READER_OK;
+}
+
 extern "C" int reader_validate_tree(const int32_t *parents_host, int32_t B, int32_t T) {
     if (!parents_host || B < 0 || T < 1) return READER_EINVAL;
     for (int32_t b = 0; b < B; ++b) {
@@ -185,14 +194,12 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     {
         // A pair that starts inside a range costs its workgroup extra (query rows to fetch, a
         // segment to finish): about four tiles' time when dedicated wavefronts copy, one otherwise.
-        // READER_ATTN_PAIR_COST (experiments) overrides it.
-        const char *env = getenv("READER_ATTN_PAIR_COST");
-        p.pair_cost = env ? atoi(env) : (p.rows_per_wg == 128 ? 4 : 1);
-        if (p.pair_cost < 0 || p.pair_cost > 64) p.pair_cost = 0;
+        const int forced_cost = tuning(READER_TUNE_ATTN_PAIR_COST);
+        p.pair_cost = forced_cost >= 0 && forced_cost <= 64 ? forced_cost : (p.rows_per_wg == 128 ? 4 : 1);
         // the kernel cuts the ranges with 32-bit arithmetic when nothing on the cost axis can overflow it
         const long long axis_max = (long long)p.Hkv * p.B * ((max_seq_len + kTile - 1) / kTile + p.n_tree_tiles + p.pair_cost);
         p.axis32 = (axis_max + 2) * (p.n_ranges + 1) < 0x7fffffffLL ? 1 : 0;
-        if (getenv("READER_ATTN_AXIS64")) p.axis32 = 0;   // tests: force the 64-bit path
+        if (tuning(READER_TUNE_ATTN_AXIS64) == 1) p.axis32 = 0;   // tests: force the 64-bit path
         p.ranges_shift = -1;
         for (int sh = 0; sh < 16; ++sh)
             if (p.n_ranges == (1 << sh)) p.ranges_shift = sh;

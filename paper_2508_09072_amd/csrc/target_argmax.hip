@@ -78,12 +78,9 @@ __global__ __launch_bounds__(NT) void target_argmax_kernel(const uint16_t *__res
 
 hipError_t launch_target_argmax(const uint16_t *logits, int32_t *out, int rows, int V, hipStream_t stream) {
     // threads per row so that the rows of the launch fill the chip's 256 x 2048 thread slots
-    const char *env = getenv("READER_ARGMAX_THREADS");      // experiments: 256, 512 or 1024
-    const int forced = env ? atoi(env) : 0;
-    const int nt = forced ? forced : rows <= 768 ? 1024 : 512;
-    if (nt == 1024) hipLaunchKernelGGL((target_argmax_kernel<1024, 8>), dim3(rows), dim3(1024), 0, stream, logits, out, V);
-    else if (nt == 512) hipLaunchKernelGGL((target_argmax_kernel<512, 8>), dim3(rows), dim3(512), 0, stream, logits, out, V);
-    else hipLaunchKernelGGL((target_argmax_kernel<256, 8>), dim3(rows), dim3(256), 0, stream, logits, out, V);
+    // (measured: 1024 threads per row are ahead up to 768 rows, 512 beyond)
+    if (rows <= 768) hipLaunchKernelGGL((target_argmax_kernel<1024, 8>), dim3(rows), dim3(1024), 0, stream, logits, out, V);
+    else hipLaunchKernelGGL((target_argmax_kernel<512, 8>), dim3(rows), dim3(512), 0, stream, logits, out, V);
     return note_hip_error("launch target_argmax_kernel", hipGetLastError());
 }
 

@@ -302,11 +302,11 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
 
 hipError_t launch_target_sample(const uint16_t *logits, const int32_t *parents, const float *uniforms, int32_t *out,
                                 int B, int T, int V, float temperature, hipStream_t stream) {
-    const int n_slots = (V / 8 + 63) / 64 + 3;
+    // one (maximum, sum) slot per kGroup blocks of 512 tokens, plus the unaligned head and tail of the row
+    // (the kernel computes the same number from the row's alignment; this is its upper bound)
+    const int n_slots = ((V / 8 + 63) / 64 + kGroup - 1) / kGroup + 2;
     const float c = 1.44269504088896340736f / temperature;
-    const char *env = getenv("READER_SAMPLE_THREADS");      // experiments: 512 or 1024
-    const int forced = env ? atoi(env) : 0;
-    const int nt = forced ? forced : (long long)B * T <= 384 ? 1024 : 512;   // (measured: equal at 512 rows, 512 threads ahead beyond)
+    const int nt = (long long)B * T <= 384 ? 1024 : 512;   // (measured: equal at 512 rows, 512 threads ahead beyond)
     if (nt == 1024)
         hipLaunchKernelGGL(target_sample_kernel<1024>, dim3(B * T), dim3(1024), (size_t)n_slots * sizeof(float2), stream,
                            logits, parents, uniforms, out, T, V, c);

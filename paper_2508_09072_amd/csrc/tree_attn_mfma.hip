@@ -232,7 +232,7 @@ struct TileDesc {
     int blk[4];    // prefix tile: page * Hkv + kv head of each 16-key quarter, -1 where the quarter
                    // reads as zeros; tree tile: all four = ((b * T + first node) * Hkv + kv head)
     int n_valid;   // rows of the tile that exist (1..64)
-    int flags;     // kDesc* bits, number of the tree tile from bit 8 up
+    int flags;     // kDesc* bits; from bit 8 up the number of the tree tile, or (kDescHoles) which quarters are missing
     int b;         // sequence
     int hkv;       // kv head
 };
@@ -243,6 +243,7 @@ enum {
     kDescMasks = 8,       // (on a fresh tile) the segment reaches the pair's tree tiles and needs its sequence's masks built
     kDescPairStart = 16,  // first tile of its pair
     kDescQ = 32,          // not a tile: the query rows of the segment that starts with the next item
+    kDescHoles = 64,      // prefix tile with quarters behind a page id outside the pool: their keys are skipped
 };
 constexpr int kDescSlots = 256;
 
@@ -272,14 +273,16 @@ __device__ inline void write_tile_desc(const AttnParams &p, const int32_t *table
 #pragma unroll
             for (int j = 0; j < 4; ++j) page[j] = j <= j_last ? row[j] : -1;
         }
+        int holes = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             blk[j] = -1;
             if (j <= j_last) {
                 if (page[j] >= 0 && page[j] < p.num_pages) blk[j] = page[j] * p.Hkv + hkv;
-                else bad |= READER_STATUS_BAD_PAGE;
+                else { bad |= READER_STATUS_BAD_PAGE; holes |= 1 << j; }
             }
         }
+        if (holes) flags |= kDescHoles | (holes << 8);
     } else {
         const int tt = idx - n_pre;
         n_valid = min(kTile, p.T - tt * kTile);
@@ -382,8 +385,9 @@ __device__ inline CopyLane<D, CW> make_copy_lane(const AttnParams &p, int cw, in
 // What one copying wavefront needs for its rows of a tile: wave-uniform base addresses and
 // which kind of source it is.  It issues exactly 2 * kCopies copy instructions per tile,
 // whatever the tile looks like: rows that do not exist (past the sequence end, past the last
-// tree node, behind an invalid page id) are copied from a block of zeros, so a missing K row
-// scores 0 (and is masked later) and a missing V row contributes nothing.
+// tree node, behind an invalid page id) are copied from a block of zeros; their scores are masked
+// before the softmax (rows past the end by the row count, quarters behind a bad page by the
+// tile's kDescHoles bits) and the zero V rows keep the masked products finite.
 struct CopyPlan {
     const char *kb, *vb;   // base of this wavefront's (page, head) block, or of the tree slab
     int n_valid;           // rows of the tile that exist
@@ -409,6 +413,9 @@ __device__ inline CopyPlan plan_copy(const AttnParams &p, int blk, int n_valid, 
         cp.kb = reinterpret_cast<const char *>(p.k_tree) + origin;
         cp.vb = reinterpret_cast<const char *>(p.v_tree) + origin;
         cp.whole = false;
+        // without tree tensors (rows in the cache) the caller gathers through the page table instead;
+        // should this plan be used all the same, every row reads as zeros and nothing is dereferenced
+        if (p.tree_in_cache) cp.page_ok = false;
     }
     return cp;
 }
@@ -518,8 +525,9 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     // A small page table is fetched whole into the last ring stage (idle until the main loop
     // starts) while the sequence lengths are on their way, so that the tile list can be written
     // without a second trip to memory.
-    const int table_ints = p.B * p.max_pages;
-    const bool table_in_lds = (size_t)table_ints * 4 + 256 <= (size_t)G::kStageBytes;   // copies come in 256-byte pieces
+    const long long table_ints_all = (long long)p.B * p.max_pages;
+    const bool table_in_lds = table_ints_all * 4 + 256 <= (long long)G::kStageBytes;   // copies come in 256-byte pieces
+    const int table_ints = table_in_lds ? (int)table_ints_all : 0;
     const int32_t *table = page_table;
     if (table_in_lds) {
         const unsigned table_lds = ring_lds + (kS - 1) * G::kStageBytes;
@@ -812,6 +820,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     f32x16 o[G::kOBlocks];
     float m_run = -INFINITY, l_run = 0.f;
     bool seg_from_pair_start = false;
+    bool ref_ok = false;   // every row of this wavefront has a finite running reference (wave-uniform)
     const float c2 = p.scale_log2;
 
     uint32_t pk[2][8];     // softmax weights of the current tile, bf16 pairs, in B-operand order
@@ -893,7 +902,8 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         // row maximum first; only if some weight comes out huge (a score far above the
         // reference) is the tile redone the careful way.  bf16 and fp32 share the exponent
         // range, so large weights lose nothing.
-        bool careful = is_tree || n_valid < kTile || (flags & kDescFresh);
+        const int holes = (flags & kDescHoles) ? (flags >> 8) & 15 : 0;   // quarters of a prefix tile to skip
+        bool careful = is_tree || n_valid < kTile || (flags & (kDescFresh | kDescHoles)) || !ref_ok;
         if (!careful) {
             const float lsum = weights();
             if (__any(!(lsum < 0x1p40f))) careful = true;
@@ -913,13 +923,14 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                         if (!((bits >> r) & 1u)) s[kb][i] = -INFINITY;
                     }
                 }
-            } else if (n_valid < kTile) {
+            } else if (n_valid < kTile || holes) {
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int key = kb * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
-                        if (key >= n_valid) s[kb][i] = -INFINITY;
+                        const int quarter = kb * 2 + (i >> 3);     // = key / 16
+                        if (key >= n_valid || ((holes >> quarter) & 1)) s[kb][i] = -INFINITY;
                     }
             }
             // ---- online softmax along the keys (all values of a lane share one query row) ----
@@ -945,6 +956,8 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                     for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
             }
             l_run += weights();
+            // (a row has no reference yet only if every key it met so far was skipped: quarters behind bad page ids)
+            ref_ok = !__any(m_run == -INFINITY);
         }
         between(2);
 
@@ -971,6 +984,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
 
     auto reset_state = [&](int flags) {
         seg_from_pair_start = (flags & kDescPairStart) != 0;
+        ref_ok = false;
         m_run = -INFINITY;
         l_run = 0.f;
 #pragma unroll
@@ -1148,12 +1162,19 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             // a copy instruction while the memory pipeline is full.  The two wavefronts that share a
             // SIMD (w and w + 4) are kept out of step by it: one copies before it computes, the other
             // after, so that one's matrix work tends to run under the other's vector work.
+            // (a tree tile whose rows live in the cache has no tree tensor to copy from: it is
+            // gathered row by row through the page table, by the same code as in the prologue)
+            const bool gather_next = p.tree_in_cache && (c_flags & kDescTree);
             CopyPlan cp;
-            if (copy_next) cp = plan_copy<D, CW>(p, c_blk, c_valid, c_flags, cw);
+            if (copy_next && !gather_next) cp = plan_copy<D, CW>(p, c_blk, c_valid, c_flags, cw);
             auto copy_all = [&]() {
                 if (copy_next) {
+                    if (gather_next) {
+                        issue_tile(cl, c_blk, c_valid, c_flags, next_stage);
+                    } else {
 #pragma unroll
-                    for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D, CW>(cp, cl, next_stage, cw, j);
+                        for (int j = 0; j < kCopiesPerTile; ++j) emit_copy<D, CW>(cp, cl, next_stage, cw, j);
+                    }
                 }
             };
             if (wave_active) {

@@ -50,7 +50,12 @@ extern "C" reader_trie *reader_trie_create(int32_t max_depth) {
     reader_trie *t = new (std::nothrow) reader_trie;
     if (!t) return nullptr;
     t->max_depth = max_depth;
-    t->nodes.push_back({-1, 0, {}});
+    try {
+        t->nodes.push_back({-1, 0, {}});
+    } catch (const std::bad_alloc &) {
+        delete t;
+        return nullptr;
+    }
     return t;
 }
 
@@ -86,16 +91,20 @@ extern "C" int reader_trie_insert(reader_trie *t, const int32_t *tokens, int64_t
 extern "C" int32_t reader_trie_search_path(const reader_trie *t, const int32_t *suffix, int32_t n_suffix, int32_t depth,
                                            int32_t *path_tokens) {
     if (!t || n_suffix < 0 || depth < 0 || (n_suffix > 0 && !suffix) || (depth > 0 && !path_tokens)) return -1;
-    std::vector<int32_t> ctx(suffix, suffix + n_suffix);
-    int32_t k = 0;
-    while (k < depth) {
-        const int32_t at = t->descend(ctx.data(), (int32_t)ctx.size());
-        if (at < 0) break;
-        const int32_t best = t->ranked_children(at)[0];
-        path_tokens[k++] = t->nodes[best].token;
-        ctx.push_back(t->nodes[best].token);
+    try {   // (no exception may cross the C boundary: running out of memory is reported as a bad call)
+        std::vector<int32_t> ctx(suffix, suffix + n_suffix);
+        int32_t k = 0;
+        while (k < depth) {
+            const int32_t at = t->descend(ctx.data(), (int32_t)ctx.size());
+            if (at < 0) break;
+            const int32_t best = t->ranked_children(at)[0];
+            path_tokens[k++] = t->nodes[best].token;
+            ctx.push_back(t->nodes[best].token);
+        }
+        return k;
+    } catch (const std::bad_alloc &) {
+        return -1;
     }
-    return k;
 }
 
 extern "C" int32_t reader_trie_extract_tree(const reader_trie *t, const int32_t *suffix, int32_t n_suffix,
@@ -108,21 +117,25 @@ extern "C" int32_t reader_trie_extract_tree(const reader_trie *t, const int32_t 
     if (start < 0) return used;
     // depth-first, most frequent continuation first, within the depth and the node budget
     struct Frame { int32_t trie_node, tree_node, depth; };
-    std::vector<Frame> stack;
-    stack.push_back({start, 0, 0});
-    while (!stack.empty() && used < budget) {
-        const Frame f = stack.back();
-        stack.pop_back();
-        int32_t me = f.tree_node;
-        if (f.depth > 0) {                  // (the start node itself is the root, already numbered)
-            me = used++;
-            tokens[me] = t->nodes[f.trie_node].token;
-            parents[me] = f.tree_node;
+    try {
+        std::vector<Frame> stack;
+        stack.push_back({start, 0, 0});
+        while (!stack.empty() && used < budget) {
+            const Frame f = stack.back();
+            stack.pop_back();
+            int32_t me = f.tree_node;
+            if (f.depth > 0) {                  // (the start node itself is the root, already numbered)
+                me = used++;
+                tokens[me] = t->nodes[f.trie_node].token;
+                parents[me] = f.tree_node;
+            }
+            if (f.depth < max_depth) {
+                const std::vector<int32_t> c = t->ranked_children(f.trie_node);
+                for (auto it = c.rbegin(); it != c.rend(); ++it) stack.push_back({*it, me, f.depth + 1});   // best on top
+            }
         }
-        if (f.depth < max_depth) {
-            const std::vector<int32_t> c = t->ranked_children(f.trie_node);
-            for (auto it = c.rbegin(); it != c.rend(); ++it) stack.push_back({*it, me, f.depth + 1});   // best on top
-        }
+    } catch (const std::bad_alloc &) {
+        return -1;
     }
     return used;
 }
@@ -146,22 +159,26 @@ extern "C" double reader_self_repetition(const int32_t *prompt, int64_t n_prompt
     if (n_prompt < 0 || n_response < 0 || (n_prompt > 0 && !prompt) || (n_response > 0 && !response)) return -1.0;
     if (n_response == 0) return 0.0;
     // history = prompt, then the processed part of the response; a match must lie inside it
-    std::vector<int32_t> hist(prompt, prompt + n_prompt);
-    hist.reserve((size_t)(n_prompt + n_response));
-    int64_t ptr = 0, advances = 0;
-    while (ptr < n_response) {
-        int64_t best = 0;
-        const int64_t h = (int64_t)hist.size();
-        for (int64_t s = 0; s < h; ++s) {
-            if (hist[s] != response[ptr]) continue;
-            int64_t len = 0;
-            while (s + len < h && ptr + len < n_response && hist[s + len] == response[ptr + len]) ++len;
-            best = std::max(best, len);
+    try {
+        std::vector<int32_t> hist(prompt, prompt + n_prompt);
+        hist.reserve((size_t)(n_prompt + n_response));
+        int64_t ptr = 0, advances = 0;
+        while (ptr < n_response) {
+            int64_t best = 0;
+            const int64_t h = (int64_t)hist.size();
+            for (int64_t s = 0; s < h; ++s) {
+                if (hist[s] != response[ptr]) continue;
+                int64_t len = 0;
+                while (s + len < h && ptr + len < n_response && hist[s + len] == response[ptr + len]) ++len;
+                best = std::max(best, len);
+            }
+            const int64_t step = best > 0 ? best : 1;
+            hist.insert(hist.end(), response + ptr, response + ptr + step);
+            ptr += step;
+            ++advances;
         }
-        const int64_t step = best > 0 ? best : 1;
-        hist.insert(hist.end(), response + ptr, response + ptr + step);
-        ptr += step;
-        ++advances;
+        return (double)n_response / (double)advances;
+    } catch (const std::bad_alloc &) {
+        return -1.0;
     }
-    return (double)n_response / (double)advances;
 }

@@ -21,6 +21,19 @@ def R():
     return binding
 
 
+@pytest.fixture
+def tune(R):
+    """Planner overrides for one test; cleared afterwards whatever happens."""
+    touched = []
+
+    def set_(which, value):
+        touched.append(which)
+        R.reader_tuning_override(which, value)
+    yield set_
+    for which in touched:
+        R.reader_tuning_override(which, -1)
+
+
 def bf16_to_np(t):
     return t.float().cpu().numpy().astype(np.float64)
 
@@ -96,20 +109,20 @@ def test_attn_more_sequences_than_lengths_fit_in_lds(R, oracle_mod):
 
 
 @pytest.mark.parametrize("T,Hq", [(16, 8), (48, 16)])
-def test_attn_ranges_longer_than_the_tile_list(R, oracle_mod, T, Hq, monkeypatch):
+def test_attn_ranges_longer_than_the_tile_list(R, oracle_mod, T, Hq, tune):
     # few, long ranges: a workgroup walks more items than its list holds at once and has to
     # extend the list on the way (both kernel flavours: up to 128 query rows, and more)
-    monkeypatch.setenv("READER_ATTN_RANGES", "8")
+    tune(R.TUNE_ATTN_RANGES, 8)
     w = W.make_custom("long_ranges", B=1, Hq=Hq, Hkv=4, D=128, T=T, seq_lens=[35000], tree="trie", depth=6,
                       seed=405)
     check_attn(R, oracle_mod, w)
 
 
 @pytest.mark.parametrize("T,Hq", [(16, 8), (48, 16)])
-def test_attn_ranges_cut_with_64_bit_arithmetic(R, oracle_mod, T, Hq, monkeypatch):
+def test_attn_ranges_cut_with_64_bit_arithmetic(R, oracle_mod, T, Hq, tune):
     # the kernel cuts its ranges in 32-bit arithmetic when the host can show that nothing
     # overflows, else in 64-bit: force the second path on a ragged batch
-    monkeypatch.setenv("READER_ATTN_AXIS64", "1")
+    tune(R.TUNE_ATTN_AXIS64, 1)
     w = W.make_custom("axis64", B=5, Hq=Hq, Hkv=4, D=128, T=T, seq_lens=[1, 900, 64, 2051, 130], tree="trie",
                       depth=5, seed=406)
     check_attn(R, oracle_mod, w)
@@ -140,13 +153,13 @@ def test_attn_seeded_random_shapes(R, oracle_mod, case):
     check_attn(R, oracle_mod, w, variants=(0,))
 
 
-@pytest.mark.parametrize("rows", ["128", "256"])
+@pytest.mark.parametrize("rows", [128, 256])
 @pytest.mark.parametrize("T,Hq", [(64, 16), (128, 16), (100, 32)])
-def test_attn_more_than_128_query_rows_both_decompositions(R, oracle_mod, rows, T, Hq, monkeypatch):
+def test_attn_more_than_128_query_rows_both_decompositions(R, oracle_mod, rows, T, Hq, tune):
     # more than 128 query rows per kv head: workgroups of 128 rows (several row chunks per key range) and of
     # 256 rows must agree with the oracle; the library picks between them by problem size
-    monkeypatch.setenv("READER_ATTN_ROWS", rows)
-    w = W.make_custom("rows%s_T%d" % (rows, T), B=3, Hq=Hq, Hkv=4, D=128, T=T, seq_lens=[700, 0, 131], tree="trie",
+    tune(R.TUNE_ATTN_ROWS, rows)
+    w = W.make_custom("rows%d_T%d" % (rows, T), B=3, Hq=Hq, Hkv=4, D=128, T=T, seq_lens=[700, 0, 131], tree="trie",
                       depth=7, seed=407)
     check_attn(R, oracle_mod, w, variants=(0,))
 
@@ -155,9 +168,23 @@ def test_attn_more_than_128_query_rows_both_decompositions(R, oracle_mod, rows, 
                                          (64, 16, 128, [500, 31]), (128, 16, 128, [260]), (100, 32, 128, [64, 129]),
                                          (16, 8, 64, [5, 700]), (1, 8, 128, [40, 0])])
 def test_attn_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens):
+    check_attn_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens, variants=(0, 1))
+
+
+@pytest.mark.parametrize("T,Hq,D,lens", [(64, 16, 128, [500, 31]), (128, 16, 128, [260, 1500]), (100, 32, 128, [64, 129]),
+                                         (128, 8, 64, [300, 5, 0]), (33, 32, 128, [15])])
+def test_attn_tree_rows_in_the_cache_with_256_row_workgroups(R, oracle_mod, T, Hq, D, lens, tune):
+    # the planner picks 256-row workgroups only for large problems; forced here so that their copy loop
+    # (which fetches tree tiles two tiles ahead) meets tree tiles that have to be gathered from the cache
+    tune(R.TUNE_ATTN_ROWS, 256)
+    check_attn_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens, variants=(0,))
+
+
+def check_attn_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens, variants):
     # the in-cache layout: no tree tensors, node n of sequence b sits at cache position L_b + n (any alignment
     # to the 16-position pages); the result must be what the oracle gives for the separate-tensor layout
     import torch
+    print("in-cache attn: T", T, "Hq", Hq, "D", D, "lens", lens, "variants", variants, flush=True)
     w = W.make_custom("incache_T%d" % T, B=len(lens), Hq=Hq, Hkv=4, D=D, T=T, seq_lens=lens, tree="trie", depth=6,
                       seed=408 + T)
     ref, ref_lse = oracle_mod.tree_attn(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table, w.seq_lens,
@@ -168,7 +195,7 @@ def test_attn_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens):
     dims = R.make_dims(w.B, w.T, w.Hq, w.Hkv, w.D, table.shape[1], w.max_path, kc.shape[0])
     bound = int(max(lens))
     ws = torch.empty(max(R.reader_workspace_bytes(dims, bound), 256), dtype=torch.uint8, device="cuda")
-    for variant in (0, 1):
+    for variant in variants:
         dims.variant = variant
         dw.out.fill_(float("nan"))
         dw.status.zero_()
@@ -243,6 +270,27 @@ def test_malformed_tree_and_bad_page_set_status_without_faulting(R, oracle_mod):
         ref, _ = oracle_mod.tree_attn(w.q[:1], w.k_tree[:1], w.v_tree[:1], w.k_cache, w.v_cache,
                                       w.page_table[:1], w.seq_lens[:1], w.parents[:1])
         assert_close(out[:1], ref, what="sequence next to the bad one")
+    # the keys behind a bad page id are skipped: with the bad id in the last (partial) page of a sequence
+    # the result is that of the sequence cut in front of that page; with the bad id in the middle the two
+    # device implementations must agree
+    w = W.make_custom("status3", B=2, Hq=4, Hkv=2, D=128, T=10, seq_lens=[40, 90], tree="uniform", depth=4, seed=406)
+    w.page_table[1, 5] = -3
+    cut = w.seq_lens.copy()
+    cut[1] = 80
+    ref, ref_lse = oracle_mod.tree_attn(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table, cut, w.parents)
+    for variant in (0, 1):
+        out, lse = run_attn(R, w, variant=variant, want_status=R.STATUS_BAD_PAGE)
+        assert_close(out, ref, what="bad last page, variant %d" % variant)
+        assert_close(lse, ref_lse, what="bad last page lse, variant %d" % variant)
+    w = W.make_custom("status4", B=2, Hq=8, Hkv=2, D=128, T=40, seq_lens=[300, 200], tree="trie", depth=5, seed=407)
+    w.page_table[0, 0] = w.num_pages          # first quarter of the first tile
+    w.page_table[0, 9] = -1
+    w.page_table[1, 4] = w.num_pages + 1      # a whole tile of sequence 1 (pages 4..7)
+    w.page_table[1, 5] = w.page_table[1, 6] = w.page_table[1, 7] = -1
+    outs = [run_attn(R, w, variant=v, want_status=R.STATUS_BAD_PAGE) for v in (0, 1)]
+    assert np.isfinite(outs[0][0]).all() and np.isfinite(outs[0][1]).all()
+    assert_close(outs[0][0], outs[1][0], what="bad pages in the middle: matrix-core kernel against the scalar one")
+    assert_close(outs[0][1], outs[1][1], what="bad pages in the middle, lse")
 
 
 # ------------------------------------------------------------------ acceptance
@@ -421,8 +469,19 @@ def test_verify_step_equals_the_three_calls_and_the_oracle(R, oracle_mod, index,
 @pytest.mark.parametrize("T,Hq,D,lens", [(16, 8, 128, [0, 1, 15, 16, 200]), (40, 16, 64, [333, 1024, 77, 5]),
                                          (128, 16, 128, [50, 700])])
 def test_verify_step_with_the_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens):
+    check_verify_step_with_the_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens)
+
+
+@pytest.mark.parametrize("T,Hq,D,lens", [(64, 16, 128, [333, 1024, 77]), (128, 16, 64, [50, 700])])
+def test_verify_step_with_the_tree_rows_in_the_cache_and_256_row_workgroups(R, oracle_mod, T, Hq, D, lens, tune):
+    tune(R.TUNE_ATTN_ROWS, 256)
+    check_verify_step_with_the_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens)
+
+
+def check_verify_step_with_the_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens):
     # in-cache layout, one layer: attention over the cache, acceptance, the accepted rows move in place
     import torch
+    print("in-cache step: T", T, "Hq", Hq, "D", D, "lens", lens, flush=True)
     w = W.make_custom("incache_step_T%d" % T, B=len(lens), Hq=Hq, Hkv=4, D=D, T=T, seq_lens=lens, tree="trie", depth=7,
                       p_match=0.8, seed=418 + T)
     ref, ref_lse = oracle_mod.tree_attn(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table, w.seq_lens,
