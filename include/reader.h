@@ -157,6 +157,33 @@ int reader_tree_attn(const reader_dims *dims,
                      int32_t *status, void *stream);
 
 /*
+ * reader_tree_attn for callers that cannot allocate device memory or hand in a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (without workspace and workspace_bytes), same kernels and the same results as reader_tree_attn
+ * with dims->variant = 0; the partial records go to a workspace of READER_NOALLOC_WORKSPACE_BYTES
+ * that is part of the library's device code (every GPU the library is used on holds its own copy
+ * until the process ends).  The call allocates and frees nothing, on the host or the device.
+ *
+ *  - Dims whose reader_workspace_bytes(dims, max_seq_len) exceeds READER_NOALLOC_WORKSPACE_BYTES
+ *    are refused with READER_EWORKSPACE (reader_last_error_detail says by how much); the limit
+ *    covers e.g. B = 64, Hq = 64, Hkv = 8, T = 64, D = 128 at any length.
+ *  - All calls on one GPU share that GPU's workspace: calls that may overlap in time (different
+ *    streams, or host threads without ordering) race on it and must be ordered by the caller.
+ *  - The first call on a device looks up the workspace's device address (this may load the
+ *    library's device code).  A call with dims->B == 0 does only that and is the way to set a
+ *    device up ahead of time, outside any graph capture.
+ * dims->variant must be 0.  Returns as reader_tree_attn, READER_EUNSUPPORTED for a device index
+ * above 63.
+ */
+#define READER_NOALLOC_WORKSPACE_BYTES (72u << 20)
+int reader_tree_attn_noalloc(const reader_dims *dims,
+                             const void *q, const void *k_tree, const void *v_tree,
+                             const void *k_cache, const void *v_cache,
+                             const int32_t *page_table, const int32_t *seq_lens, const int32_t *parents,
+                             void *out, float *lse,
+                             int32_t max_seq_len, int32_t *status, void *stream);
+
+/*
  * Greedy lossless acceptance (Algorithm 5; Appendix C invariants 2 and 3).
  * target_tokens[b][i] is the base model's own next token after the prefix that
  * ends at node i.  A non-root node is accepted iff its parent is accepted and

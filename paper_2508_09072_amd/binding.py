@@ -27,7 +27,7 @@ TUNE_ATTN_ROWS, TUNE_ATTN_RANGES, TUNE_ATTN_PAIR_COST, TUNE_ATTN_AXIS64 = 0, 1, 
 
 EXPORTS = (
     "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",
-    "reader_tree_attn", "reader_accept_path", "reader_kv_compact", "reader_verify_step",
+    "reader_tree_attn", "reader_tree_attn_noalloc", "reader_accept_path", "reader_kv_compact", "reader_verify_step",
     "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax", "reader_target_sample", "reader_kv_compact_layers",
     "reader_trie_create", "reader_trie_destroy", "reader_trie_nodes", "reader_trie_insert", "reader_trie_search_path",
     "reader_trie_extract_tree", "reader_tree_attach_path", "reader_self_repetition",
@@ -81,6 +81,8 @@ def load():
     lib.reader_workspace_bytes.argtypes = [dp, i32]
     lib.reader_tree_attn.restype = ctypes.c_int
     lib.reader_tree_attn.argtypes = [dp] + [vp] * 10 + [i32, vp, ctypes.c_size_t, vp, vp]
+    lib.reader_tree_attn_noalloc.restype = ctypes.c_int
+    lib.reader_tree_attn_noalloc.argtypes = [dp] + [vp] * 10 + [i32, vp, vp]
     lib.reader_accept_path.restype = ctypes.c_int
     lib.reader_accept_path.argtypes = [dp] + [vp] * 8
     lib.reader_kv_compact.restype = ctypes.c_int
@@ -189,6 +191,22 @@ def reader_tree_attn(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_
         _dev(lse, torch.float32, optional=True), int(max_seq_len), _dev(workspace, optional=True),
         ws_bytes, _dev(status, torch.int32, optional=True), _stream())
     _check(code, "reader_tree_attn")
+
+
+NOALLOC_WORKSPACE_BYTES = 72 << 20
+
+
+def reader_tree_attn_noalloc(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, out, lse,
+                             max_seq_len, status=None):
+    import torch
+    code = load().reader_tree_attn_noalloc(
+        ctypes.byref(dims), _dev(q, torch.bfloat16, optional=dims.B == 0), _dev(k_tree, torch.bfloat16, optional=True),
+        _dev(v_tree, torch.bfloat16, optional=True),
+        _dev(k_cache, torch.bfloat16, optional=dims.B == 0), _dev(v_cache, torch.bfloat16, optional=dims.B == 0),
+        _dev(page_table, torch.int32, optional=dims.B == 0), _dev(seq_lens, torch.int32, optional=dims.B == 0),
+        _dev(parents, torch.int32, optional=dims.B == 0), _dev(out, torch.bfloat16, optional=dims.B == 0),
+        _dev(lse, torch.float32, optional=True), int(max_seq_len), _dev(status, torch.int32, optional=True), _stream())
+    _check(code, "reader_tree_attn_noalloc")
 
 
 def reader_accept_path(dims, draft_tokens, target_tokens, parents, accept_len, path, bonus_token, status=None):

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 
 #include <atomic>
+#include <mutex>
 #include <utility>
 #include <vector>
 
@@ -104,6 +105,35 @@ static bool profile_next(hipEvent_t *a, hipEvent_t *b) {
     *b = g_profile.pairs[g_profile.used].second;
     ++g_profile.used;
     return true;
+}
+
+// Workspace of reader_tree_attn_noalloc: device memory that belongs to the library's code object,
+// so that the call allocates nothing.  Every GPU the library runs on holds its own copy of the
+// array, at its own address, until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; `scratch_on_current_device` turns it into the device address
+// once per device, and everything else (kernel arguments) uses that address.
+static __device__ __align__(256) unsigned char scratch[READER_NOALLOC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];   // guarded by g_scratch_guard
+static std::mutex g_scratch_guard;
+
+static int scratch_on_current_device(void **ptr) {
+    int dev = -1;
+    if (note_hip_error("hipGetDevice", hipGetDevice(&dev)) != hipSuccess) return READER_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return READER_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_guard);
+    if (!g_scratch_ptr[dev]) {
+        void *addr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !addr) {
+            (void)hipGetLastError();
+            note_hip_error("hipGetSymbolAddress(scratch)", e != hipSuccess ? e : hipErrorInvalidSymbol);
+            return READER_EHIP;
+        }
+        g_scratch_ptr[dev] = addr;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return READER_OK;
 }
 
 static int row_chunks(const reader_dims &d, int32_t max_seq_len) {
@@ -267,6 +297,37 @@ extern "C" int reader_tree_attn(const reader_dims *dims, const void *q, const vo
         e = launch_tree_attn_mfma(p, (hipStream_t)stream, ev_a, ev_b);
     }
     return e == hipSuccess ? READER_OK : READER_EHIP;
+}
+
+extern "C" int reader_tree_attn_noalloc(const reader_dims *dims, const void *q, const void *k_tree,
+                                        const void *v_tree, const void *k_cache, const void *v_cache,
+                                        const int32_t *page_table, const int32_t *seq_lens,
+                                        const int32_t *parents, void *out, float *lse, int32_t max_seq_len,
+                                        int32_t *status, void *stream) {
+    int err = 0;
+    if (!dims_ok(dims, &err)) return err;
+    if (max_seq_len < 0 || dims->variant != 0) return READER_EINVAL;
+    // the size check comes first: a problem that does not fit is refused whatever the device's state
+    const size_t need = reader_workspace_bytes(dims, max_seq_len);
+    if (need > (size_t)READER_NOALLOC_WORKSPACE_BYTES) {
+        snprintf(g_error_detail, sizeof g_error_detail,
+                 "reader_tree_attn_noalloc: these dims need %zu bytes of workspace, the built-in one holds %zu", need,
+                 (size_t)READER_NOALLOC_WORKSPACE_BYTES);
+        return READER_EWORKSPACE;
+    }
+    void *ws = nullptr;
+    const int rc_ws = scratch_on_current_device(&ws);   // first call on a device: looks the address up (B = 0 does only this)
+    if (rc_ws != READER_OK) return rc_ws;
+    AttnParams p;
+    bool empty = false;
+    const int rc = attn_prepare(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, out, lse,
+                                max_seq_len, ws, status, p, &empty);
+    if (rc != READER_OK || empty) return rc;
+    // Nothing in the workspace has to start at zero: every range workgroup writes its tile count and the
+    // pair table afresh before the merge reads them, and a record slot is only read when this call's
+    // tile count of its range says that this call wrote it.
+    forget_stale_error();
+    return launch_tree_attn_mfma(p, (hipStream_t)stream, nullptr, nullptr) == hipSuccess ? READER_OK : READER_EHIP;
 }
 
 extern "C" int reader_verify_step(const reader_dims *dims, const void *q, const void *k_tree, const void *v_tree,
