@@ -23,7 +23,27 @@ FLAGS = [
     "-Wall",
     # the LDS-copy inline asm names m0 as clobbered on purpose
     "-Wno-inline-asm",
+    # per-kernel register and scratch usage as compiler remarks: checked below
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+
+
+def spilled_kernels(compiler_output: str):
+    """(kernel, spilled VGPRs) for every kernel the compiler had to spill vector registers in.
+
+    The attention kernels are written against the register file (256 registers per lane with two
+    wavefronts per SIMD, 512 with one): a change that makes them spill costs a factor of two and
+    shows in no test, so the build refuses it."""
+    import re
+    found, name = [], None
+    for line in compiler_output.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"VGPRs? Spill: (\d+)", line)
+        if m and name and int(m.group(1)) > 0:
+            found.append((name, int(m.group(1))))
+    return found
 
 
 def build(verbose: bool = False) -> str:
@@ -34,10 +54,23 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines() if "not a recognized feature" not in l)
-    if res.returncode != 0:
+    spilled = spilled_kernels(res.stdout)
+    kept, after_remark = [], False
+    for l in res.stdout.splitlines():
+        if "remark:" in l:
+            after_remark = True
+            continue
+        if after_remark and l.lstrip()[:1] in "|0123456789":    # the source line and the caret under a remark
+            continue
+        after_remark = False
+        if "not a recognized feature" not in l:
+            kept.append(l)
+    out = "\n".join(kept)
+    if res.returncode != 0 or spilled:
         if os.path.exists(tmp):
             os.remove(tmp)
+        if spilled:
+            raise RuntimeError("kernels spill vector registers: %s" % spilled)
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)

@@ -127,7 +127,7 @@ static int scratch_on_current_device(void **ptr) {
         const hipError_t e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
         if (e != hipSuccess || !addr) {
             (void)hipGetLastError();
-            note_hip_error("hipGetSymbolAddress(scratch)", e != hipSuccess ? e : hipErrorInvalidSymbol);
+            (void)note_hip_error("hipGetSymbolAddress(scratch)", e != hipSuccess ? e : hipErrorInvalidSymbol);
             return READER_EHIP;
         }
         g_scratch_ptr[dev] = addr;
