@@ -9,13 +9,16 @@ instead), all on one stream, inputs resident in HBM before the clock starts.  Th
 second (B * T draft-tree nodes verified per step) together with the achieved HBM
 bandwidth of the attention kernel, which streams the K/V cache and dominates.
 
-    python bench.py --gpus 1 --steps 500 --warmup 1000
+    python bench.py --gpus 1 --steps 200 --warmup 20
 
-prints ONE JSON line.  The headline workload is the batched ragged serving preset
-(B=16, L in [1024,4096], T=32), the HBM-bound shape the 70 %-of-peak target is
-stated for; the other presets are timed with fewer steps and reported inside the
-same line under "other_workloads".  `--gpus N` with N > 1 is refused: this build
-is single-GPU.
+prints ONE JSON line.  The headline workload is the largest single-GPU preset (cfg4:
+B=64, Hq=64, L in [2048,8192], T=64, the whole step timed end to end); the other four
+presets are timed the same way and reported inside the same line under
+"other_workloads", each with its own roofline object and its own CPU-oracle baseline.
+Before the timed steps of a workload the same steps run untimed for at least
+SETTLE_MS (the GPU needs some tens of milliseconds of load to reach its clocks; the
+`warmup` argument is honoured on top of that and echoed unchanged).  `--gpus N` with
+N > 1 is refused: this build is single-GPU.
 """
 from __future__ import annotations
 
@@ -34,6 +37,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 ROTATE_BYTES = 512 << 20       # K/V copies cycled per step so the 256 MB Infinity Cache cannot serve the stream
 CALIBRATION_BYTES = 256 << 20  # size of the plain elementwise pass the counter runs are scaled by
+SETTLE_MS = 60.0               # untimed load in front of every timed region
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "tree_attn_mfma_kernel_hbm_traffic.txt")
 
 
@@ -95,13 +99,55 @@ class StepRunner:
                 raise RuntimeError("library call failed in step %d" % k)
 
 
+def settle(run, torch, warmup, min_ms=SETTLE_MS):
+    """The workload's own steps, untimed, until the GPU has been under load for min_ms: `warmup` steps at
+    least.  Returns (milliseconds spent, steps run)."""
+    t0 = time.perf_counter()
+    n = 0
+    while True:
+        run.run(0, max(warmup, 1))
+        run.reset()
+        torch.cuda.synchronize()
+        n += max(warmup, 1)
+        ms = (time.perf_counter() - t0) * 1e3
+        if ms >= min_ms or n >= 100000:
+            return ms, n
+
+
+def roofline_of(w, each):
+    """Roofline object of the attention main kernel from its per-launch times (ms, HIP events bound to the kernel)."""
+    import numpy as np
+    n = len(each)
+    kernel_ms = float(each.sum()) / max(n, 1)
+    alg_bytes = w.algorithmic_bytes()
+    flops = w.attention_flops()
+    gbs = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    tflops = flops / (kernel_ms * 1e-3) / 1e12
+    hbm_t = alg_bytes / (HBM_PEAK_GBS * 1e9)
+    mfma_t = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if hbm_t >= mfma_t:
+        roof = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+    else:
+        roof = {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tflops / MFMA_BF16_PEAK_TFLOPS}
+    roof.update({"kernel": "tree_attn_mfma_kernel", "kernel_ms": kernel_ms, "launches_timed": n,
+                 "kernel_ms_median": float(np.median(each)) if n else None,
+                 "kernel_ms_min": float(each.min()) if n else None,
+                 "algorithmic_bytes": alg_bytes, "algorithmic_flops": flops, "hbm_gbs": gbs,
+                 "hbm_frac": gbs / HBM_PEAK_GBS, "mfma_tflops": tflops, "mfma_frac": tflops / MFMA_BF16_PEAK_TFLOPS,
+                 "traffic": measured_traffic(w.name)})
+    return roof
+
+
 def time_workload(R, torch, w, steps, warmup, use_graph=True, fused=True):
     total = warmup + steps
     run = StepRunner(R, torch, w, total, fused=fused)
     res = {"workload": w.name, "kv_copies_rotated": run.n_copies,
            "entry_points": "reader_verify_step" if fused else "reader_tree_attn+reader_accept_path+reader_kv_compact"}
 
-    # ---- eager: warmup, then exactly `steps` steps between two synchronisations
+    # ---- untimed load until the clocks have settled, then `warmup` steps, then exactly `steps` steps
+    # between two synchronisations
+    res["settle_ms"], res["settle_steps"] = settle(run, torch, warmup)
     run.run(0, warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -122,7 +168,7 @@ def time_workload(R, torch, w, steps, warmup, use_graph=True, fused=True):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):
                 run.run(warmup, steps)
-            for _ in range(2):                      # replay is checked against eager every time
+            for _ in range(3):                      # replay is checked against eager every time
                 run.reset()
                 run.dw.out.zero_()
                 torch.cuda.synchronize()
@@ -152,26 +198,7 @@ def time_workload(R, torch, w, steps, warmup, use_graph=True, fused=True):
     torch.cuda.synchronize()
     each = R.reader_profile_collect_each()
     R.reader_profile_enable(False)
-    n = len(each)
-    kernel_ms = float(each.sum()) / max(n, 1)
-    alg_bytes = w.algorithmic_bytes()
-    flops = w.attention_flops()
-    gbs = alg_bytes / (kernel_ms * 1e-3) / 1e9
-    tflops = flops / (kernel_ms * 1e-3) / 1e12
-    hbm_t = alg_bytes / (HBM_PEAK_GBS * 1e9)
-    mfma_t = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
-    if hbm_t >= mfma_t:
-        roof = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
-    else:
-        roof = {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": tflops / MFMA_BF16_PEAK_TFLOPS}
-    import numpy as np
-    roof.update({"kernel": "tree_attn_mfma_kernel", "kernel_ms": kernel_ms, "launches_timed": n,
-                 "kernel_ms_median": float(np.median(each)) if n else None,
-                 "kernel_ms_min": float(each.min()) if n else None,
-                 "algorithmic_bytes": alg_bytes, "algorithmic_flops": flops, "hbm_gbs": gbs,
-                 "hbm_frac": gbs / HBM_PEAK_GBS, "mfma_tflops": tflops, "traffic": measured_traffic(w.name)})
-    res["roofline"] = roof
+    res["roofline"] = roofline_of(w, each)
     return res
 
 
@@ -180,6 +207,7 @@ def time_steps_only(R, torch, w, steps, warmup, **runner_kw):
     of the headline preset (attention alone; K/V not rotated)."""
     total = warmup + steps
     run = StepRunner(R, torch, w, total, **runner_kw)
+    settle(run, torch, warmup)
     run.run(0, warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -243,10 +271,9 @@ def calibration_pass(torch):
     del x, y
 
 
-def cpu_baseline(w, budget_s=12.0):
-    """The CPU oracle, as it stands, on the same workload: whole steps until the budget is used."""
+def oracle_steps(w, budget_s, max_reps):
+    """Whole steps of the CPU oracle, as it stands, on workload w until the budget is used.  Returns (steps, seconds)."""
     import oracle
-    import numpy as np
     reps, t0 = 0, time.perf_counter()
     while True:
         kc, vc, sl = w.k_cache, w.v_cache, w.seq_lens.copy()
@@ -256,11 +283,31 @@ def cpu_baseline(w, budget_s=12.0):
         oracle.kv_compact(w.k_tree, w.v_tree, path, al, kc, vc, w.page_table, sl)
         reps += 1
         dt = time.perf_counter() - t0
-        if dt >= budget_s or reps >= 50:
-            break
-    return {"value": w.B * w.T * reps / dt, "unit": "tree tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "cpu_model": cpu_model(), "host_cpus": os.cpu_count(),
-            "sample": "%d whole step(s) of %s (attention + acceptance + compaction), %.1f s" % (reps, w.name, dt)}
+        if dt >= budget_s or reps >= max_reps:
+            return reps, dt
+
+
+def cpu_baseline(w, budget_s=12.0, max_reps=50, one_thread_index=None):
+    """The CPU oracle on the same workload, on the host cores of the GPU machine: a bounded sample (whole steps
+    until the budget is used; at least one).  one_thread_index: also time it with a single thread (a child
+    process, the thread count is fixed when the OpenMP runtime starts) on preset number one_thread_index."""
+    import oracle
+    reps, dt = oracle_steps(w, budget_s, max_reps)
+    res = {"value": w.B * w.T * reps / dt, "unit": "tree tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+           "cpu_model": cpu_model(), "host_cpus": os.cpu_count(),
+           "sample": "%d whole step(s) of %s (attention + acceptance + compaction), %.1f s" % (reps, w.name, dt)}
+    if one_thread_index is not None:
+        import subprocess
+        code = ("import sys, json; sys.path.insert(0, %r); import bench; from paper_2508_09072_amd import workloads as W; "
+                "w = W.make_config(%d); r, t = bench.oracle_steps(w, 3.0, 20); print(json.dumps([r, t]))" % (ROOT, one_thread_index))
+        try:
+            out = subprocess.run([sys.executable, "-c", code], env=dict(os.environ, OMP_NUM_THREADS="1"), stdout=subprocess.PIPE,
+                                 stderr=subprocess.DEVNULL, text=True, timeout=120).stdout
+            r1, t1 = json.loads(out.strip().splitlines()[-1])
+            res["one_thread"] = {"value": w.B * w.T * r1 / t1, "cores": 1, "sample": "%d whole step(s), %.1f s" % (r1, t1)}
+        except Exception as e:      # the all-cores figure stands on its own
+            log("one-thread oracle timing failed:", repr(e))
+    return res
 
 
 def time_rearrange(R, torch, W, reps=10):
@@ -407,12 +454,12 @@ def time_drafter(R, W, n_tokens=65536, n_trees=2000):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=1000,
-                    help="untimed steps first; the GPU needs some tens of milliseconds of load to settle at its clocks")
-    ap.add_argument("--config", type=int, default=2, help="headline preset (0..4)")
-    ap.add_argument("--others", type=str, default="0,1,3,4", help="presets also timed (comma list, '' for none)")
-    ap.add_argument("--other-steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed steps right before the timed ones (on top of the time-based settle phase)")
+    ap.add_argument("--config", type=int, default=4, help="headline preset (0..4)")
+    ap.add_argument("--others", type=str, default="0,1,2,3", help="presets also timed (comma list, '' for none)")
+    ap.add_argument("--other-steps", type=int, default=0, help="timed steps of the other presets (0: as --steps)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-calls", action="store_true",
@@ -464,41 +511,45 @@ def main():
                    "entry_points": head["entry_points"]},
         "eager_ms_per_step": head["eager_ms_per_step"],
         "graph_ms_per_step": head.get("graph_ms_per_step"),
+        "settle_ms": head["settle_ms"],
         "roofline": head["roofline"],
     }
-    if not args.no_scaled_shapes:
-        # side figures of the headline preset: the attention entry point alone (its two launches), and the
-        # step with K/V not rotated (one copy, small enough for the 256 MB Infinity Cache)
-        side_steps, side_warm = min(args.steps, 200), min(args.warmup, 300)
-        line["attention_only"] = time_steps_only(R, torch, w, side_steps, side_warm, attention_only=True)
-        line["cache_resident"] = time_steps_only(R, torch, w, side_steps, side_warm, rotate=False)
-        line["cache_resident"]["note"] = ("K/V not rotated: a single copy, which fits the 256 MB Infinity Cache where the "
-                                          "rotated copies cannot; the tile copies carry the non-temporal hint")
     if not args.no_cpu_baseline:
-        log("timing the CPU oracle")
-        line["cpu_baseline"] = cpu_baseline(w)
-    del head
+        log("timing the CPU oracle on the headline workload")
+        line["cpu_baseline"] = cpu_baseline(w, budget_s=8.0, max_reps=50,
+                                            one_thread_index=args.config if args.config in (0, 1) else None)
+    del head, w
+    torch.cuda.empty_cache()
 
     others = {}
+    other_steps = args.other_steps if args.other_steps > 0 else args.steps
     for idx in [int(x) for x in args.others.split(",") if x.strip() != ""]:
         if idx == args.config:
             continue
         log("generating", W.CONFIG_NAMES[idx])
         wo = W.make_config(idx)
-        r = time_workload(R, torch, wo, args.other_steps, min(args.warmup, 50), use_graph=not args.no_graph,
+        r = time_workload(R, torch, wo, other_steps, args.warmup, use_graph=not args.no_graph,
                           fused=not args.separate_calls)
         others[wo.name] = {"tree_tokens_per_s": r["tree_tokens_per_s"], "ms_per_step": r["ms_per_step"],
-                           "launch_mode": r["launch_mode"], "steps": args.other_steps,
-                           "kernel_ms": r["roofline"]["kernel_ms"], "bound": r["roofline"]["bound"],
-                           "frac": r["roofline"]["frac"], "hbm_gbs": r["roofline"]["hbm_gbs"],
-                           "hbm_frac": r["roofline"]["hbm_frac"], "mfma_tflops": r["roofline"]["mfma_tflops"]}
+                           "launch_mode": r["launch_mode"], "steps": other_steps, "settle_ms": r["settle_ms"],
+                           "roofline": r["roofline"]}
+        if idx == 2 and not args.no_scaled_shapes:
+            # side figures of the batched HBM-bound preset: the attention entry point alone (its two launches),
+            # and the step with K/V not rotated (one copy, small enough for the 256 MB Infinity Cache)
+            side_steps = min(other_steps, 200)
+            others[wo.name]["attention_only"] = time_steps_only(R, torch, wo, side_steps, args.warmup, attention_only=True)
+            others[wo.name]["cache_resident"] = time_steps_only(R, torch, wo, side_steps, args.warmup, rotate=False)
+        if not args.no_cpu_baseline:
+            # the two long presets run once (several seconds each); the small ones also with one thread
+            others[wo.name]["cpu_baseline"] = cpu_baseline(wo, budget_s=4.0, max_reps=20,
+                                                           one_thread_index=idx if idx in (0, 1) else None)
         log(wo.name, json.dumps(others[wo.name]))
         del wo, r
         torch.cuda.empty_cache()
     line["other_workloads"] = others
     if not args.no_scaled_shapes:
-        # The headline shape with more bytes per launch (longer contexts, or more sequences): the fixed part
-        # of a launch (start, first latency, end) weighs less, the achieved fraction of the HBM peak rises.
+        # The batched HBM-bound shape (cfg2) with more bytes per launch (longer contexts, or more sequences): the
+        # fixed part of a launch (start, first latency, end) weighs less, the achieved fraction of the HBM peak rises.
         import numpy as np
         scaled = {}
         rng = np.random.Generator(np.random.PCG64(W.SEED_BASE + 90))
@@ -507,7 +558,7 @@ def main():
             L = [int(x) for x in rng.integers(lo, hi + 1, size=B)]
             wo = W.make_custom(name, B=B, Hq=32, Hkv=8, D=128, T=32, seq_lens=L, tree="trie", depth=6, branch=3,
                                vocab=128256, p_match=0.7, seed=W.SEED_BASE + 91)
-            r = time_workload(R, torch, wo, args.other_steps, min(args.warmup, 50), use_graph=not args.no_graph,
+            r = time_workload(R, torch, wo, min(other_steps, 100), args.warmup, use_graph=not args.no_graph,
                               fused=not args.separate_calls)
             scaled[name] = {"tree_tokens_per_s": r["tree_tokens_per_s"], "ms_per_step": r["ms_per_step"],
                             "kernel_ms": r["roofline"]["kernel_ms"], "algorithmic_bytes": r["roofline"]["algorithmic_bytes"],
