@@ -411,6 +411,29 @@ int32_t reader_tree_attach_path(int32_t *tokens, int32_t *parents, int32_t n_nod
 double reader_self_repetition(const int32_t *prompt, int64_t n_prompt, const int32_t *response, int64_t n_response);
 
 /*
+ * Tree-shape selection (Appendix E; objective of Theorem 1, Section 3.3).  Host pointers, no GPU.
+ * A seed tree (parents as everywhere: parents[0] = -1, 0 <= parents[i] < i) carries per node an
+ * acceptance frequency alpha[i] (alpha[0] = 1 for the root; a child's is at most its parent's) and
+ * an effective drafting time t_draft[i] (Lemma 2; t_draft[0] is ignored).  T_n is the seed tree after
+ * n removals, each of the leaf with the lowest alpha (equal alphas: the highest node id), so
+ * every T_n is a prefix subtree of the seed tree.  Its modelled throughput is
+ *     ( sum of alpha_i over its nodes ) / ( sum of t_draft_i over its non-root nodes + tv[|T_n| - 1] ),
+ * tv[k - 1] = measured verification time of a tree of k nodes (same unit as t_draft), k = 1..T.
+ *
+ * reader_tree_prune_order writes the removal order (T - 1 node ids) and returns T - 1.
+ * reader_tree_select returns the pruning level n* with the best throughput and marks the nodes of
+ * T_n* in keep[T] (1 = stays).  exhaustive != 0 scores every n; otherwise a golden-section search
+ * is run, which assumes that the curve rises and then falls (Appendix E: close to unimodal) and
+ * scores O(log T) trees: the way to go when a score is a benchmark run.  *throughput and
+ * *evaluations (both optional) receive the best score and the number of trees scored.
+ * Both return -1 on a bad argument (malformed tree, null pointer, negative or undefined value,
+ * tv not positive) or when memory runs out.
+ */
+int32_t reader_tree_prune_order(const int32_t *parents, const float *alpha, int32_t T, int32_t *order);
+int32_t reader_tree_select(const int32_t *parents, const float *alpha, const float *t_draft, const float *tv,
+                           int32_t T, int32_t exhaustive, int32_t *keep, double *throughput, int32_t *evaluations);
+
+/*
  * Measurement hooks for benchmarks (not operations of the method).  While enabled,
  * every reader_tree_attn / reader_verify_step call launches its main streaming kernel
  * with a HIP event pair that takes the kernel's own start and end time stamps (the

@@ -30,7 +30,8 @@ EXPORTS = (
     "reader_tree_attn", "reader_tree_attn_noalloc", "reader_accept_path", "reader_kv_compact", "reader_verify_step",
     "reader_kv_rearrange_scratch_bytes", "reader_kv_rearrange", "reader_target_argmax", "reader_target_sample", "reader_kv_compact_layers",
     "reader_trie_create", "reader_trie_destroy", "reader_trie_nodes", "reader_trie_insert", "reader_trie_search_path",
-    "reader_trie_extract_tree", "reader_tree_attach_path", "reader_self_repetition",
+    "reader_trie_extract_tree", "reader_tree_attach_path", "reader_self_repetition", "reader_tree_prune_order",
+    "reader_tree_select",
     "reader_profile_enable", "reader_profile_collect", "reader_profile_collect_each", "reader_tuning_override",
 )
 
@@ -112,6 +113,10 @@ def load():
     lib.reader_tree_attach_path.argtypes = [vp, vp, i32, i32, i32, vp, i32]
     lib.reader_self_repetition.restype = ctypes.c_double
     lib.reader_self_repetition.argtypes = [vp, i64, vp, i64]
+    lib.reader_tree_prune_order.restype = i32
+    lib.reader_tree_prune_order.argtypes = [vp, vp, i32, vp]
+    lib.reader_tree_select.restype = i32
+    lib.reader_tree_select.argtypes = [vp, vp, vp, vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
     lib.reader_kv_compact_layers.restype = ctypes.c_int
     lib.reader_kv_compact_layers.argtypes = [ctypes.POINTER(ReaderDims), i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.reader_target_sample.restype = ctypes.c_int
@@ -351,6 +356,41 @@ def reader_tree_attach_path(tokens, parents, n_nodes: int, at_node: int, path_to
     if n < 0:
         raise ValueError("reader_tree_attach_path: bad argument")
     return int(n)
+
+
+def _host_f32(a):
+    import numpy as np
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, ctypes.c_void_p(a.ctypes.data)
+
+
+def reader_tree_prune_order(parents, alpha):
+    """Removal order of Appendix E (numpy int32 array of T - 1 node ids)."""
+    import numpy as np
+    par, pp = _host_i32(parents)
+    al, pa = _host_f32(alpha)
+    order = np.zeros(max(par.size - 1, 1), dtype=np.int32)
+    n = load().reader_tree_prune_order(pp, pa, par.size, ctypes.c_void_p(order.ctypes.data))
+    if n < 0:
+        raise ValueError("reader_tree_prune_order: bad argument")
+    return order[:n].copy()
+
+
+def reader_tree_select(parents, alpha, t_draft, tv, exhaustive=False):
+    """Returns (n_star, keep mask as numpy bool [T], modelled throughput, trees scored)."""
+    import numpy as np
+    par, pp = _host_i32(parents)
+    al, pa = _host_f32(alpha)
+    td, pt = _host_f32(t_draft)
+    tvv, pv = _host_f32(tv)
+    assert al.size == par.size and td.size == par.size and tvv.size == par.size
+    keep = np.zeros(par.size, dtype=np.int32)
+    thr, ev = ctypes.c_double(0.0), ctypes.c_int32(0)
+    n = load().reader_tree_select(pp, pa, pt, pv, par.size, 1 if exhaustive else 0, ctypes.c_void_p(keep.ctypes.data),
+                                  ctypes.byref(thr), ctypes.byref(ev))
+    if n < 0:
+        raise ValueError("reader_tree_select: bad argument")
+    return int(n), keep.astype(bool), float(thr.value), int(ev.value)
 
 
 def reader_self_repetition(prompt, response) -> float:

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libreader_hip.so")
-SOURCES = ["reader_api.hip", "trie_drafter.cpp", "accept_compact.hip", "kv_compact_layers.hip", "kv_rearrange.hip", "target_argmax.hip", "target_sample.hip", "tree_attn_scalar.hip", "tree_attn_mfma.hip"]
+SOURCES = ["reader_api.hip", "trie_drafter.cpp", "tree_shape.cpp", "accept_compact.hip", "kv_compact_layers.hip", "kv_rearrange.hip", "target_argmax.hip", "target_sample.hip", "tree_attn_scalar.hip", "tree_attn_mfma.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions

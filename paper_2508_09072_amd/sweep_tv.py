@@ -5,13 +5,19 @@ time for a tree of T nodes: flat while the step is bound by reading the KV cache
 growing once the tree makes it compute bound (Section 3.2: reads grow with b*h*(gamma+s),
 flops with b*h*gamma*(gamma+s); Section 3.3 and Appendix E take T_V as given).  This
 script measures that curve for the attention part of the step with the library's own
-kernels, on the batched ragged serving shape (B=16, 32/8 heads, D=128, L in [1024,4096]):
+kernels, on the shapes of three presets: the single prompt (B=1, L=4096; the paper's case for
+large trees), the batched ragged serving shape (B=16, L in [1024,4096]) and the large batch
+(B=64, 64/8 heads, L in [2048,8192]):
 
-    python -m paper_2508_09072_amd.sweep_tv [--steps 50]
+    python -m paper_2508_09072_amd.sweep_tv [--steps 50] [--shapes single,batched,large]
 
 One line per tree size: query rows per kv head, time of the attention main kernel and of
 the whole fused step, tree tokens per second, achieved HBM bandwidth and matrix rate.
-Inputs are seeded and synthetic (same recipe as the benchmark presets).
+Then the curve is handed to the tree-shape selection of Appendix E (reader_tree_select): a
+seed tree of 128 nodes with synthetic acceptance frequencies (a child's at most its parent's)
+is pruned leaf by leaf and the size with the best modelled throughput sum(alpha) / (T_D + T_V)
+is reported, for drafting that is free (retrieval on the host, in parallel) and for a drafter
+that costs 2 us per node.  Inputs are seeded and synthetic (same recipe as the benchmark presets).
 """
 from __future__ import annotations
 
@@ -66,10 +72,37 @@ def measure(R, torch, w, steps: int, warmup: int = 5):
     return step_s, ms_sum / max(launches, 1) * 1e-3
 
 
+SHAPES = {
+    # name: (B, Hq, Hkv, (L lo, L hi), trie depth, branching)
+    "single": (1, 32, 8, (4096, 4096), 8, 4),
+    "batched": (16, 32, 8, (1024, 4096), 6, 3),
+    "large": (64, 64, 8, (2048, 8192), 10, 4),
+}
+
+
+def seed_tree(T, rng):
+    """An overprovisioned seed tree in the manner of Appendix E: a trie-shaped tree whose k-th child is accepted
+    less often than the (k-1)-th and whose acceptance decays with depth; alpha = product along the root path."""
+    parents, alpha, rank = [-1], [1.0], [0]
+    n_children = [0]
+    while len(parents) < T:
+        p = int(rng.integers(0, len(parents)))
+        if n_children[p] >= 4:
+            continue
+        k = n_children[p]
+        n_children[p] += 1
+        parents.append(p)
+        n_children.append(0)
+        rank.append(k)
+        alpha.append(alpha[p] * (0.62, 0.2, 0.08, 0.04)[k] * float(rng.uniform(0.85, 1.0)))
+    return np.asarray(parents, dtype=np.int32), np.asarray(alpha, dtype=np.float32)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--sizes", type=str, default="1,2,4,8,16,24,32,48,64,96,128")
+    ap.add_argument("--shapes", type=str, default="single,batched,large")
     args = ap.parse_args()
 
     import torch
@@ -78,18 +111,40 @@ def main():
 
     R.load()
     torch.cuda.set_device(0)
-    rng = np.random.Generator(np.random.PCG64(W.SEED_BASE + 2))
-    L = [int(x) for x in rng.integers(1024, 4096 + 1, size=16)]
-    print("# T_V(T): attention of one verification step, B=16 Hq=32 Hkv=8 D=128 sum_L=%d, eager launches" % sum(L))
-    print("# %4s %5s %10s %10s %14s %9s %9s" % ("T", "rows", "kernel_us", "step_us", "tree_tok_per_s", "HBM_GB/s", "TFLOP/s"))
-    for T in [int(x) for x in args.sizes.split(",")]:
-        w = W.make_custom("sweep_T%d" % T, B=16, Hq=32, Hkv=8, D=128, T=T, seq_lens=L,
-                          tree="trie" if T > 1 else "chain", depth=min(6, max(T - 1, 1)), branch=3, vocab=128256,
-                          p_match=0.7, seed=W.SEED_BASE + 3000 + T)
-        step_s, kern_s = measure(R, torch, w, args.steps)
-        print("  %4d %5d %10.1f %10.1f %14.0f %9.0f %9.1f" % (
-            T, T * 4, kern_s * 1e6, step_s * 1e6, 16 * T / step_s, w.algorithmic_bytes() / kern_s / 1e9,
-            w.attention_flops() / kern_s / 1e12), flush=True)
+    sizes = [int(x) for x in args.sizes.split(",")]
+    for shape in [x for x in args.shapes.split(",") if x]:
+        B, Hq, Hkv, (lo, hi), depth, branch = SHAPES[shape]
+        rng = np.random.Generator(np.random.PCG64(W.SEED_BASE + 2))
+        L = [int(x) for x in rng.integers(lo, hi + 1, size=B)]
+        G = Hq // Hkv
+        print("# T_V(T), shape %s: attention of one verification step, B=%d Hq=%d Hkv=%d D=128 sum_L=%d, eager launches"
+              % (shape, B, Hq, Hkv, sum(L)))
+        print("# %4s %5s %10s %10s %14s %9s %9s" % ("T", "rows", "kernel_us", "step_us", "tree_tok_per_s", "HBM_GB/s", "TFLOP/s"))
+        step_us = {}
+        for T in sizes:
+            w = W.make_custom("sweep_%s_T%d" % (shape, T), B=B, Hq=Hq, Hkv=Hkv, D=128, T=T, seq_lens=L,
+                              tree="trie" if T > 1 else "chain", depth=min(depth, max(T - 1, 1)), branch=branch,
+                              vocab=128256, p_match=0.7, seed=W.SEED_BASE + 3000 + T)
+            step_s, kern_s = measure(R, torch, w, args.steps)
+            step_us[T] = step_s * 1e6
+            print("  %4d %5d %10.1f %10.1f %14.0f %9.0f %9.1f" % (
+                T, T * G, kern_s * 1e6, step_s * 1e6, B * T / step_s, w.algorithmic_bytes() / kern_s / 1e9,
+                w.attention_flops() / kern_s / 1e12), flush=True)
+            del w
+            torch.cuda.empty_cache()
+        # Appendix E on the measured curve (linear between the measured sizes)
+        T0 = max(sizes)
+        tv = np.interp(np.arange(1, T0 + 1), sizes, [step_us[t] for t in sizes]).astype(np.float32)
+        parents, alpha = seed_tree(T0, np.random.Generator(np.random.PCG64(W.SEED_BASE + 4)))
+        for label, per_node in (("free drafting", 0.0), ("2 us per drafted node", 2.0)):
+            t_draft = np.full(T0, per_node, dtype=np.float32)
+            n, keep, thr, evals = R.reader_tree_select(parents, alpha, t_draft, tv)
+            n_x, keep_x, thr_x, _ = R.reader_tree_select(parents, alpha, t_draft, tv, exhaustive=True)
+            print("# tree-shape selection, %s: seed tree of %d nodes (sum alpha %.2f) -> %d nodes kept, expected tokens per step %.2f, "
+                  "modelled %.0f tokens/s per sequence (%d trees scored; exhaustive search: %d nodes, %.0f tokens/s)"
+                  % (label, T0, float(alpha.sum()), int(keep.sum()), float(alpha[keep].sum()), thr * 1e6, evals,
+                     int(keep_x.sum()), thr_x * 1e6), flush=True)
+        print(flush=True)
 
 
 if __name__ == "__main__":

@@ -236,24 +236,53 @@ def test_attn_max_seq_len_bound_may_be_loose(R, oracle_mod):
 
 # ------------------------------------------------------------------ attention, full size, sampled rows
 
-@pytest.mark.parametrize("index", [2, 3, 4])
-def test_attn_full_size_sampled_rows(R, oracle_mod, index):
-    # the launch configuration the benchmark times; the oracle checks a sample of output rows
-    w = W.make_config(index)
-    print("full-size attn:", w.name, flush=True)
-    out, lse = run_attn(R, w)
-    rng = np.random.Generator(np.random.PCG64(900 + index))
-    n = 96
-    rows = np.stack([rng.integers(0, w.B, n), rng.integers(0, w.Hq, n), rng.integers(0, w.T, n)], axis=1).astype(np.int32)
-    rows[0] = (0, 0, 0)
-    rows[1] = (w.B - 1, w.Hq - 1, w.T - 1)
+def stratified_rows(w, rng):
+    """Output rows (b, hq, node) to check at full size: for every (sequence, kv head) pair one random row in each
+    chunk of 128 query rows (a query row is node * G + grouped head; workgroups carry 128 or 256 of them), and
+    the pair's first and last query row.  Pairs that are cut between workgroups, second row chunks and merged
+    pairs are all hit this way, whatever the launch plan is."""
+    G = w.Hq // w.Hkv
+    M = w.T * G
+    rows = []
+    for b in range(w.B):
+        for hkv in range(w.Hkv):
+            picks = {0, M - 1}
+            for lo in range(0, M, 128):
+                picks.add(int(rng.integers(lo, min(lo + 128, M))))
+            for m in sorted(picks):
+                rows.append((b, hkv * G + m % G, m // G))
+    return np.asarray(rows, dtype=np.int32)
+
+
+def check_sampled_rows(oracle_mod, w, out, lse, rows, what):
     ref, ref_lse = oracle_mod.tree_attn_rows(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table,
                                              w.seq_lens, w.parents, rows)
     got = np.stack([out[b, i, hq] for b, hq, i in rows])
     got_lse = np.asarray([lse[b, hq, i] for b, hq, i in rows])
-    assert_close(got, ref, what=w.name + " sampled rows")
-    assert_close(got_lse, ref_lse, what=w.name + " sampled lse")
+    assert_close(got, ref, what=what + " sampled rows")
+    assert_close(got_lse, ref_lse, what=what + " sampled lse")
     assert np.isfinite(out).all()
+
+
+@pytest.mark.parametrize("index", [2, 3, 4])
+def test_attn_full_size_sampled_rows(R, oracle_mod, index):
+    # the launch configuration the benchmark times; the oracle checks a stratified sample of output rows
+    w = W.make_config(index)
+    out, lse = run_attn(R, w)
+    rows = stratified_rows(w, np.random.Generator(np.random.PCG64(900 + index)))
+    print("full-size attn:", w.name, len(rows), "rows", flush=True)
+    check_sampled_rows(oracle_mod, w, out, lse, rows, w.name)
+
+
+def test_attn_full_size_head_dim_64_with_256_row_workgroups(R, oracle_mod):
+    # D = 64 on a problem large enough for the planner to pick 256-row workgroups by itself (512 query rows per
+    # kv head, > 1100 workgroup-tiles), ragged lengths, stratified sample of rows
+    rng = np.random.Generator(np.random.PCG64(77))
+    L = [int(x) for x in rng.integers(3000, 5000, size=8)]
+    w = W.make_custom("d64_rows256", B=8, Hq=32, Hkv=4, D=64, T=64, seq_lens=L, tree="trie", depth=8, branch=4, seed=460)
+    print("full-size attn:", w.name, "L", L, flush=True)
+    out, lse = run_attn(R, w)
+    check_sampled_rows(oracle_mod, w, out, lse, stratified_rows(w, rng), w.name)
 
 
 # ------------------------------------------------------------------ device-side input errors
@@ -520,8 +549,8 @@ def check_verify_step_with_the_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, l
 
 @pytest.mark.parametrize("index", [3, 4])
 def test_verify_step_full_size_sampled_rows(R, oracle_mod, index):
-    # the fused step exactly as the benchmark launches it, at the presets' full sizes: sampled attention rows
-    # against the oracle; acceptance, appended rows and new lengths bit for bit (the oracle does those at any size)
+    # the fused step exactly as the benchmark launches it, at the presets' full sizes: a stratified sample of attention
+    # rows against the oracle; acceptance, appended rows and new lengths bit for bit (the oracle does those at any size)
     import torch
     w = W.make_config(index)
     print("full-size fused step:", w.name, flush=True)
@@ -532,18 +561,42 @@ def test_verify_step_full_size_sampled_rows(R, oracle_mod, index):
     torch.cuda.synchronize()
     assert int(dw.status.item()) == 0
     out, lse = bf16_to_np(dw.out), dw.lse.cpu().numpy().astype(np.float64)
-    rng = np.random.Generator(np.random.PCG64(950 + index))
-    n = 64
-    rows = np.stack([rng.integers(0, w.B, n), rng.integers(0, w.Hq, n), rng.integers(0, w.T, n)], axis=1).astype(np.int32)
-    ref, ref_lse = oracle_mod.tree_attn_rows(w.q, w.k_tree, w.v_tree, w.k_cache, w.v_cache, w.page_table,
-                                             w.seq_lens, w.parents, rows)
-    assert_close(np.stack([out[b, i, hq] for b, hq, i in rows]), ref, what=w.name + " fused step, sampled rows")
-    assert_close(np.asarray([lse[b, hq, i] for b, hq, i in rows]), ref_lse, what=w.name + " fused step, sampled lse")
-    assert np.isfinite(out).all()
+    rows = stratified_rows(w, np.random.Generator(np.random.PCG64(950 + index)))
+    check_sampled_rows(oracle_mod, w, out, lse, rows, w.name + " fused step")
     al, path, bonus, kc, vc, sl = oracle_step(oracle_mod, w)
     assert np.array_equal(dw.accept_len.cpu().numpy(), al) and np.array_equal(dw.bonus.cpu().numpy(), bonus)
     assert np.array_equal(dw.path.cpu().numpy(), path) and np.array_equal(dw.seq_lens.cpu().numpy(), sl)
     assert np.array_equal(cache_bits(dw.k_cache), kc) and np.array_equal(cache_bits(dw.v_cache), vc)
+
+
+def test_verify_step_full_size_with_the_tree_rows_in_the_cache(R, oracle_mod):
+    # the batched ragged preset at full size in the in-cache layout: the fused step (attention over the cache,
+    # acceptance, in-place move of the accepted rows); stratified attention rows against the oracle, everything
+    # else bit for bit
+    import torch
+    w = W.make_config(2)
+    print("full-size in-cache fused step:", w.name, flush=True)
+    kc, vc, table = W.place_tree_in_cache(w, seed=11)
+    al, path, bonus = oracle_mod.accept_path(w.draft_tokens, w.target_tokens, w.parents, w.max_path)
+    kc_ref, vc_ref, sl_ref = kc[None].copy(), vc[None].copy(), w.seq_lens.copy()
+    oracle_mod.kv_compact_layers(kc_ref, vc_ref, path, al, table, sl_ref)
+    dw = R.to_device(w)
+    bf16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    dims = R.make_dims(w.B, w.T, w.Hq, w.Hkv, w.D, table.shape[1], w.max_path, kc.shape[0])
+    bound = int(w.seq_lens.max())
+    ws = torch.empty(max(R.reader_workspace_bytes(dims, bound), 256), dtype=torch.uint8, device="cuda")
+    d_kc, d_vc, d_table = bf16(kc), bf16(vc), torch.from_numpy(table).cuda()
+    dw.out.fill_(float("nan"))
+    R.reader_verify_step(dims, dw.q, None, None, d_kc, d_vc, d_table, dw.seq_lens, dw.parents, dw.draft_tokens,
+                         dw.target_tokens, dw.out, dw.lse, dw.accept_len, dw.path, dw.bonus, bound, ws, dw.status)
+    torch.cuda.synchronize()
+    assert int(dw.status.item()) == 0
+    out, lse = bf16_to_np(dw.out), dw.lse.cpu().numpy().astype(np.float64)
+    check_sampled_rows(oracle_mod, w, out, lse, stratified_rows(w, np.random.Generator(np.random.PCG64(961))),
+                       w.name + " in-cache fused step")
+    assert np.array_equal(dw.accept_len.cpu().numpy(), al) and np.array_equal(dw.bonus.cpu().numpy(), bonus)
+    assert np.array_equal(dw.path.cpu().numpy(), path) and np.array_equal(dw.seq_lens.cpu().numpy(), sl_ref)
+    assert np.array_equal(cache_bits(d_kc), kc_ref[0]) and np.array_equal(cache_bits(d_vc), vc_ref[0])
 
 
 def test_two_host_threads_on_their_own_streams(R, oracle_mod):
