@@ -464,6 +464,8 @@ int reader_profile_collect_each(float *ms_each, int32_t capacity, int32_t *launc
  *   READER_TUNE_ATTN_RANGES     >= 1 key ranges asked for (capped at the number of compute units)
  *   READER_TUNE_ATTN_PAIR_COST  0..64 tile times booked per pair start
  *   READER_TUNE_ATTN_AXIS64     1 = cut the ranges in 64-bit arithmetic even where 32 bits suffice
+ *   READER_TUNE_ATTN_WIDE       1 = 256-row workgroups of four wavefronts with 64 rows each (one per SIMD, the
+ *                               accumulation registers managed by hand) instead of eight with 32 rows each
  * Returns READER_OK, or READER_EINVAL for an unknown `which`.
  */
 enum {
@@ -471,7 +473,8 @@ enum {
     READER_TUNE_ATTN_RANGES = 1,
     READER_TUNE_ATTN_PAIR_COST = 2,
     READER_TUNE_ATTN_AXIS64 = 3,
-    READER_TUNE_COUNT_ = 4
+    READER_TUNE_ATTN_WIDE = 4,
+    READER_TUNE_COUNT_ = 5
 };
 int reader_tuning_override(int32_t which, int32_t value);
 

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libreader_hip.so")
-SOURCES = ["reader_api.hip", "trie_drafter.cpp", "tree_shape.cpp", "accept_compact.hip", "kv_compact_layers.hip", "kv_rearrange.hip", "target_argmax.hip", "target_sample.hip", "tree_attn_scalar.hip", "tree_attn_mfma.hip"]
+SOURCES = ["reader_api.hip", "trie_drafter.cpp", "tree_shape.cpp", "accept_compact.hip", "kv_compact_layers.hip", "kv_rearrange.hip", "target_argmax.hip", "target_sample.hip", "tree_attn_scalar.hip", "tree_attn_mfma.hip", "tree_attn_wide.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions
@@ -23,6 +23,8 @@ FLAGS = [
     "-Wall",
     # the LDS-copy inline asm names m0 as clobbered on purpose
     "-Wno-inline-asm",
+    # the wide attention kernel manages the accumulation registers by hand: the compiler must not park values there
+    "-mllvm", "-amdgpu-spill-vgpr-to-agpr=0",
     # per-kernel register and scratch usage as compiler remarks: checked below
     "-Rpass-analysis=kernel-resource-usage",
 ]
@@ -49,6 +51,38 @@ def spilled_kernels(compiler_output: str):
         if m and name and int(m.group(1)) > 0 and scratch > 0:
             found.append((name, int(m.group(1)), scratch))
     return found
+
+
+def foreign_agpr_uses(asm_text: str):
+    """Lines of compiler-generated code (outside inline-asm blocks) that touch an accumulation register.
+
+    tree_attn_wide.hip keeps its output accumulators and query fragments in accumulation registers it names
+    by number in inline asm; the register allocator does not know that, so it must never put anything
+    there itself (a value parked in one would be overwritten, and an overwritten address faults the GPU)."""
+    import re
+    bad, inside = [], False
+    for line in asm_text.splitlines():
+        if "#ASMSTART" in line:
+            inside = True
+        elif "#ASMEND" in line:
+            inside = False
+        elif not inside and not line.lstrip().startswith((";", ".")) and re.search(r"(^|[\s,\[])a(\d+|\[\d+:\d+\])", line):
+            bad.append(line.strip())
+    return bad
+
+
+def check_wide_kernel(hipcc: str, verbose: bool) -> None:
+    cmd = [hipcc] + [f for f in FLAGS if f not in ("-fPIC", "-shared", "-Rpass-analysis=kernel-resource-usage")]
+    cmd += ["--cuda-device-only", "-S", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
+            os.path.join(CSRC, "tree_attn_wide.hip"), "-o", "-"]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc -S of tree_attn_wide.hip failed")
+    bad = foreign_agpr_uses(res.stdout)
+    if bad:
+        raise RuntimeError("the compiler uses accumulation registers of its own in tree_attn_wide.hip: %s" % bad[:5])
+    if verbose:
+        print("tree_attn_wide.hip: accumulation registers are touched by hand-written instructions only")
 
 
 def build(verbose: bool = False) -> str:
@@ -79,6 +113,11 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+    try:
+        check_wide_kernel(hipcc, verbose)
+    except Exception:
+        os.remove(tmp)
+        raise
     os.replace(tmp, LIB)
     return LIB
 

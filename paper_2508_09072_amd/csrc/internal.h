@@ -35,11 +35,14 @@ struct AttnParams {
     float *workspace;  // partial records, see attn_slot_floats() (behind the header, see attn_header_bytes())
     int32_t *pair_info;      // header: per (sequence, kv head) the first and the last workgroup that hold its tiles
     int32_t *range_tiles;    // header: per range workgroup the number of tiles it holds (0: it wrote no record)
+    int32_t *redo;           // header: per workgroup of the wide kernel 1 if its range has to be computed again (kMaxAttnWorkgroups entries)
     int32_t pair_cost;       // what the start of a pair costs a workgroup, in tiles, when the ranges are cut
     int32_t axis32;          // 1: every position of the cost axis times n_ranges fits in an int
     int32_t ranges_shift;    // log2(n_ranges) when it is a power of two (the even cut is then a shift), else -1
     int32_t merge_groups;    // thread groups that share a query row's partial records in the merge: 1, or 4 when pairs are cut into many parts
     int32_t tree_in_cache;   // 1: k_tree / v_tree are null, tree node n of sequence b sits at cache position L_b + n
+    int32_t wide;            // (256 rows per workgroup) 1: four wavefronts of 64 rows, 0: eight of 32
+    int32_t redo_only;       // 1: second pass behind the wide kernel, only the workgroups flagged in `redo` do anything
     int32_t *status;
     int32_t B, T, Hq, Hkv, D, G, M;       // G = Hq/Hkv, M = T*G query rows per (sequence, kv head)
     int32_t max_pages, max_seq_len;
@@ -55,10 +58,13 @@ struct AttnParams {
 // record's own sum), then the rows' running maxima and running sums as fp32.
 __host__ __device__ inline size_t attn_slot_floats(int D, int rows) { return (size_t)rows * (size_t)(D / 2 + 2); }
 
-// The workspace starts with a header the main kernel leaves for the merge kernel: one int per
-// range workgroup (kNumCU of them at most), then two ints per (sequence, kv head).
+// The workspace starts with a header the main kernel leaves for the kernels after it: one int per
+// range workgroup (kNumCU of them at most), one int per workgroup of the 256-row kernels (the
+// "compute again" flags), then two ints per (sequence, kv head).
+constexpr int kMaxRowChunks = 8;                           // ceil(READER_MAX_T * 16 grouped heads / 256 rows)
+constexpr int kMaxAttnWorkgroups = kNumCU * kMaxRowChunks;  // range workgroups x row chunks of the 256-row kernels
 __host__ __device__ inline size_t attn_header_bytes(int B, int Hkv) {
-    return ((size_t)kNumCU * 4 + (size_t)B * (size_t)Hkv * 8 + 255) & ~(size_t)255;
+    return ((size_t)kNumCU * 4 + (size_t)kMaxAttnWorkgroups * 4 + (size_t)B * (size_t)Hkv * 8 + 255) & ~(size_t)255;
 }
 
 // Number of range workgroups the planner picks; a pure function of the dims so that
@@ -72,6 +78,8 @@ struct CompactParams;
 hipError_t launch_tree_attn_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop,
                                  const AcceptParams *ap = nullptr, const CompactParams *cp = nullptr);
 hipError_t launch_tree_attn_scalar(const AttnParams &p, hipStream_t stream);
+// main kernel of the 256-row flavour with four wavefronts of 64 rows (tree_attn_wide.hip); no second launch
+hipError_t launch_tree_attn_wide_main(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 struct AcceptParams {
     const int32_t *draft, *target, *parents;

@@ -16,7 +16,7 @@ namespace reader {
 static char g_error_detail[256] = "";
 
 // Planner overrides set through reader_tuning_override (tests, experiments); -1 = the planner decides.
-static std::atomic<int32_t> g_tuning[READER_TUNE_COUNT_] = {{-1}, {-1}, {-1}, {-1}};
+static std::atomic<int32_t> g_tuning[READER_TUNE_COUNT_] = {{-1}, {-1}, {-1}, {-1}, {-1}};
 static int tuning(int which) { return g_tuning[which].load(std::memory_order_relaxed); }
 
 // The runtime keeps the last error of the calling thread until somebody reads it, whoever caused
@@ -212,7 +212,8 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     p.page_table = page_table; p.seq_lens = seq_lens; p.parents = parents;
     p.out = (uint16_t *)out; p.lse = lse; p.status = status;
     p.range_tiles = (int32_t *)workspace;
-    p.pair_info = workspace ? (int32_t *)((char *)workspace + kNumCU * 4) : nullptr;
+    p.redo = workspace ? (int32_t *)((char *)workspace + kNumCU * 4) : nullptr;
+    p.pair_info = workspace ? (int32_t *)((char *)workspace + kNumCU * 4 + kMaxAttnWorkgroups * 4) : nullptr;
     p.workspace = workspace ? (float *)((char *)workspace + attn_header_bytes(dims->B, dims->Hkv)) : nullptr;
     p.B = dims->B; p.T = dims->T; p.Hq = dims->Hq; p.Hkv = dims->Hkv; p.D = dims->D;
     p.G = dims->Hq / dims->Hkv; p.M = p.T * p.G;
@@ -238,6 +239,8 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     // few pairs, many ranges: a pair is cut into eight parts or more on average, the merge fetches them four abreast
     p.merge_groups = (long long)dims->B * dims->Hkv * 8 <= p.n_ranges ? 4 : 1;
     p.tree_in_cache = tree_in_cache ? 1 : 0;
+    p.wide = p.rows_per_wg == 256 && tuning(READER_TUNE_ATTN_WIDE) == 1 ? 1 : 0;   // (not the default: measured no faster yet)
+    p.redo_only = 0;
     float scale = dims->sm_scale > 0.f ? dims->sm_scale : 1.0f / sqrtf((float)dims->D);
     p.scale_log2 = scale * 1.44269504088896340736f;
     return READER_OK;

@@ -6,6 +6,9 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+#include <utility>
+
 #include "internal.h"
 
 namespace reader {
@@ -411,6 +414,17 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
 // as 4 rows of 16, and lane i receives element i of each row.
 __device__ inline s16x4 lds_read_tr16(const char *ptr) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(ptr));
+}
+
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ...: a loop the compiler sees as straight-line
+// code with compile-time indices (the fixed instruction order of a tile is written with it)
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    static_for_impl(static_cast<F &&>(f), std::make_integer_sequence<int, N>{});
 }
 
 // What a range workgroup knows once it has found its place: its share [lo, hi) of the tile axis, where

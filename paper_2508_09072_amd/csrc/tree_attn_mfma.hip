@@ -104,6 +104,8 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         chunk_id = blockIdx.x / p.n_ranges;
         range_id = blockIdx.x - chunk_id * p.n_ranges;
     }
+    // second pass behind the wide kernel: only the workgroups it asks for (same grid, same ranges)
+    if (!kDma && p.redo_only && !p.redo[blockIdx.x]) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool is_computer = !kDma || wave_s < 4;
@@ -830,8 +832,7 @@ __global__ __launch_bounds__(256) void verify_tail_kernel(AttnParams p, AcceptPa
 }
 
 template <int D, int RB>
-static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop,
-                              const AcceptParams *ap, const CompactParams *cp) {
+static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
     using G = Geometry<D, RB == 4 ? 4 : 8>;
     const size_t pref_bytes = ((size_t)(p.B + 1) * sizeof(int) + 15) & ~(size_t)15;
     const size_t main_lds = (size_t)ring_stages(RB) * G::kStageBytes +
@@ -858,8 +859,12 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
     else
         hipLaunchKernelGGL((tree_attn_mfma_kernel<D, RB>), dim3(p.n_ranges * p.n_row_chunks), dim3(kThreads),
                            main_lds, stream, p, p.page_table, p.seq_lens);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return note_hip_error("launch tree_attn_mfma_kernel", e);
+    return note_hip_error("launch tree_attn_mfma_kernel", hipGetLastError());
+}
+
+// Second launch: merge of the partial records, and in the fused step acceptance and compaction.
+template <int D>
+static hipError_t launch_tail(const AttnParams &p, hipStream_t stream, const AcceptParams *ap, const CompactParams *cp) {
     const int merge_y = p.n_row_chunks * (p.rows_per_wg / (256 / p.merge_groups / (D / 8)));
     if (ap && cp) {
         const int n_merge = p.B * p.Hkv * merge_y;
@@ -872,11 +877,24 @@ static hipError_t launch_mfma(const AttnParams &p, hipStream_t stream, hipEvent_
 
 hipError_t launch_tree_attn_mfma(const AttnParams &p, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop,
                                  const AcceptParams *ap, const CompactParams *cp) {
-    if (p.rows_per_wg == 128)
-        return p.D == 64 ? launch_mfma<64, 4>(p, stream, ev_start, ev_stop, ap, cp)
-                         : launch_mfma<128, 4>(p, stream, ev_start, ev_stop, ap, cp);
-    return p.D == 64 ? launch_mfma<64, 8>(p, stream, ev_start, ev_stop, ap, cp)
-                     : launch_mfma<128, 8>(p, stream, ev_start, ev_stop, ap, cp);
+    hipError_t e;
+    if (p.rows_per_wg == 128) {
+        e = p.D == 64 ? launch_mfma<64, 4>(p, stream, ev_start, ev_stop) : launch_mfma<128, 4>(p, stream, ev_start, ev_stop);
+    } else if (p.wide) {
+        // Four wavefronts of 64 rows with a softmax reference that is fixed per segment; a workgroup whose
+        // scores outgrew that reference says so, and the kernel that moves its reference (eight wavefronts of
+        // 32 rows, same ranges, same records) then computes those workgroups' ranges again.  It is launched
+        // every time and leaves at once where nothing is asked of it.
+        e = launch_tree_attn_wide_main(p, stream, ev_start, ev_stop);
+        if (e != hipSuccess) return e;
+        AttnParams again = p;
+        again.redo_only = 1;
+        e = p.D == 64 ? launch_mfma<64, 8>(again, stream, nullptr, nullptr) : launch_mfma<128, 8>(again, stream, nullptr, nullptr);
+    } else {
+        e = p.D == 64 ? launch_mfma<64, 8>(p, stream, ev_start, ev_stop) : launch_mfma<128, 8>(p, stream, ev_start, ev_stop);
+    }
+    if (e != hipSuccess) return e;
+    return p.D == 64 ? launch_tail<64>(p, stream, ap, cp) : launch_tail<128>(p, stream, ap, cp);
 }
 
 }  // namespace reader

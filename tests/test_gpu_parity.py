@@ -153,11 +153,15 @@ def test_attn_seeded_random_shapes(R, oracle_mod, case):
     check_attn(R, oracle_mod, w, variants=(0,))
 
 
-@pytest.mark.parametrize("rows", [128, 256])
+@pytest.mark.parametrize("rows", [128, 256, 257])
 @pytest.mark.parametrize("T,Hq", [(64, 16), (128, 16), (100, 32)])
 def test_attn_more_than_128_query_rows_both_decompositions(R, oracle_mod, rows, T, Hq, tune):
     # more than 128 query rows per kv head: workgroups of 128 rows (several row chunks per key range) and of
-    # 256 rows must agree with the oracle; the library picks between them by problem size
+    # 256 rows (eight wavefronts of 32 rows, or, "257", four of 64) must agree with the oracle; the library
+    # picks between them by problem size
+    if rows == 257:
+        tune(R.TUNE_ATTN_WIDE, 1)
+        rows = 256
     tune(R.TUNE_ATTN_ROWS, rows)
     w = W.make_custom("rows%d_T%d" % (rows, T), B=3, Hq=Hq, Hkv=4, D=128, T=T, seq_lens=[700, 0, 131], tree="trie",
                       depth=7, seed=407)
@@ -173,10 +177,13 @@ def test_attn_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens):
 
 @pytest.mark.parametrize("T,Hq,D,lens", [(64, 16, 128, [500, 31]), (128, 16, 128, [260, 1500]), (100, 32, 128, [64, 129]),
                                          (128, 8, 64, [300, 5, 0]), (33, 32, 128, [15])])
-def test_attn_tree_rows_in_the_cache_with_256_row_workgroups(R, oracle_mod, T, Hq, D, lens, tune):
+@pytest.mark.parametrize("wide", [0, 1])
+def test_attn_tree_rows_in_the_cache_with_256_row_workgroups(R, oracle_mod, T, Hq, D, lens, wide, tune):
     # the planner picks 256-row workgroups only for large problems; forced here so that their copy loop
-    # (which fetches tree tiles two tiles ahead) meets tree tiles that have to be gathered from the cache
+    # (which fetches tree tiles two tiles ahead) meets tree tiles that have to be gathered from the cache;
+    # both 256-row kernels (eight wavefronts of 32 rows, four of 64)
     tune(R.TUNE_ATTN_ROWS, 256)
+    tune(R.TUNE_ATTN_WIDE, wide)
     check_attn_tree_rows_in_the_cache(R, oracle_mod, T, Hq, D, lens, variants=(0,))
 
 
@@ -272,6 +279,50 @@ def test_attn_full_size_sampled_rows(R, oracle_mod, index):
     rows = stratified_rows(w, np.random.Generator(np.random.PCG64(900 + index)))
     print("full-size attn:", w.name, len(rows), "rows", flush=True)
     check_sampled_rows(oracle_mod, w, out, lse, rows, w.name)
+
+
+@pytest.mark.parametrize("index", [3, 4])
+def test_attn_full_size_sampled_rows_four_wavefronts_of_64_rows(R, oracle_mod, index, tune):
+    # the other 256-row kernel (one wavefront per SIMD, fixed softmax reference, second pass for workgroups
+    # whose scores outgrew it) at the two matrix-bound presets
+    tune(R.TUNE_ATTN_WIDE, 1)
+    w = W.make_config(index)
+    out, lse = run_attn(R, w)
+    rows = stratified_rows(w, np.random.Generator(np.random.PCG64(930 + index)))
+    print("full-size attn, wide kernel:", w.name, len(rows), "rows", flush=True)
+    check_sampled_rows(oracle_mod, w, out, lse, rows, w.name + " wide")
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_attn_seeded_random_shapes_four_wavefronts_of_64_rows(R, oracle_mod, case, tune):
+    tune(R.TUNE_ATTN_ROWS, 256)
+    tune(R.TUNE_ATTN_WIDE, 1)
+    rng = np.random.Generator(np.random.PCG64(9300 + case))
+    D = int(rng.choice([64, 128]))
+    Hkv, G = int(rng.choice([1, 2, 4])), int(rng.choice([4, 8, 16]))
+    T = int(rng.choice([16, 33, 64, 100, 128]))
+    B = int(rng.integers(1, 6))
+    L = [int(x) for x in (rng.integers(0, 700, size=B) if case % 2 else rng.integers(900, 2600, size=B))]
+    w = W.make_custom("randwide%d" % case, B=B, Hq=Hkv * G, Hkv=Hkv, D=D, T=T, seq_lens=L,
+                      tree=str(rng.choice(["trie", "uniform", "chain", "star"])), depth=int(rng.integers(2, 12)),
+                      branch=int(rng.integers(1, 6)), k_outlier_frac=0.05 if case % 3 == 0 else 0.0, seed=9400 + case)
+    check_attn(R, oracle_mod, w, variants=(0,))
+
+
+def test_attn_scores_that_outgrow_the_fixed_reference_are_computed_again(R, oracle_mod, tune):
+    # The four-wavefront kernel fixes a row's softmax reference at the first tile of a segment.  Keys late
+    # in the context that score 2^100 and more above everything before them cannot be held by that; the
+    # workgroups concerned flag it and the second pass (moving reference) has to produce the right rows.
+    tune(R.TUNE_ATTN_ROWS, 256)
+    tune(R.TUNE_ATTN_WIDE, 1)
+    w = W.make_custom("outgrow", B=2, Hq=16, Hkv=2, D=128, T=40, seq_lens=[1500, 900], tree="trie", depth=6, seed=470)
+    # one late key per sequence aligned with every query of the first kv head: q . k large and positive
+    f32 = W.bf16_bits_to_f32
+    for b, pos in ((0, 1400), (1, 700)):
+        page, slot = int(w.page_table[b, pos // 16]), pos % 16
+        w.q[b, :, :8, :] = W.to_bf16_bits(np.abs(f32(w.q[b, :, :8, :])) * 4.0 + 1.0)
+        w.k_cache[page, 0, slot, :] = W.to_bf16_bits(np.full(w.D, 9.0, dtype=np.float32))
+    check_attn(R, oracle_mod, w, variants=(0,))
 
 
 def test_attn_full_size_head_dim_64_with_256_row_workgroups(R, oracle_mod):
