@@ -287,7 +287,8 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
                        ((((db * 4) | c_lo) ^ swizzle_v<D>(key_lo)) << 4) + (i16 & 1) * 8;
     }
 
-    float m_ref[2] = {-INFINITY, -INFINITY}, mc[2] = {0.f, 0.f}, l_run[2] = {0.f, 0.f};   // mc = reference in the exp2 domain
+    float m_ref[2] = {-INFINITY, -INFINITY}, mc[2] = {0.f, 0.f};   // mc = reference in the exp2 domain
+    float lsum[2][2] = {{0.f, 0.f}, {0.f, 0.f}};   // per row block two partial sums of the segment's weights
     bool seg_from_pair_start = false;
     bool overflowed = false;              // a weight came out too large for the fixed reference: this workgroup's work is redone
     const float c2 = p.scale_log2;
@@ -313,86 +314,144 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
     };
     auto p_frag = [&](int kb, int r, int m2) { return __builtin_bit_cast(bf16x8, pk[kb][r][m2]); };
     // weights of scores i, i + 1 of block (kb, r) against the row's reference
-    float lacc[2][2];   // per row block two partial sums of the tile's weights
     auto weight_pair = [&](int kb, int r, int i) {
         const float p0 = __builtin_amdgcn_exp2f(s[kb][r][i] * c2 - mc[r]);
         const float p1 = __builtin_amdgcn_exp2f(s[kb][r][i + 1] * c2 - mc[r]);
-        lacc[r][0] += p0;
-        lacc[r][1] += p1;
+        lsum[r][0] += p0;
+        lsum[r][1] += p1;
         pk[kb][r][i >> 3][(i >> 1) & 3] = pack_bf16x2(p0, p1);
     };
+    // the same one score at a time (the even one is kept until the odd one completes the pair)
+    float p_even = 0.f;
+    auto weight_single = [&](int kb, int r, int i) {
+        // (written out, so that it stays in the slot it is written in: the instruction selector moves
+        // plain arithmetic freely within the unrolled tile, and bunches it up ahead of the matrix work)
+        float x;
+        asm volatile("v_fma_f32 %0, %1, %2, -%3" : "=v"(x) : "v"(s[kb][r][i]), "v"(c2), "v"(mc[r]));
+        const float pi = __builtin_amdgcn_exp2f(x);
+        lsum[r][i & 1] += pi;
+        if (i & 1) pk[kb][r][i >> 3][(i >> 1) & 3] = pack_bf16x2(p_even, pi);
+        else p_even = pi;
+    };
 
-    // A whole prefix tile that is not the first of its segment: no masks, no maxima.  The 64 (D = 128)
-    // matrix instructions of the tile are issued in a fixed order, each followed by its share of the
-    // other work, so that the vector ALU, the LDS reads and the copies run under the matrix pipe:
-    //   slots [0, nQ):  S(kb, r) = K(kb) . Q(r)^T, one accumulator after the other (kb0 r0, kb0 r1, kb1 r0, kb1 r1)
-    //   slots [nQ, nQ + nP):  O(r) += V(kb)^T . P(kb, r)^T in the same order of (kb, r)
-    //   the weights of block (kb, r) are computed, a pair of scores per step, once its scores are
-    //   complete (and the result wait has passed) and are ready two slots before its products start;
-    //   the K fragments of key block 1 and the V fragments of both key blocks are read from LDS into the
-    //   registers their predecessors have just left, some slots ahead of their use; the copies of
-    //   the tile three tiles ahead (with_copy: a whole prefix tile, base addresses kbase / vbase) go first.
-    auto tile_fast = [&](auto with_copy, const char *stage, const char *kbase, const char *vbase, unsigned copy_stage_lds) {
-        constexpr int kK = G::kKSteps, kOB = G::kOBlocks;
-        constexpr int nQ = 4 * kK, nP = 8 * kOB;
-        constexpr int kFirstItem = kK + 4;                  // slot of the first pair of weights
-        constexpr int kLastItemEnd = nQ + 3 * (nP / 4) - 1; // all weights are done before this slot
-        // a block's scores are read no sooner than four slots after its last matrix instruction, and its
-        // weights are complete two slots before its products start
-        static_assert(weight_slot(8, kFirstItem, kLastItemEnd) >= 2 * kK + 4 && weight_slot(16, kFirstItem, kLastItemEnd) >= 3 * kK + 4 &&
-                      weight_slot(24, kFirstItem, kLastItemEnd) >= 4 * kK + 4, "weights start before their scores are there");
-        static_assert(weight_slot(7, kFirstItem, kLastItemEnd) <= nQ - 2 && weight_slot(15, kFirstItem, kLastItemEnd) <= nQ + nP / 4 - 2 &&
-                      weight_slot(23, kFirstItem, kLastItemEnd) <= nQ + nP / 2 - 2 && weight_slot(31, kFirstItem, kLastItemEnd) <= nQ + 3 * nP / 4 - 2,
-                      "weights finish after their products start");
-        bf16x8 kf0[kK], kf1[kK];
-        s16x8 vfa[2 * kOB], vfb[2 * kOB];                   // V^T fragments of key block 0 / 1: [16-key step in the block][output block]
-        lacc[0][0] = lacc[0][1] = lacc[1][0] = lacc[1][1] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < kK; ++kk) kf0[kk] = k_frag(stage, 0, kk);
-        auto v_frag = [&](int ks, int db) {
-            return __builtin_shufflevector(v_half(stage, ks, db, 0), v_half(stage, ks, db, 1), 0, 1, 2, 3, 4, 5, 6, 7);
-        };
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<nQ + nP>([&](auto slot) {
-            constexpr int m = decltype(slot)::value;
-            // ---- the slot's matrix instruction
-            if constexpr (m < nQ) {
-                constexpr int g = m / kK, kb = g >> 1, r = g & 1, kk = m % kK;
-                if constexpr (kk == 0) mfma_s0<Acc::q(r, kk)>(s[kb][r], kb ? kf1[kk] : kf0[kk]);
-                else mfma_s<Acc::q(r, kk)>(s[kb][r], kb ? kf1[kk] : kf0[kk]);
-            } else {
-                constexpr int g = (m - nQ) / (2 * kOB), kb = g >> 1, r = g & 1, j = (m - nQ) % (2 * kOB);
-                mfma_o<Acc::o(r, j % kOB)>(__builtin_bit_cast(bf16x8, kb ? vfb[j] : vfa[j]), p_frag(kb, r, j / kOB));
-            }
-            // ---- copies of the tile three tiles ahead: one per slot from the start
-            if constexpr (decltype(with_copy)::value && m < kCopiesPerTile) {
-                constexpr bool is_v = m >= G::kCopies;
-                constexpr int i = is_v ? m - G::kCopies : m;
-                copy16_uniform(is_v ? vbase : kbase, is_v ? fast_v_off[i] : fast_k_off[i],
-                               copy_stage_lds + (is_v ? G::kTileBytes : 0) + cw * G::kRowsPerWave * G::kRowBytes + i * 1024);
-            }
-            // ---- operand reads: into the registers the fragment used one slot earlier has left
-            if constexpr (m > kK && m <= 2 * kK) kf1[m - kK - 1] = k_frag(stage, 1, m - kK - 1);
-            if constexpr (m >= 2 * kK && m < nQ && (m - 2 * kK) % 2 == 0) {
-                constexpr int f = (m - 2 * kK) / 2;         // fragment f of key block 0: a fragment every other slot
-                vfa[f] = v_frag(f / kOB, f % kOB);
-            }
-            if constexpr (m > nQ + 2 * kOB && m <= nQ + 4 * kOB) {
-                constexpr int f = m - nQ - 2 * kOB - 1;     // fragment f of key block 1
-                vfb[f] = v_frag(2 + f / kOB, f % kOB);
-            }
-            // ---- weights: the pairs that belong to this slot
-            constexpr int j0 = first_weight_in_slot(m, kFirstItem, kLastItemEnd);
-            constexpr int nj = weights_in_slot(m, kFirstItem, kLastItemEnd);
-            static_for<nj>([&](auto item) {
-                constexpr int j = j0 + decltype(item)::value;
-                if constexpr ((j & 7) == 0) asm volatile("s_nop 3");   // (room to spare before the first read of a block's scores)
-                weight_pair(j >> 4, (j >> 3) & 1, (j & 7) * 2);
+    // ---------------------------------------------------------------------------------------------
+    // Whole prefix tiles that do not start a segment (no masks, no maxima) are run as a software
+    // pipeline over two tiles.  A tile is handled in two half steps, one per block of 32 keys; half
+    // step kb of tile t holds, interleaved:
+    //   S(t+1, kb) = K.Q^T        2 kK matrix instructions, into the score registers of key block kb,
+    //                             whose weights were taken in the half step before;
+    //   O += V(t, kb)^T.P(t, kb)^T  4 kOB matrix instructions, with the weights made in the half step before;
+    //   weights of the other key block: of (t, 1) in half step 0, of (t+1, 0) in half step 1, one
+    //                             score per matrix instruction (a wavefront's vector instructions
+    //                             run under its own matrix instructions only in the second half
+    //                             of each, so a slot has room for about four of them).
+    // Every operand fragment is read from LDS once, two groups of four matrix instructions ahead of
+    // its use, and serves both row blocks back to back.
+    auto v_frag = [&](const char *stage, int ks, int db) {
+        return __builtin_shufflevector(v_half(stage, ks, db, 0), v_half(stage, ks, db, 1), 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    // S = K.Q^T of a tile
+    auto scores = [&](const char *stage) {
+        constexpr int kK = G::kKSteps;
+        bf16x8 kf[3][2];
+        kf[0][0] = k_frag(stage, 0, 0); kf[0][1] = k_frag(stage, 1, 0);
+        kf[1][0] = k_frag(stage, 0, 1); kf[1][1] = k_frag(stage, 1, 1);
+        static_for<kK>([&](auto kc) {
+            constexpr int kk = decltype(kc)::value;
+            if constexpr (kk + 2 < kK) { kf[(kk + 2) % 3][0] = k_frag(stage, 0, kk + 2); kf[(kk + 2) % 3][1] = k_frag(stage, 1, kk + 2); }
+            static_for<4>([&](auto gc) {
+                constexpr int kb = decltype(gc)::value >> 1, r = decltype(gc)::value & 1;
+                if constexpr (kk == 0) mfma_s0<Acc::q(r, kk)>(s[kb][r], kf[kk % 3][kb]);
+                else mfma_s<Acc::q(r, kk)>(s[kb][r], kf[kk % 3][kb]);
             });
-            __builtin_amdgcn_sched_barrier(0);
         });
-        l_run[0] += lacc[0][0] + lacc[0][1];
-        l_run[1] += lacc[1][0] + lacc[1][1];
+        READER_RESULT_WAIT();
+    };
+    // O^T += V^T.P^T of a tile whose weights are in pk: a V fragment serves both row blocks
+    auto products = [&](const char *stage) {
+        constexpr int kOB = G::kOBlocks;
+        s16x4 vf[2][kOB][2];
+#pragma unroll
+        for (int db = 0; db < kOB; ++db) { vf[0][db][0] = v_half(stage, 0, db, 0); vf[0][db][1] = v_half(stage, 0, db, 1); }
+        static_for<4>([&](auto kc) {
+            constexpr int ks = decltype(kc)::value;
+            if constexpr (ks + 1 < 4) {
+#pragma unroll
+                for (int db = 0; db < kOB; ++db) {
+                    vf[(ks + 1) & 1][db][0] = v_half(stage, ks + 1, db, 0);
+                    vf[(ks + 1) & 1][db][1] = v_half(stage, ks + 1, db, 1);
+                }
+            }
+            static_for<2 * kOB>([&](auto jc) {
+                constexpr int r = decltype(jc)::value / kOB, db = decltype(jc)::value % kOB;
+                const s16x8 a8 = __builtin_shufflevector(vf[ks & 1][db][0], vf[ks & 1][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                mfma_o<Acc::o(r, db)>(__builtin_bit_cast(bf16x8, a8), p_frag(ks >> 1, r, ks & 1));
+            });
+        });
+    };
+    auto weights_of_key_block = [&](int kb) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) weight_pair(kb, r, i);
+        asm volatile("s_nop 3");   // (weights written by the vector ALU are matrix operands next)
+    };
+
+    // One pipelined tile: products and key-block-1 weights of the tile in `stage`, scores and
+    // key-block-0 weights of the next tile in `next_stage`.  with_copy: the copies of a whole prefix
+    // tile (base addresses kbase / vbase, LDS address copy_stage_lds) are issued on the way, one per
+    // matrix instruction from the start.
+    auto tile_pipelined = [&](auto with_copy, const char *stage, const char *next_stage, const char *kbase, const char *vbase,
+                              unsigned copy_stage_lds) {
+        constexpr int kK = G::kKSteps, kOB = G::kOBlocks;
+        static_assert(kK == 2 * kOB, "a half step has as many score as product instructions");
+        bf16x8 kf[3];
+        s16x8 vf[3];
+        // fragments of group g of half step kb: K rows of key block kb, k-step g; V^T of 16-key step 2 kb + g / kOB, output block g % kOB
+        auto load_group = [&](auto kbc, auto gc) {
+            constexpr int kb = decltype(kbc)::value, g = decltype(gc)::value;
+            kf[(kb * kK + g) % 3] = k_frag(next_stage, kb, g);
+            vf[(kb * kK + g) % 3] = v_frag(stage, 2 * kb + g / kOB, g % kOB);
+        };
+        load_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        load_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<2 * kK>([&](auto gg) {
+            constexpr int kb = decltype(gg)::value / kK, g = decltype(gg)::value % kK;
+            // two groups ahead, into the registers the group before this one has left
+            if constexpr (g + 2 < kK) load_group(std::integral_constant<int, kb>{}, std::integral_constant<int, g + 2>{});
+            else if constexpr (kb == 0) load_group(std::integral_constant<int, 1>{}, std::integral_constant<int, g + 2 - kK>{});
+            static_for<4>([&](auto mc4) {
+                constexpr int m = decltype(mc4)::value, j = g * 4 + m;      // slot j of 4 kK in this half step
+                // Half step 0: P S P S (the first K fragment is the last to arrive); half step 1: S S P P.  Either
+                // way the last score instruction of row block 0 is followed by two more matrix instructions
+                // before the half step ends: the vector ALU of the next half step starts with exactly those
+                // scores, and a result needs 11 issue slots after its instruction before it may be read.
+                constexpr bool is_p = kb == 0 ? (m & 1) == 0 : m >= 2;
+                constexpr int r = kb == 0 ? m >> 1 : m & 1;
+                constexpr int w3 = (kb * kK + g) % 3;                        // this group's place in the window of three
+                if constexpr (is_p) {
+                    mfma_o<Acc::o(r, g % kOB)>(__builtin_bit_cast(bf16x8, vf[w3]), p_frag(kb, r, g / kOB));
+                } else {
+                    if constexpr (g == 0) mfma_s0<Acc::q(r, g)>(s[kb][r], kf[w3]);
+                    else mfma_s<Acc::q(r, g)>(s[kb][r], kf[w3]);
+                }
+                if constexpr (decltype(with_copy)::value && kb == 0 && j < kCopiesPerTile) {
+                    constexpr bool is_v = j >= G::kCopies;
+                    constexpr int i = is_v ? j - G::kCopies : j;
+                    copy16_uniform(is_v ? vbase : kbase, is_v ? fast_v_off[i] : fast_k_off[i],
+                                   copy_stage_lds + (is_v ? G::kTileBytes : 0) + cw * G::kRowsPerWave * G::kRowBytes + i * 1024);
+                }
+                // weights of the other key block (of the next tile in half step 1), 32 scores over 4 kK slots
+                constexpr int lo = j * 32 / (4 * kK), hi = (j + 1) * 32 / (4 * kK);
+                static_for<hi - lo>([&](auto ic) {
+                    constexpr int e = lo + decltype(ic)::value;
+                    weight_single(1 - kb, e / 16, e % 16);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
     };
 
     // Any tile, one step after the other: scores, masks, (first tile of a segment) row maxima,
@@ -403,21 +462,7 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
         const bool first = (flags & kDescFresh) != 0;
         const int tt = flags >> 8;
         const int holes = (flags & kDescHoles) ? (flags >> 8) & 15 : 0;   // quarters of a prefix tile to skip
-        {
-            bf16x8 kf[3][2];
-            kf[0][0] = k_frag(stage, 0, 0); kf[0][1] = k_frag(stage, 1, 0);
-            kf[1][0] = k_frag(stage, 0, 1); kf[1][1] = k_frag(stage, 1, 1);
-            static_for<kK>([&](auto kc) {
-                constexpr int kk = decltype(kc)::value;
-                if constexpr (kk + 2 < kK) { kf[(kk + 2) % 3][0] = k_frag(stage, 0, kk + 2); kf[(kk + 2) % 3][1] = k_frag(stage, 1, kk + 2); }
-                static_for<4>([&](auto gc) {
-                    constexpr int kb = decltype(gc)::value >> 1, r = decltype(gc)::value & 1;
-                    if constexpr (kk == 0) mfma_s0<Acc::q(r, kk)>(s[kb][r], kf[kk % 3][kb]);
-                    else mfma_s<Acc::q(r, kk)>(s[kb][r], kf[kk % 3][kb]);
-                });
-            });
-        }
-        READER_RESULT_WAIT();
+        scores(stage);
 
         // keep(kb, r, i): does score i of block (kb, r) belong to a key this row attends to
         auto softmax = [&](auto &&keep) {
@@ -440,12 +485,10 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
                     m_ref[r] = holes ? fmaxf(mx, -1e30f) : mx;
                     mc[r] = (m_ref[r] == -INFINITY) ? 0.f : m_ref[r] * c2;
                 }
-                lacc[r][0] = lacc[r][1] = 0.f;
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int i = 0; i < 16; i += 2) weight_pair(kb, r, i);
-                l_run[r] += lacc[r][0] + lacc[r][1];
             }
         };
         if (is_tree) {
@@ -457,34 +500,19 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
             // score i of a block is key (i / 4) * 8 + 4 h + i % 4 of its 32 keys (the 4 h is shifted out above)
             softmax([&](int kb, int r, int i) { return ((bits[kb][r] >> ((i >> 2) * 8 + (i & 3))) & 1u) != 0; });
         } else if (n_valid < kTile || holes) {
+            // score i of block kb is key kb * 32 + (i / 4) * 8 + 4 h + i % 4; the lane's part of that is made here,
+            // out of the compiler's sight, or 64 key numbers would wait in registers through the whole main loop
+            int lim = n_valid - 4 * h;
+            asm volatile("" : "+v"(lim));
             softmax([&](int kb, int, int i) {
-                const int key = kb * 32 + (i >> 2) * 8 + 4 * h + (i & 3);
-                return key < n_valid && !((holes >> (kb * 2 + (i >> 3))) & 1);
+                return kb * 32 + (i >> 2) * 8 + (i & 3) < lim && !((holes >> (kb * 2 + (i >> 3))) & 1);
             });
         } else {
             softmax([](int, int, int) { return true; });
         }
         asm volatile("s_nop 3");   // (weights written by the vector ALU are matrix operands next)
 
-        // ---- O^T += V^T . P^T: a V fragment serves both row blocks; the weights are the B operand ----
-        s16x4 vf[2][kOB][2];
-#pragma unroll
-        for (int db = 0; db < kOB; ++db) { vf[0][db][0] = v_half(stage, 0, db, 0); vf[0][db][1] = v_half(stage, 0, db, 1); }
-        static_for<4>([&](auto kc) {
-            constexpr int ks = decltype(kc)::value;
-            if constexpr (ks + 1 < 4) {
-#pragma unroll
-                for (int db = 0; db < kOB; ++db) {
-                    vf[(ks + 1) & 1][db][0] = v_half(stage, ks + 1, db, 0);
-                    vf[(ks + 1) & 1][db][1] = v_half(stage, ks + 1, db, 1);
-                }
-            }
-            static_for<2 * kOB>([&](auto jc) {
-                constexpr int r = decltype(jc)::value / kOB, db = decltype(jc)::value % kOB;
-                const s16x8 a8 = __builtin_shufflevector(vf[ks & 1][db][0], vf[ks & 1][db][1], 0, 1, 2, 3, 4, 5, 6, 7);
-                mfma_o<Acc::o(r, db)>(__builtin_bit_cast(bf16x8, a8), p_frag(ks >> 1, r, ks & 1));
-            });
-        });
+        products(stage);
     };
 
     auto reset_state = [&](int flags) {
@@ -493,7 +521,7 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
         for (int r = 0; r < 2; ++r) {
             m_ref[r] = -INFINITY;
             mc[r] = 0.f;
-            l_run[r] = 0.f;
+            lsum[r][0] = lsum[r][1] = 0.f;
         }
         static_for<2 * G::kOBlocks * 16>([&](auto ic) { acc_zero<decltype(ic)::value>(); });   // the output accumulators
     };
@@ -506,7 +534,8 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
         static_for<2>([&](auto rc) {
             constexpr int R = decltype(rc)::value;
             const int r = R;
-            const float l_tot = l_run[r] + __shfl_xor(l_run[r], 32);
+            const float l_mine = lsum[r][0] + lsum[r][1];
+            const float l_tot = l_mine + __shfl_xor(l_mine, 32);
             if (__any(!(l_tot < kTooLarge))) overflowed = true;   // (also an infinite or undefined sum)
             const bool whole = seg_from_pair_start && pair_ends;
             const float inv = whole ? 1.f / l_tot : (l_tot > 0.f ? 1.f / l_tot : 0.f);   // (a row may see no key of a part)
@@ -552,70 +581,97 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
         }
     };
 
-    // descriptor words of the tile to compute (rows, flags) and of the tile to copy, read one iteration
-    // ahead so that the LDS latency hides behind the barrier
+    // descriptor words (rows, flags) of the tile to compute and of the one after it, and of the tile to copy,
+    // read ahead so that the LDS latency hides behind the barrier
     int2 d_cur = *reinterpret_cast<const int2 *>(&desc_of(0)->n_valid);
+    int2 d_nxt = *reinterpret_cast<const int2 *>(&desc_of(1)->n_valid);
     int2 d_cpy = *reinterpret_cast<const int2 *>(&desc_of(kS - 1)->n_valid);
     int d_blk = desc_of(kS - 1)->blk[cw];
-    for (int it = 0; it < n_iter; ++it) {
-        const char *stage = ring + (it % kS) * G::kStageBytes;
-        const int t_valid = __builtin_amdgcn_readfirstlane(d_cur.x);
-        const int t_flags = __builtin_amdgcn_readfirstlane(d_cur.y);
+    auto is_whole = [](int valid, int flags) { return valid == kTile && !(flags & (kDescTree | kDescFresh | kDescHoles)); };
+
+    // What every iteration starts with, whichever tile code follows: wait for the tiles, barrier, the tile
+    // list, the copies of the tile three ahead (unless they go inside a pipelined tile).
+    struct Iter {
+        int t_valid, t_flags;          // the tile to compute
+        int c_blk;                     // first page block of the tile to copy (this wavefront's rows), or -1
+        unsigned copy_stage_lds;
+        bool last_iter, pair_ends, whole, pipelined, copy_inside;
+    };
+    auto begin_iteration = [&](int it) {
+        Iter I;
+        I.t_valid = __builtin_amdgcn_readfirstlane(d_cur.x);
+        I.t_flags = __builtin_amdgcn_readfirstlane(d_cur.y);
+        const int n_valid = __builtin_amdgcn_readfirstlane(d_nxt.x);
+        const int n_flags = __builtin_amdgcn_readfirstlane(d_nxt.y);
         const int c_valid = __builtin_amdgcn_readfirstlane(d_cpy.x);
         const int c_flags = __builtin_amdgcn_readfirstlane(d_cpy.y);
-        const int c_blk = __builtin_amdgcn_readfirstlane(d_blk);
-        const bool last_iter = it + 1 == n_iter;
-        const bool pair_ends = (t_flags & kDescPairEnd) != 0;
+        I.c_blk = __builtin_amdgcn_readfirstlane(d_blk);
+        I.last_iter = it + 1 == n_iter;
+        I.pair_ends = (I.t_flags & kDescPairEnd) != 0;
 
-        // this wavefront's copies of tile `it` have landed once at most those of the tiles after it
-        // (up to kS - 2 of them) are outstanding
-        const int ahead = n_iter - 1 - it;
-        if (ahead >= kS - 2) wait_vmcnt<(kS - 2) * kCopiesPerTile>();
-        else if (ahead == 1) wait_vmcnt<kCopiesPerTile>();
+        // Tiles up to it + 1 have to be complete in LDS (the pipelined tile code reads the next tile's K):
+        // this wavefront's copies of them have landed once at most those of tile it + 2 are outstanding.
+        if (it + 2 < n_iter) wait_vmcnt<kCopiesPerTile>();
         else wait_vmcnt<0>();
-        __syncthreads();   // tile `it` is complete in LDS; every wavefront is done with tile it - 1
+        __syncthreads();   // tiles it and it + 1 are complete in LDS; every wavefront is done with tile it - 1
 
-        d_cur = *reinterpret_cast<const int2 *>(&desc_of(it + 1)->n_valid);
+        d_cur = d_nxt;
+        d_nxt = *reinterpret_cast<const int2 *>(&desc_of(it + 2)->n_valid);
         d_cpy = *reinterpret_cast<const int2 *>(&desc_of(it + kS)->n_valid);
         d_blk = desc_of(it + kS)->blk[cw];
         extend_list(it);
 
         // Tile it + kS - 1 goes into the stage that tile it - 1 has left.  A whole prefix tile copied
-        // behind a tile that takes the fast path has its copy instructions spread over that tile's
-        // first matrix instructions; every other tile is asked for here.
+        // behind a pipelined tile has its copy instructions spread over that tile's matrix instructions;
+        // every other tile is asked for here.
         const bool copy_next = it + kS - 1 < n_iter;
-        const unsigned copy_stage_lds = ring_lds + ((it + kS - 1) % kS) * G::kStageBytes;
-        const bool fast = wave_active && t_valid == kTile && !(t_flags & (kDescTree | kDescFresh | kDescHoles));
-        const bool whole_next = c_blk >= 0 && !(c_flags & kDescTree) && (cw + 1) * G::kRowsPerWave <= c_valid;
-        const bool copy_inside = copy_next && fast && whole_next;
-        if (copy_next && !copy_inside) issue_tile(c_blk, c_valid, c_flags, copy_stage_lds);
+        I.copy_stage_lds = ring_lds + ((it + kS - 1) % kS) * G::kStageBytes;
+        I.whole = is_whole(I.t_valid, I.t_flags);
+        I.pipelined = wave_active && I.whole && !I.last_iter && is_whole(n_valid, n_flags);
+        const bool whole_next = I.c_blk >= 0 && !(c_flags & kDescTree) && (cw + 1) * G::kRowsPerWave <= c_valid;
+        I.copy_inside = copy_next && I.pipelined && whole_next;
+        if (copy_next && !I.copy_inside) issue_tile(I.c_blk, c_valid, c_flags, I.copy_stage_lds);
+        if (I.pair_ends && !I.last_iter) prefetch_q(desc_b(it + 1), desc_hkv(it + 1));
+        return I;
+    };
+    auto stage_of = [&](int it) { return ring + (it % kS) * G::kStageBytes; };
 
-        if (t_flags & kDescFresh) {
-            reset_state(t_flags);
+    for (int it = 0; it < n_iter; ++it) {
+        Iter I = begin_iteration(it);
+        if (I.t_flags & kDescFresh) {
+            reset_state(I.t_flags);
             const int sb = desc_b(it);
             if (it != 0) load_q(sb, desc_hkv(it));
             // ancestor-or-self masks of this sequence's tree, if this segment reaches its tree tiles
-            if (t_flags & kDescMasks) {
+            if (I.t_flags & kDescMasks) {
                 if (tid < p.T) s_par[tid] = p.parents[(size_t)sb * p.T + tid];
                 __syncthreads();
                 build_masks();
                 __syncthreads();
             }
         }
-        if (pair_ends && !last_iter) prefetch_q(desc_b(it + 1), desc_hkv(it + 1));
-
-        if (wave_active) {
-            if (fast) {
-                const size_t boff = (size_t)(c_blk >= 0 ? c_blk : 0) * (16 * G::kRowBytes);
+        if (!wave_active) continue;
+        if (!I.whole) {
+            tile_plain(stage_of(it), I.t_flags, I.t_valid);
+        } else {
+            // A run of whole tiles.  All but its last tile are pipelined, in a loop of their own: the
+            // registers of scores and weights then pass from tile to tile without meeting another path
+            // (where paths meet, the compiler moves every one of them into place with a copy).
+            scores(stage_of(it));
+            weights_of_key_block(0);
+            while (I.pipelined) {
+                const size_t boff = (size_t)(I.c_blk >= 0 ? I.c_blk : 0) * (16 * G::kRowBytes);
                 const char *kbase = reinterpret_cast<const char *>(p.k_cache) + boff;
                 const char *vbase = reinterpret_cast<const char *>(p.v_cache) + boff;
-                if (copy_inside) tile_fast(std::true_type{}, stage, kbase, vbase, copy_stage_lds);
-                else tile_fast(std::false_type{}, stage, kbase, vbase, copy_stage_lds);
-            } else {
-                tile_plain(stage, t_flags, t_valid);
+                if (I.copy_inside) tile_pipelined(std::true_type{}, stage_of(it), stage_of(it + 1), kbase, vbase, I.copy_stage_lds);
+                else tile_pipelined(std::false_type{}, stage_of(it), stage_of(it + 1), kbase, vbase, I.copy_stage_lds);
+                ++it;
+                I = begin_iteration(it);    // (a whole tile that starts no segment: nothing else to prepare)
             }
-            if (pair_ends || last_iter) finish_segment(it, pair_ends);
+            weights_of_key_block(1);
+            products(stage_of(it));
         }
+        if (I.pair_ends || I.last_iter) finish_segment(it, I.pair_ends);
     }
 
     // one word per workgroup, written every time: 1 asks for this workgroup's range to be computed again
