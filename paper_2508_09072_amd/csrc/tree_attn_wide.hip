@@ -58,6 +58,15 @@ struct AccMap {
     static constexpr int o(int r, int db) { return (r * kOB + db) * 16; }
     static constexpr int q(int r, int kk) { return 2 * kOB * 16 + (r * kK + kk) * 4; }
     static constexpr int kCount = 2 * kOB * 16 + 2 * kK * 4;   // 192 (D = 128), 96 (D = 64)
+    // ... and per-lane values that are needed once per tile or per segment, kept out of the vector
+    // registers the pipelined tile code needs for itself (one instruction brings one back):
+    static constexpr int kParked = kCount;
+    static constexpr int node(int r) { return kParked + r; }            // tree node of the lane's row in row block r
+    static constexpr int group(int r) { return kParked + 2 + r; }       // ... and its query head within the kv head
+    static constexpr int m_ref(int r) { return kParked + 4 + r; }       // the row's softmax reference (a score, not yet scaled)
+    static constexpr int k_off(int i) { return kParked + 6 + i; }       // byte offsets of the lane's part of copy i of a whole prefix tile (K, V)
+    static constexpr int v_off(int i) { return kParked + 6 + D / 32 + i; }
+    static constexpr int kEnd = kParked + 6 + 2 * (D / 32);
 };
 // Nothing here is known to the compiler as a matrix instruction, so the waits the hardware leaves to software
 // are the caller's business: a result is read by the vector ALU (v_accvgpr_read, or any instruction on a
@@ -79,6 +88,11 @@ template <int I> __device__ __forceinline__ float acc_read() {
     asm volatile("v_accvgpr_read_b32 %0, a%c1" : "=v"(x) : "n"(I));
     return x;
 }
+template <int I> __device__ __forceinline__ uint32_t acc_read_u32() {
+    uint32_t x;
+    asm volatile("v_accvgpr_read_b32 %0, a%c1" : "=v"(x) : "n"(I));
+    return x;
+}
 #define READER_RESULT_WAIT() asm volatile("s_nop 15")   /* 16 wait states: matrix result -> vector ALU */
 }  // namespace
 
@@ -93,8 +107,9 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
 
     using Acc = AccMap<D>;
     // (for the kernel's register count: the accumulation registers up to the last one used by hand)
-    if constexpr (D == 128) asm volatile("" ::: "a0", "a191");
-    else asm volatile("" ::: "a0", "a95");
+    static_assert(AccMap<128>::kEnd == 206 && AccMap<64>::kEnd == 106, "the register count below is the map's last register");
+    if constexpr (D == 128) asm volatile("" ::: "a0", "a205");
+    else asm volatile("" ::: "a0", "a105");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     char *ring = smem;                                                               // [kS][kStageBytes]
@@ -126,16 +141,19 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
     const int n = lane & 31, h = lane >> 5;
     const int chunk_base = chunk_id * kWideRows;
     // the two row blocks of this wavefront
-    int row_local[2], node[2], group[2];
+    int row_local[2];
     bool row_real[2];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
+    static_for<2>([&](auto rc) {
+        constexpr int r = decltype(rc)::value;
         row_local[r] = wave_s * 64 + r * 32 + n;
         const int m_row = chunk_base + row_local[r];
         row_real[r] = m_row < p.M;
-        node[r] = row_real[r] ? m_row / p.G : 0;
-        group[r] = row_real[r] ? m_row - node[r] * p.G : 0;
-    }
+        const int node = row_real[r] ? m_row / p.G : 0;
+        acc_write<Acc::node(r)>((uint32_t)node);
+        acc_write<Acc::group(r)>((uint32_t)(row_real[r] ? m_row - node * p.G : 0));
+    });
+    auto node_of = [](auto rc) { return (int)acc_read_u32<Acc::node(decltype(rc)::value)>(); };
+    auto group_of = [](auto rc) { return (int)acc_read_u32<Acc::group(decltype(rc)::value)>(); };
     const bool wave_active = chunk_base + wave_s * 64 < p.M;
 
     RangeSetup rs;
@@ -172,7 +190,7 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
     auto load_q = [&](int b, int hkv) {
         static_for<2>([&](auto rc) {
             constexpr int r = decltype(rc)::value;
-            const uint16_t *qrow = p.q + (((size_t)b * p.T + node[r]) * p.Hq + hkv * p.G + group[r]) * D;
+            const uint16_t *qrow = p.q + (((size_t)b * p.T + node_of(rc)) * p.Hq + hkv * p.G + group_of(rc)) * D;
             u32x4 w[G::kKSteps];
 #pragma unroll
             for (int kk = 0; kk < G::kKSteps; ++kk) w[kk] = keep_if(row_real[r], ld16(qrow + kk * 16 + h * 8));
@@ -189,12 +207,12 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
     // touch the next pair's query rows one tile before they are needed, so that they wait in the
     // cache: an LDS copy of 4 bytes per lane into a scratch area nobody reads
     auto prefetch_q = [&](int b, int hkv) {
-#pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const uint16_t *qrow = p.q + (((size_t)b * p.T + node[r]) * p.Hq + hkv * p.G + group[r]) * D;
-            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off"
-                         :: "v"(qrow + (h * 64) % D), "s"(prefetch_lds) : "memory", "m0");
-        }
+        static_for<2>([&](auto rc) {
+            const uint16_t *qrow = p.q + (((size_t)b * p.T + node_of(rc)) * p.Hq + hkv * p.G + group_of(rc)) * D;
+            const uint16_t *src = qrow + (h * 64) % D;
+            const unsigned dst = prefetch_lds;
+            asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" :: "v"(src), "s"(dst) : "memory", "m0");
+        });
     };
 
     auto build_masks = [&]() {
@@ -219,11 +237,13 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
     // Per-lane byte offsets of the copies of a whole prefix tile (the common case, issued from inside the
     // tile code); everything else about a lane's copies is made again whenever a tile needs it, so that
     // it does not sit in registers through the main loop.
-    unsigned fast_k_off[G::kCopies], fast_v_off[G::kCopies];
     {
         const CopyLane<D, CW> cl0 = make_copy_lane<D, CW>(p, cw, lane);
-#pragma unroll
-        for (int i = 0; i < G::kCopies; ++i) { fast_k_off[i] = cl0.k_cache_off[i]; fast_v_off[i] = cl0.v_cache_off[i]; }
+        static_for<G::kCopies>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            acc_write<Acc::k_off(i)>(cl0.k_cache_off[i]);
+            acc_write<Acc::v_off(i)>(cl0.v_cache_off[i]);
+        });
     }
     // Copies of this wavefront's 16 rows of a tile into the stage at LDS byte address stage_lds:
     // exactly kCopiesPerTile copy instructions, whatever the tile looks like.
@@ -287,7 +307,7 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
                        ((((db * 4) | c_lo) ^ swizzle_v<D>(key_lo)) << 4) + (i16 & 1) * 8;
     }
 
-    float m_ref[2] = {-INFINITY, -INFINITY}, mc[2] = {0.f, 0.f};   // mc = reference in the exp2 domain
+    float mc[2] = {0.f, 0.f};   // the rows' softmax references in the exp2 domain (the references themselves are parked)
     float lsum[2][2] = {{0.f, 0.f}, {0.f, 0.f}};   // per row block two partial sums of the segment's weights
     bool seg_from_pair_start = false;
     bool overflowed = false;              // a weight came out too large for the fixed reference: this workgroup's work is redone
@@ -321,17 +341,36 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
         lsum[r][1] += p1;
         pk[kb][r][i >> 3][(i >> 1) & 3] = pack_bf16x2(p0, p1);
     };
-    // the same one score at a time (the even one is kept until the odd one completes the pair)
-    float p_even = 0.f;
-    auto weight_single = [&](int kb, int r, int i) {
+    // The weights of pipelined tiles are made one per matrix instruction slot, and as a pipeline of their own,
+    // so that no instruction of a slot waits for another of the same slot: slot e takes the exponential
+    // of the argument made in slot e - 1, makes the argument of weight e + 1, adds weight e - 1 to its
+    // row's sum and, when e is even, packs weights e - 2 and e - 1.  Between slots:
+    float w_x = 0.f;             // argument of the exponential of the slot's own weight
+    float w_p1 = 0.f, w_p2 = 0.f;   // the weights of one and two slots ago
+    auto weight_arg = [&](float score, float ref) {
         // (written out, so that it stays in the slot it is written in: the instruction selector moves
         // plain arithmetic freely within the unrolled tile, and bunches it up ahead of the matrix work)
         float x;
-        asm volatile("v_fma_f32 %0, %1, %2, -%3" : "=v"(x) : "v"(s[kb][r][i]), "v"(c2), "v"(mc[r]));
-        const float pi = __builtin_amdgcn_exp2f(x);
-        lsum[r][i & 1] += pi;
-        if (i & 1) pk[kb][r][i >> 3][(i >> 1) & 3] = pack_bf16x2(p_even, pi);
-        else p_even = pi;
+        asm volatile("v_fma_f32 %0, %1, %2, -%3" : "=v"(x) : "v"(score), "v"(c2), "v"(ref));
+        return x;
+    };
+    // Slot e (0..31) of the half step that computes the weights of key block wkb; the block before it in
+    // this order is the other key block (of the same tile for wkb = 1, of the tile before for wkb = 0).
+    auto weight_slot = [&](auto wkbc, auto ec) {
+        constexpr int wkb = decltype(wkbc)::value, e = decltype(ec)::value;
+        const float p_cur = __builtin_amdgcn_exp2f(w_x);
+        // the next argument: score e + 1 of this block, or score 0 of the other one (complete by now: its last
+        // matrix instruction was issued at least two matrix instructions ago)
+        constexpr int nb = e == 31 ? 1 - wkb : wkb, ne = (e + 1) & 31;
+        w_x = weight_arg(s[nb][ne / 16][ne % 16], mc[ne / 16]);
+        constexpr int pe = (e + 31) & 31;                     // the weight of one slot ago
+        lsum[pe / 16][pe & 1] += w_p1;
+        if constexpr ((e & 1) == 0) {
+            constexpr int pb = e == 0 ? 1 - wkb : wkb, p2 = (e + 30) & 31, r = p2 / 16, i = p2 % 16;
+            pk[pb][r][i >> 3][(i >> 1) & 3] = pack_bf16x2(w_p2, w_p1);
+        }
+        w_p2 = w_p1;
+        w_p1 = p_cur;
     };
 
     // ---------------------------------------------------------------------------------------------
@@ -397,11 +436,27 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
             for (int i = 0; i < 16; i += 2) weight_pair(kb, r, i);
         asm volatile("s_nop 3");   // (weights written by the vector ALU are matrix operands next)
     };
+    // Start of a run of whole tiles: the weights of key block 0, left the way slot 31 of a pipelined tile leaves them
+    // (the last weight not yet added to its sum, the last pair not yet packed, the next argument made).
+    auto begin_run = [&]() {
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+#pragma unroll
+            for (int i = 0; i < (r == 0 ? 16 : 14); i += 2) weight_pair(0, r, i);
+        w_p2 = __builtin_amdgcn_exp2f(s[0][1][14] * c2 - mc[1]);
+        w_p1 = __builtin_amdgcn_exp2f(s[0][1][15] * c2 - mc[1]);
+        lsum[1][0] += w_p2;
+        w_x = weight_arg(s[1][0][0], mc[0]);
+    };
+    // End of a run: what slot 0 of a further pipelined tile would have done with key block 0
+    auto end_run = [&]() {
+        lsum[1][1] += w_p1;
+        pk[0][1][1][3] = pack_bf16x2(w_p2, w_p1);
+    };
 
     // One pipelined tile: products and key-block-1 weights of the tile in `stage`, scores and
     // key-block-0 weights of the next tile in `next_stage`.  with_copy: the copies of a whole prefix
-    // tile (base addresses kbase / vbase, LDS address copy_stage_lds) are issued on the way, one per
-    // matrix instruction from the start.
+    // tile (base addresses kbase / vbase, LDS address copy_stage_lds) are issued on the way.
     auto tile_pipelined = [&](auto with_copy, const char *stage, const char *next_stage, const char *kbase, const char *vbase,
                               unsigned copy_stage_lds) {
         constexpr int kK = G::kKSteps, kOB = G::kOBlocks;
@@ -425,9 +480,9 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
             static_for<4>([&](auto mc4) {
                 constexpr int m = decltype(mc4)::value, j = g * 4 + m;      // slot j of 4 kK in this half step
                 // Half step 0: P S P S (the first K fragment is the last to arrive); half step 1: S S P P.  Either
-                // way the last score instruction of row block 0 is followed by two more matrix instructions
-                // before the half step ends: the vector ALU of the next half step starts with exactly those
-                // scores, and a result needs 11 issue slots after its instruction before it may be read.
+                // way the last score instruction of row block 0 is followed by at least two more matrix
+                // instructions before the vector ALU, in the last slot of the half step, reads the first of those
+                // scores: a result needs 11 issue slots after its instruction before it may be read.
                 constexpr bool is_p = kb == 0 ? (m & 1) == 0 : m >= 2;
                 constexpr int r = kb == 0 ? m >> 1 : m & 1;
                 constexpr int w3 = (kb * kK + g) % 3;                        // this group's place in the window of three
@@ -437,18 +492,22 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
                     if constexpr (g == 0) mfma_s0<Acc::q(r, g)>(s[kb][r], kf[w3]);
                     else mfma_s<Acc::q(r, g)>(s[kb][r], kf[w3]);
                 }
-                if constexpr (decltype(with_copy)::value && kb == 0 && j < kCopiesPerTile) {
-                    constexpr bool is_v = j >= G::kCopies;
-                    constexpr int i = is_v ? j - G::kCopies : j;
-                    copy16_uniform(is_v ? vbase : kbase, is_v ? fast_v_off[i] : fast_k_off[i],
-                                   copy_stage_lds + (is_v ? G::kTileBytes : 0) + cw * G::kRowsPerWave * G::kRowBytes + i * 1024);
+                // Copies of the tile three ahead: spread evenly over the tile, so that the copy instructions reach
+                // the memory pipeline as a trickle: issued together they fill its queue, and a wavefront that
+                // waits there issues no matrix instructions either.
+                if constexpr (decltype(with_copy)::value) {
+                    constexpr int J = kb * 4 * kK + j, kSpacing = 8 * kK / kCopiesPerTile;
+                    if constexpr (J % kSpacing == 1) {
+                        constexpr int c = J / kSpacing;
+                        constexpr bool is_v = c >= G::kCopies;
+                        constexpr int i = is_v ? c - G::kCopies : c;
+                        copy16_uniform(is_v ? vbase : kbase, acc_read_u32<is_v ? Acc::v_off(i) : Acc::k_off(i)>(),
+                                       copy_stage_lds + (is_v ? G::kTileBytes : 0) + cw * G::kRowsPerWave * G::kRowBytes + i * 1024);
+                    }
                 }
                 // weights of the other key block (of the next tile in half step 1), 32 scores over 4 kK slots
                 constexpr int lo = j * 32 / (4 * kK), hi = (j + 1) * 32 / (4 * kK);
-                static_for<hi - lo>([&](auto ic) {
-                    constexpr int e = lo + decltype(ic)::value;
-                    weight_single(1 - kb, e / 16, e % 16);
-                });
+                static_for<hi - lo>([&](auto ic) { weight_slot(std::integral_constant<int, 1 - kb>{}, std::integral_constant<int, lo + decltype(ic)::value>{}); });
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
@@ -482,8 +541,10 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
                     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
                     mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
                     // (a row whose every key was skipped because of bad page ids gets a finite, very low reference)
-                    m_ref[r] = holes ? fmaxf(mx, -1e30f) : mx;
-                    mc[r] = (m_ref[r] == -INFINITY) ? 0.f : m_ref[r] * c2;
+                    const float ref = holes ? fmaxf(mx, -1e30f) : mx;
+                    if (r == 0) acc_write<Acc::m_ref(0)>(__float_as_uint(ref));
+                    else acc_write<Acc::m_ref(1)>(__float_as_uint(ref));
+                    mc[r] = (ref == -INFINITY) ? 0.f : ref * c2;
                 }
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
@@ -493,10 +554,12 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
         };
         if (is_tree) {
             uint32_t bits[2][2];
+            static_for<2>([&](auto rc) {
+                constexpr int r = decltype(rc)::value;
+                const int nd = node_of(rc);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 2; ++r) bits[kb][r] = (row_real[r] ? s_anc[node[r] * 4 + tt * 2 + kb] : 0u) >> (4 * h);
+                for (int kb = 0; kb < 2; ++kb) bits[kb][r] = (row_real[r] ? s_anc[nd * 4 + tt * 2 + kb] : 0u) >> (4 * h);
+            });
             // score i of a block is key (i / 4) * 8 + 4 h + i % 4 of its 32 keys (the 4 h is shifted out above)
             softmax([&](int kb, int r, int i) { return ((bits[kb][r] >> ((i >> 2) * 8 + (i & 3))) & 1u) != 0; });
         } else if (n_valid < kTile || holes) {
@@ -519,7 +582,8 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
         seg_from_pair_start = (flags & kDescPairStart) != 0;
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
-            m_ref[r] = -INFINITY;
+            if (r == 0) acc_write<Acc::m_ref(0)>(__float_as_uint(-INFINITY));
+            else acc_write<Acc::m_ref(1)>(__float_as_uint(-INFINITY));
             mc[r] = 0.f;
             lsum[r][0] = lsum[r][1] = 0.f;
         }
@@ -539,7 +603,9 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
             if (__any(!(l_tot < kTooLarge))) overflowed = true;   // (also an infinite or undefined sum)
             const bool whole = seg_from_pair_start && pair_ends;
             const float inv = whole ? 1.f / l_tot : (l_tot > 0.f ? 1.f / l_tot : 0.f);   // (a row may see no key of a part)
-            uint16_t *orow = p.out + (((size_t)e_b * p.T + node[r]) * p.Hq + e_hkv * p.G + group[r]) * D;
+            const int nd = node_of(rc), gr = group_of(rc);
+            const float ref = __uint_as_float(acc_read_u32<Acc::m_ref(R)>());
+            uint16_t *orow = p.out + (((size_t)e_b * p.T + nd) * p.Hq + e_hkv * p.G + gr) * D;
             const size_t slot = ((size_t)(2 * range_id + (seg_from_pair_start ? 1 : 0)) * p.n_row_chunks + chunk_id);
             float *rec = p.workspace + slot * attn_slot_floats(D, kWideRows);
             u32x4 *rec16 = reinterpret_cast<u32x4 *>(rec);
@@ -564,11 +630,10 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
             });
             if (whole) {
                 if (row_real[r] && p.lse && h == 0)
-                    p.lse[((size_t)e_b * p.Hq + e_hkv * p.G + group[r]) * p.T + node[r]] =
-                        (m_ref[r] * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
+                    p.lse[((size_t)e_b * p.Hq + e_hkv * p.G + gr) * p.T + nd] = (ref * c2 + __builtin_amdgcn_logf(l_tot)) * kLn2;
             } else if (h == 0) {
                 float *ml = rec + (size_t)kWideRows * (D / 2);
-                ml[row_local[r]] = m_ref[r] * c2;
+                ml[row_local[r]] = ref * c2;
                 ml[kWideRows + row_local[r]] = l_tot;
             }
         });
@@ -658,7 +723,7 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
             // registers of scores and weights then pass from tile to tile without meeting another path
             // (where paths meet, the compiler moves every one of them into place with a copy).
             scores(stage_of(it));
-            weights_of_key_block(0);
+            begin_run();
             while (I.pipelined) {
                 const size_t boff = (size_t)(I.c_blk >= 0 ? I.c_blk : 0) * (16 * G::kRowBytes);
                 const char *kbase = reinterpret_cast<const char *>(p.k_cache) + boff;
@@ -668,6 +733,7 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
                 ++it;
                 I = begin_iteration(it);    // (a whole tile that starts no segment: nothing else to prepare)
             }
+            end_run();
             weights_of_key_block(1);
             products(stage_of(it));
         }
