@@ -464,8 +464,9 @@ int reader_profile_collect_each(float *ms_each, int32_t capacity, int32_t *launc
  *   READER_TUNE_ATTN_RANGES     >= 1 key ranges asked for (capped at the number of compute units)
  *   READER_TUNE_ATTN_PAIR_COST  0..64 tile times booked per pair start
  *   READER_TUNE_ATTN_AXIS64     1 = cut the ranges in 64-bit arithmetic even where 32 bits suffice
- *   READER_TUNE_ATTN_WIDE       1 = 256-row workgroups of four wavefronts with 64 rows each (one per SIMD, the
- *                               accumulation registers managed by hand) instead of eight with 32 rows each
+ *   READER_TUNE_ATTN_WIDE       which kernel 256-row workgroups run: 1 = four wavefronts with 64 rows each (one per
+ *                               SIMD, the accumulation registers managed by hand), 0 = eight with 32 rows each;
+ *                               the planner takes the first at head dimension 128 and the second at 64
  * Returns READER_OK, or READER_EINVAL for an unknown `which`.
  */
 enum {

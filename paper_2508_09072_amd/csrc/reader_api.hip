@@ -239,7 +239,10 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     // few pairs, many ranges: a pair is cut into eight parts or more on average, the merge fetches them four abreast
     p.merge_groups = (long long)dims->B * dims->Hkv * 8 <= p.n_ranges ? 4 : 1;
     p.tree_in_cache = tree_in_cache ? 1 : 0;
-    p.wide = p.rows_per_wg == 256 && tuning(READER_TUNE_ATTN_WIDE) == 1 ? 1 : 0;   // (not the default: measured no faster yet)
+    // 256-row workgroups: four wavefronts of 64 rows at head dimension 128 (measured 2 to 4 % faster than eight of
+    // 32 rows at the two matrix-bound presets), eight of 32 at head dimension 64 (measured: no difference)
+    const int wide = tuning(READER_TUNE_ATTN_WIDE);
+    p.wide = p.rows_per_wg == 256 && (wide == 1 || (wide < 0 && dims->D == 128)) ? 1 : 0;
     p.redo_only = 0;
     float scale = dims->sm_scale > 0.f ? dims->sm_scale : 1.0f / sqrtf((float)dims->D);
     p.scale_log2 = scale * 1.44269504088896340736f;

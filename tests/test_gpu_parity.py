@@ -159,9 +159,8 @@ def test_attn_more_than_128_query_rows_both_decompositions(R, oracle_mod, rows, 
     # more than 128 query rows per kv head: workgroups of 128 rows (several row chunks per key range) and of
     # 256 rows (eight wavefronts of 32 rows, or, "257", four of 64) must agree with the oracle; the library
     # picks between them by problem size
-    if rows == 257:
-        tune(R.TUNE_ATTN_WIDE, 1)
-        rows = 256
+    tune(R.TUNE_ATTN_WIDE, 1 if rows == 257 else 0)
+    rows = min(rows, 256)
     tune(R.TUNE_ATTN_ROWS, rows)
     w = W.make_custom("rows%d_T%d" % (rows, T), B=3, Hq=Hq, Hkv=4, D=128, T=T, seq_lens=[700, 0, 131], tree="trie",
                       depth=7, seed=407)
@@ -281,22 +280,25 @@ def test_attn_full_size_sampled_rows(R, oracle_mod, index):
     check_sampled_rows(oracle_mod, w, out, lse, rows, w.name)
 
 
+@pytest.mark.parametrize("wide", [0, 1])
 @pytest.mark.parametrize("index", [3, 4])
-def test_attn_full_size_sampled_rows_four_wavefronts_of_64_rows(R, oracle_mod, index, tune):
-    # the other 256-row kernel (one wavefront per SIMD, fixed softmax reference, second pass for workgroups
-    # whose scores outgrew it) at the two matrix-bound presets
-    tune(R.TUNE_ATTN_WIDE, 1)
+def test_attn_full_size_sampled_rows_either_256_row_kernel(R, oracle_mod, index, wide, tune):
+    # both 256-row kernels by name at the two matrix-bound presets: eight wavefronts of 32 rows (moving softmax
+    # reference), and four of 64 rows (one per SIMD, fixed reference, second pass for workgroups whose scores
+    # outgrew it), whichever of them the planner would take
+    tune(R.TUNE_ATTN_WIDE, wide)
     w = W.make_config(index)
     out, lse = run_attn(R, w)
     rows = stratified_rows(w, np.random.Generator(np.random.PCG64(930 + index)))
-    print("full-size attn, wide kernel:", w.name, len(rows), "rows", flush=True)
-    check_sampled_rows(oracle_mod, w, out, lse, rows, w.name + " wide")
+    print("full-size attn, 256-row kernel", wide, ":", w.name, len(rows), "rows", flush=True)
+    check_sampled_rows(oracle_mod, w, out, lse, rows, w.name + " kernel %d" % wide)
 
 
+@pytest.mark.parametrize("wide", [0, 1])
 @pytest.mark.parametrize("case", range(8))
-def test_attn_seeded_random_shapes_four_wavefronts_of_64_rows(R, oracle_mod, case, tune):
+def test_attn_seeded_random_shapes_either_256_row_kernel(R, oracle_mod, case, wide, tune):
     tune(R.TUNE_ATTN_ROWS, 256)
-    tune(R.TUNE_ATTN_WIDE, 1)
+    tune(R.TUNE_ATTN_WIDE, wide)
     rng = np.random.Generator(np.random.PCG64(9300 + case))
     D = int(rng.choice([64, 128]))
     Hkv, G = int(rng.choice([1, 2, 4])), int(rng.choice([4, 8, 16]))
