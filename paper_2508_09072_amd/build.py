@@ -15,6 +15,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libreader_hip.so")
+# the same library with per-workgroup time stamps in the 128-row attention kernel (python -m ...build --stamps;
+# used by wg_timeline.py only)
+STAMPS_LIB = os.path.join(HERE, "libreader_hip_stamps.so")
 SOURCES = ["reader_api.hip", "trie_drafter.cpp", "tree_shape.cpp", "accept_compact.hip", "kv_compact_layers.hip", "kv_rearrange.hip", "target_argmax.hip", "target_sample.hip", "tree_attn_scalar.hip", "tree_attn_mfma.hip", "tree_attn_wide.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -85,10 +88,11 @@ def check_wide_kernel(hipcc: str, verbose: bool) -> None:
         print("tree_attn_wide.hip: accumulation registers are touched by hand-written instructions only")
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, stamps: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + FLAGS + ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+    lib = STAMPS_LIB if stamps else LIB
+    tmp = lib + ".tmp.%d" % os.getpid()
+    cmd = [hipcc] + FLAGS + (["-DREADER_WG_STAMPS"] if stamps else []) + ["-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
     cmd += [os.path.join(CSRC, s) for s in SOURCES] + ["-o", tmp]
     if verbose:
         print(" ".join(cmd))
@@ -118,9 +122,9 @@ def build(verbose: bool = False) -> str:
     except Exception:
         os.remove(tmp)
         raise
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, stamps="--stamps" in sys.argv))

@@ -36,6 +36,9 @@ struct AttnParams {
     int32_t *pair_info;      // header: per (sequence, kv head) the first and the last workgroup that hold its tiles
     int32_t *range_tiles;    // header: per range workgroup the number of tiles it holds (0: it wrote no record)
     int32_t *redo;           // header: per workgroup of the wide kernel 1 if its range has to be computed again (kMaxAttnWorkgroups entries)
+#ifdef READER_WG_STAMPS
+    long long *stamps;       // profiling build only: kWgStamps time stamps per workgroup (100 MHz counter), or null
+#endif
     int32_t pair_cost;       // what the start of a pair costs a workgroup, in tiles, when the ranges are cut
     int32_t axis32;          // 1: every position of the cost axis times n_ranges fits in an int
     int32_t ranges_shift;    // log2(n_ranges) when it is a power of two (the even cut is then a shift), else -1
@@ -61,6 +64,26 @@ __host__ __device__ inline size_t attn_slot_floats(int D, int rows) { return (si
 // The workspace starts with a header the main kernel leaves for the kernels after it: one int per
 // range workgroup (kNumCU of them at most), one int per workgroup of the 256-row kernels (the
 // "compute again" flags), then two ints per (sequence, kv head).
+#ifdef READER_WG_STAMPS
+// What a workgroup of the 128-row attention kernel records in the profiling build (thread 0 of a
+// computing wavefront, or of a copying one where noted): the constant-rate counter at each point.
+enum WgStamp {
+    kStampEntry = 0,        // kernel entry
+    kStampRange = 1,        // share of the tile axis known
+    kStampList = 2,         // tile list written
+    kStampFirstIssue = 3,   // (copying wavefront) the first two key tiles are asked for
+    kStampFirstItem = 4,    // first item complete in LDS
+    kStampFirstTile = 5,    // first key tile computed
+    kStampLastTile = 6,     // last item done
+    kStampExit = 7,         // after the last record / output row is written
+    kStampCopyReady = 8,    // (copying wavefront) per-lane copy constants made, nothing asked for yet
+    kStampItem0Issued = 9,  // (copying wavefront) the first key tile is asked for
+    kStampLoopWait = 10,    // (copying wavefront, iteration 8) at the top of the iteration, before the wait for its copies
+    kStampLoopIssue = 11,   // ... past the barrier, about to ask for the item three ahead
+    kStampLoopIssued = 12,  // ... that item asked for
+    kWgStamps = 13
+};
+#endif
 constexpr int kMaxRowChunks = 8;                           // ceil(READER_MAX_T * 16 grouped heads / 256 rows)
 constexpr int kMaxAttnWorkgroups = kNumCU * kMaxRowChunks;  // range workgroups x row chunks of the 256-row kernels
 __host__ __device__ inline size_t attn_header_bytes(int B, int Hkv) {

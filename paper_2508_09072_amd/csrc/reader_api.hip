@@ -17,6 +17,9 @@ static char g_error_detail[256] = "";
 
 // Planner overrides set through reader_tuning_override (tests, experiments); -1 = the planner decides.
 static std::atomic<int32_t> g_tuning[READER_TUNE_COUNT_] = {{-1}, {-1}, {-1}, {-1}, {-1}};
+#ifdef READER_WG_STAMPS
+static std::atomic<long long *> g_wg_stamps{nullptr};
+#endif
 static int tuning(int which) { return g_tuning[which].load(std::memory_order_relaxed); }
 
 // The runtime keeps the last error of the calling thread until somebody reads it, whoever caused
@@ -161,6 +164,15 @@ extern "C" const char *reader_strerror(int code) {
 
 extern "C" const char *reader_last_error_detail(void) { return g_error_detail; }
 
+#ifdef READER_WG_STAMPS
+// Profiling build only (not declared in the public header): device buffer of kWgStamps 64-bit stamps per
+// workgroup of the attention main kernel, at least 2048 workgroups; null switches the stamps off.
+extern "C" int reader_profile_wg_stamps(void *device_buffer) {
+    g_wg_stamps.store(static_cast<long long *>(device_buffer), std::memory_order_relaxed);
+    return READER_OK;
+}
+#endif
+
 extern "C" int reader_tuning_override(int32_t which, int32_t value) {
     if (which < 0 || which >= READER_TUNE_COUNT_) return READER_EINVAL;
     g_tuning[which].store(value < 0 ? -1 : value, std::memory_order_relaxed);
@@ -244,6 +256,9 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     const int wide = tuning(READER_TUNE_ATTN_WIDE);
     p.wide = p.rows_per_wg == 256 && (wide == 1 || (wide < 0 && dims->D == 128)) ? 1 : 0;
     p.redo_only = 0;
+#ifdef READER_WG_STAMPS
+    p.stamps = g_wg_stamps.load(std::memory_order_relaxed);
+#endif
     float scale = dims->sm_scale > 0.f ? dims->sm_scale : 1.0f / sqrtf((float)dims->D);
     p.scale_log2 = scale * 1.44269504088896340736f;
     return READER_OK;

@@ -67,6 +67,17 @@ namespace reader {
 //        them into ancestor masks, and extend the tile list, all ahead of the computation,
 //        so that a computing wavefront never waits on a memory counter inside the loop.
 //   RB = 8: every wavefront computes and copies its share of each tile.
+// Profiling build (-DREADER_WG_STAMPS): thread `who` of the workgroup notes the time at point k
+#ifdef READER_WG_STAMPS
+#define READER_STAMP(k, who)                                                                              \
+    do {                                                                                                  \
+        if (p.stamps && threadIdx.x == (who))                                                             \
+            p.stamps[(size_t)blockIdx.x * kWgStamps + (k)] = (long long)__builtin_amdgcn_s_memrealtime(); \
+    } while (0)
+#else
+#define READER_STAMP(k, who) do { } while (0)
+#endif
+
 template <int D, int RB>
 __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                                                                     const int32_t *__restrict__ page_table,
@@ -106,6 +117,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     }
     // second pass behind the wide kernel: only the workgroups it asks for (same grid, same ranges)
     if (!kDma && p.redo_only && !p.redo[blockIdx.x]) return;
+    READER_STAMP(kStampEntry, 0);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
     const bool is_computer = !kDma || wave_s < 4;
@@ -134,6 +146,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     const int n_tiles = hi.flat - lo.flat;
     if (chunk_id == 0 && tid == 0) p.range_tiles[range_id] = n_tiles;
     if (n_tiles <= 0) return;
+    READER_STAMP(kStampRange, 0);
     // items of the list: the tiles, and with dedicated copy wavefronts one query unit per segment
     // (one segment per pair the range touches)
     int n_iter = n_tiles;
@@ -148,6 +161,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     if (htid >= 0)
         for (int i = htid; i < min(n_iter, kDescSlots); i += kHelpers) write_item(i);
     __syncthreads();   // the list is written
+    READER_STAMP(kStampList, 0);
 
     // (off the path to the first copy: with dedicated copy wavefronts the computing ones do it, which wait anyway)
     write_pair_info(p, s_pref, lo, hi, range_id, tid);
@@ -176,6 +190,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     // RB = 4: a query unit.  The copying wavefronts move the pair's query rows into a ring
     // stage (rows swizzled like a K tile, rows past the last one as zeros); the computing
     // wavefronts read their fragments from there.
+    const float g_rcp = 1.0f / (float)p.G;
     auto issue_q = [&](int b, int hkv, unsigned stage_lds) {
         const char *qbase = reinterpret_cast<const char *>(p.q) + ((size_t)b * p.T * p.Hq + hkv * p.G) * (D * 2);
         const char *zeros = reinterpret_cast<const char *>(kZeroRow) + (lane & 15) * 16;
@@ -184,7 +199,10 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             const int r = (cw * kCopiesPerTile + i) * G::kRowsPerCopy + lane / G::kChunks;
             const int c = (lane % G::kChunks) ^ swizzle_k<D>(r);
             const int m = chunk_base + r;                  // query row inside the pair
-            const int nd = m / p.G, gr = m - nd * p.G;
+            // m / G without the integer division (sixteen of them per query unit held the first copies back
+            // by a microsecond): m + 0.5 is at least 0.5 / G away from the next multiple of G, far more
+            // than the rounding of the product moves it (m / G <= 128)
+            const int nd = (int)(((float)m + 0.5f) * g_rcp), gr = m - nd * p.G;
             const char *src = m < p.M ? qbase + ((size_t)nd * p.Hq + gr) * (D * 2) + c * 16 : zeros;
             copy16_lane(src, stage_lds + (cw * kCopiesPerTile + i) * 1024);
         }
@@ -287,16 +305,23 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     // prologue: the first kS - 1 items are put in flight
     if (is_copier) {
         const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
+        READER_STAMP(kStampCopyReady, kDma ? 256 : 0);
         if (kDma) {
 #pragma unroll
-            for (int i = 0; i < kS - 1; ++i)
+            // (item 0, the first pair's query unit, is not copied: the computing wavefronts, idle until the
+            // first tile arrives, read their rows straight into registers meanwhile, and the first
+            // K/V tiles are asked for that much sooner)
+            for (int i = 1; i < kS - 1; ++i) {
                 if (i < n_iter) issue_item(cl, i, ring_lds + i * G::kStageBytes);
+                if (i == 1) READER_STAMP(kStampItem0Issued, 256);
+            }
         } else {
             issue_tile_at(cl, 0, ring_lds);
             if (n_iter > 1) issue_tile_at(cl, 1, ring_lds + G::kStageBytes);
         }
     }
-    if (!kDma) load_q(desc_b(0), desc_hkv(0));
+    READER_STAMP(kStampFirstIssue, kDma ? 256 : 0);
+    if (!kDma || wave_active) load_q(desc_b(0), desc_hkv(0));
 
     // per-lane LDS offsets of the matrix-core operand reads (relative to the stage)
     int k_rd[G::kKSteps];   // K fragment of k-step kk, key block 0
@@ -574,6 +599,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             // This wavefront's part of item `it` has landed once at most its copies of the items
             // after it are outstanding (copies complete in the order they were issued).
             const int ahead = n_iter - 1 - it;
+            if (it == 8) READER_STAMP(kStampLoopWait, 256);
             if (ahead >= kS - 2) wait_vmcnt<(kS - 2) * kCopiesPerTile>();
             else if (ahead == 1) wait_vmcnt<kCopiesPerTile>();
             else wait_vmcnt<0>();
@@ -586,7 +612,9 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             n_flags = desc_flags(it + 2);
 
             // item it + kS - 1 goes into the stage that item it - 1 has left
+            if (it == 8) READER_STAMP(kStampLoopIssue, 256);
             if (it + kS - 1 < n_iter) issue_item(cl, it + kS - 1, ring_lds + ((it + kS - 1) % kS) * G::kStageBytes);
+            if (it == 8) READER_STAMP(kStampLoopIssued, 256);
         }
     } else if (kDma) {
         // ---------------- wavefronts that only compute (RB = 4) ----------------
@@ -598,10 +626,12 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             const bool last_iter = it + 1 == n_iter;
             const bool pair_ends = (t_flags & kDescPairEnd) != 0;
             __syncthreads();   // item `it` is complete in LDS
+            if (it == 0) READER_STAMP(kStampFirstItem, 0);
+            if (it == 2) READER_STAMP(kStampFirstTile, 0);   // (item 0 is the query unit: item 1, the first key tile, is done)
             d_cur = *reinterpret_cast<const int2 *>(&desc_of(it + 1)->n_valid);
 
             if (t_flags & kDescQ) {
-                if (wave_active) read_q_stage(stage);
+                if (wave_active && it > 0) read_q_stage(stage);   // (the first one was read from memory before the loop)
                 continue;
             }
             if (t_flags & kDescFresh) {
@@ -610,6 +640,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             }
             if (wave_active) {
                 compute_tile(stage, t_flags, t_valid, [](int) {});
+                if (last_iter) READER_STAMP(kStampLastTile, 0);
                 if (pair_ends || last_iter) finish_segment(it, pair_ends);
             }
         }
@@ -635,6 +666,8 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
 
             if (!last_iter) wait_vmcnt<kCopiesPerTile>(); else wait_vmcnt<0>();
             __syncthreads();   // tile `it` is complete in LDS; every wavefront is done with tile it - 1
+            if (it == 0) READER_STAMP(kStampFirstItem, 0);
+            if (it == 1) READER_STAMP(kStampFirstTile, 0);
 
             d_cur = *reinterpret_cast<const int2 *>(&desc_of(it + 1)->n_valid);
             d_cpy = *reinterpret_cast<const int2 *>(&desc_of(it + 3)->n_valid);
@@ -678,6 +711,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                 if (wave_s >= 4) copy_all();
                 compute_tile(stage, t_flags, t_valid, [](int) {});
                 if (wave_s < 4) copy_all();
+                if (last_iter) READER_STAMP(kStampLastTile, 0);
                 if (pair_ends || last_iter) finish_segment(it, pair_ends);
             } else {
                 copy_all();
@@ -686,6 +720,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         }
     }
 
+    READER_STAMP(kStampExit, 0);
     if (p.status && bad) atomicOr(p.status, bad);
 }
 
