@@ -192,12 +192,16 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     // wavefronts read their fragments from there.
     const float g_rcp = 1.0f / (float)p.G;
     auto issue_q = [&](int b, int hkv, unsigned stage_lds) {
+        // (the lane's part of the addresses is made here, once per pair, out of the compiler's sight: made ahead
+        // of the loop it stands between the start of the kernel and the first copy of a key tile)
+        int ql = lane;
+        asm volatile("" : "+v"(ql));
         const char *qbase = reinterpret_cast<const char *>(p.q) + ((size_t)b * p.T * p.Hq + hkv * p.G) * (D * 2);
-        const char *zeros = reinterpret_cast<const char *>(kZeroRow) + (lane & 15) * 16;
+        const char *zeros = reinterpret_cast<const char *>(kZeroRow) + (ql & 15) * 16;
 #pragma unroll
         for (int i = 0; i < kCopiesPerTile; ++i) {
-            const int r = (cw * kCopiesPerTile + i) * G::kRowsPerCopy + lane / G::kChunks;
-            const int c = (lane % G::kChunks) ^ swizzle_k<D>(r);
+            const int r = (cw * kCopiesPerTile + i) * G::kRowsPerCopy + ql / G::kChunks;
+            const int c = (ql % G::kChunks) ^ swizzle_k<D>(r);
             const int m = chunk_base + r;                  // query row inside the pair
             // m / G without the integer division (sixteen of them per query unit held the first copies back
             // by a microsecond): m + 0.5 is at least 0.5 / G away from the next multiple of G, far more
@@ -594,26 +598,56 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
     if (kDma && is_copier) {
         // ---------------- wavefronts that only move data (RB = 4) ----------------
         const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
-        int n_flags = desc_flags(1);   // flags of item it + 1
+        // Between two barriers this wavefront has one item to ask for, and how long that takes sets the
+        // pace of a workgroup whenever memory is not the limit (short contexts, the first tiles of any
+        // launch): the words of the item's descriptor are therefore read one iteration ahead, so
+        // that nothing here waits for LDS, and a whole prefix tile (the common item) is asked for
+        // with eight copy instructions and nothing else.
+        int n_flags = desc_flags(1);        // flags of item it + 1
+        int flags_2 = desc_flags(2);        // flags of item it + 2
+        int d_blk = desc_of(kS - 1)->blk[cw];                                       // of item it + kS - 1,
+        int2 d_nf = *reinterpret_cast<const int2 *>(&desc_of(kS - 1)->n_valid);    // the next one to ask for
         for (int it = 0; it < n_iter; ++it) {
             // This wavefront's part of item `it` has landed once at most its copies of the items
             // after it are outstanding (copies complete in the order they were issued).
             const int ahead = n_iter - 1 - it;
+            const int c_blk = __builtin_amdgcn_readfirstlane(d_blk);
+            const int c_valid = __builtin_amdgcn_readfirstlane(d_nf.x);
+            const int c_flags = __builtin_amdgcn_readfirstlane(d_nf.y);
             if (it == 8) READER_STAMP(kStampLoopWait, 256);
             if (ahead >= kS - 2) wait_vmcnt<(kS - 2) * kCopiesPerTile>();
             else if (ahead == 1) wait_vmcnt<kCopiesPerTile>();
             else wait_vmcnt<0>();
             __syncthreads();   // item `it` is complete in LDS; every wavefront is done with item it - 1
 
+            d_blk = desc_of(it + kS)->blk[cw];
+            d_nf = *reinterpret_cast<const int2 *>(&desc_of(it + kS)->n_valid);
             extend_list(it);
             // masks of a segment that starts with the next item (its parent pointers were asked
             // for before copies this wavefront has just waited for)
             if (ahead >= 1 && (n_flags & kDescMasks)) { build_masks(gen_bld & 1); ++gen_bld; }
-            n_flags = desc_flags(it + 2);
+            n_flags = flags_2;
+            flags_2 = c_flags;
 
             // item it + kS - 1 goes into the stage that item it - 1 has left
             if (it == 8) READER_STAMP(kStampLoopIssue, 256);
-            if (it + kS - 1 < n_iter) issue_item(cl, it + kS - 1, ring_lds + ((it + kS - 1) % kS) * G::kStageBytes);
+            if (it + kS - 1 < n_iter) {
+                const unsigned stage_lds = ring_lds + ((it + kS - 1) % kS) * G::kStageBytes;
+                const bool plain = !(c_flags & (kDescQ | kDescMasks | kDescTree)) && c_blk >= 0 &&
+                                   (cw + 1) * G::kRowsPerWave <= c_valid;
+                if (plain) {
+                    const size_t boff = (size_t)c_blk * (16 * G::kRowBytes);
+                    const char *kb = reinterpret_cast<const char *>(p.k_cache) + boff;
+                    const char *vb = reinterpret_cast<const char *>(p.v_cache) + boff;
+                    const unsigned dst = stage_lds + cw * G::kRowsPerWave * G::kRowBytes;
+#pragma unroll
+                    for (int i = 0; i < G::kCopies; ++i) copy16_uniform(kb, cl.k_cache_off[i], dst + i * 1024);
+#pragma unroll
+                    for (int i = 0; i < G::kCopies; ++i) copy16_uniform(vb, cl.v_cache_off[i], dst + G::kTileBytes + i * 1024);
+                } else {
+                    issue_item(cl, it + kS - 1, stage_lds);
+                }
+            }
             if (it == 8) READER_STAMP(kStampLoopIssued, 256);
         }
     } else if (kDma) {

@@ -96,6 +96,8 @@ def main():
         name = STAMP_NAMES[i]
         v = rel[:, :, i]
         v = v[v >= 0]
+        if v.size == 0:                 # (a point no workgroup reached: fewer than nine iterations)
+            continue
         print("%-38s %8.2f %8.2f %8.2f %8.2f %8.2f" % (name, v.min(), np.percentile(v, 10), np.median(v),
                                                         np.percentile(v, 90), v.max()))
     tiles = ranges[:n_wg].astype(np.float64) if n_wg <= 256 else None
