@@ -38,7 +38,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 ROTATE_BYTES = 512 << 20       # K/V copies cycled per step so the 256 MB Infinity Cache cannot serve the stream
 CALIBRATION_BYTES = 256 << 20  # size of the plain elementwise pass the counter runs are scaled by
 SETTLE_MS = 60.0               # untimed load in front of every timed region
-TRAFFIC_FILE = os.path.join(ROOT, "profiles", "tree_attn_mfma_kernel_hbm_traffic.txt")
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "tree_attn_hbm_traffic_all_presets.txt")
 
 
 def log(*a):
@@ -130,7 +130,11 @@ def roofline_of(w, each):
     else:
         roof = {"bound": "mfma", "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": tflops / MFMA_BF16_PEAK_TFLOPS}
-    roof.update({"kernel": "tree_attn_mfma_kernel", "kernel_ms": kernel_ms, "launches_timed": n,
+    from paper_2508_09072_amd import binding as R
+    plan = R.reader_attn_plan(R.make_dims(w.B, w.T, w.Hq, w.Hkv, w.D, w.max_pages, w.max_path, w.num_pages),
+                              int(w.seq_lens.max()))
+    roof.update({"kernel": plan["kernel"], "workgroups": plan["key_ranges"] * plan["row_chunks"],
+                 "rows_per_workgroup": plan["rows_per_workgroup"], "kernel_ms": kernel_ms, "launches_timed": n,
                  "kernel_ms_median": float(np.median(each)) if n else None,
                  "kernel_ms_min": float(each.min()) if n else None,
                  "algorithmic_bytes": alg_bytes, "algorithmic_flops": flops, "hbm_gbs": gbs,

@@ -122,6 +122,29 @@ int reader_validate_tree(const int32_t *parents_host, int32_t B, int32_t T);
 size_t reader_workspace_bytes(const reader_dims *dims, int32_t max_seq_len);
 
 /*
+ * How reader_tree_attn would run these dims when no sequence is longer than max_seq_len: which of its
+ * kernels, how many query rows a workgroup carries, into how many chunks the rows of a (sequence, kv head)
+ * pair are cut, and how many ranges of key tiles the launch has (workgroups = key_ranges * row_chunks).
+ * For benchmarks and profiles that name the kernel they time; the choice follows Section 3.2's
+ * memory-bound / compute-bound distinction (few query rows: stream K/V with dedicated copy wavefronts;
+ * many: all wavefronts on the matrix cores).  Pure host function; honours reader_tuning_override.
+ * READER_OK, or the error reader_tree_attn would return for the dims.
+ */
+enum reader_attn_kernel {
+    READER_ATTN_KERNEL_SCALAR = 0,          /* dims->variant = 1: the scalar reference kernel */
+    READER_ATTN_KERNEL_ROWS128 = 1,         /* tree_attn_mfma_kernel<D, 4>: 128 rows, 4 computing + 4 copying wavefronts */
+    READER_ATTN_KERNEL_ROWS256_WAVES8 = 2,  /* tree_attn_mfma_kernel<D, 8>: 256 rows, 8 wavefronts of 32 rows */
+    READER_ATTN_KERNEL_ROWS256_WAVES4 = 3   /* tree_attn_wide_kernel<D>: 256 rows, 4 wavefronts of 64 rows */
+};
+typedef struct reader_attn_plan_t {
+    int32_t kernel;                /* enum reader_attn_kernel */
+    int32_t rows_per_workgroup;    /* 128 or 256 (0 for the scalar kernel) */
+    int32_t row_chunks;
+    int32_t key_ranges;
+} reader_attn_plan_t;
+int reader_attn_plan(const reader_dims *dims, int32_t max_seq_len, reader_attn_plan_t *plan);
+
+/*
  * Tree-masked attention (Section 3.2; Appendix C invariant 2).
  * For every sequence b, query head hq and tree node i:
  *     out[b,i,hq,:] = sum_j softmax_j( sm_scale * <q[b,i,hq,:], k_j> ) * v_j

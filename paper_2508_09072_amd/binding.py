@@ -33,7 +33,14 @@ EXPORTS = (
     "reader_trie_extract_tree", "reader_tree_attach_path", "reader_self_repetition", "reader_tree_prune_order",
     "reader_tree_select",
     "reader_profile_enable", "reader_profile_collect", "reader_profile_collect_each", "reader_tuning_override",
+    "reader_attn_plan",
 )
+
+
+class ReaderAttnPlan(ctypes.Structure):
+    """Mirror of ``struct reader_attn_plan_t``."""
+    _fields_ = [("kernel", ctypes.c_int32), ("rows_per_workgroup", ctypes.c_int32), ("row_chunks", ctypes.c_int32),
+                ("key_ranges", ctypes.c_int32)]
 
 
 class ReaderDims(ctypes.Structure):
@@ -80,6 +87,8 @@ def load():
     lib.reader_validate_tree.argtypes = [vp, i32, i32]
     lib.reader_workspace_bytes.restype = ctypes.c_size_t
     lib.reader_workspace_bytes.argtypes = [dp, i32]
+    lib.reader_attn_plan.restype = ctypes.c_int
+    lib.reader_attn_plan.argtypes = [dp, i32, ctypes.POINTER(ReaderAttnPlan)]
     lib.reader_tree_attn.restype = ctypes.c_int
     lib.reader_tree_attn.argtypes = [dp] + [vp] * 10 + [i32, vp, ctypes.c_size_t, vp, vp]
     lib.reader_tree_attn_noalloc.restype = ctypes.c_int
@@ -178,6 +187,19 @@ def reader_validate_tree(parents_host) -> int:
                                dtype=np.int32)
     B, T = arr.shape
     return int(load().reader_validate_tree(arr.ctypes.data_as(ctypes.c_void_p), B, T))
+
+
+ATTN_KERNEL_NAMES = {0: "tree_attn_scalar_kernel", 1: "tree_attn_mfma_kernel<D, 4>", 2: "tree_attn_mfma_kernel<D, 8>",
+                     3: "tree_attn_wide_kernel<D>"}
+
+
+def reader_attn_plan(dims: ReaderDims, max_seq_len: int) -> dict:
+    """Kernel, rows per workgroup, row chunks and key ranges reader_tree_attn would use (host only)."""
+    plan = ReaderAttnPlan()
+    _check(load().reader_attn_plan(ctypes.byref(dims), int(max_seq_len), ctypes.byref(plan)), "reader_attn_plan")
+    return {"kernel": ATTN_KERNEL_NAMES[int(plan.kernel)].replace("D", str(int(dims.D))), "kernel_id": int(plan.kernel),
+            "rows_per_workgroup": int(plan.rows_per_workgroup), "row_chunks": int(plan.row_chunks),
+            "key_ranges": int(plan.key_ranges)}
 
 
 def reader_workspace_bytes(dims: ReaderDims, max_seq_len: int) -> int:

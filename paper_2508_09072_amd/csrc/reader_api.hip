@@ -199,6 +199,29 @@ extern "C" size_t reader_workspace_bytes(const reader_dims *dims, int32_t max_se
     return attn_header_bytes(dims->B, dims->Hkv) + ((bytes + 255) & ~(size_t)255);
 }
 
+static int attn_use_wide(const reader_dims &d, int rows_per_wg) {
+    // 256-row workgroups: four wavefronts of 64 rows at head dimension 128 (measured 2 to 4 % faster than eight of
+    // 32 rows at the two matrix-bound presets), eight of 32 at head dimension 64 (measured: no difference)
+    const int wide = tuning(READER_TUNE_ATTN_WIDE);
+    return rows_per_wg == 256 && (wide == 1 || (wide < 0 && d.D == 128)) ? 1 : 0;
+}
+
+extern "C" int reader_attn_plan(const reader_dims *dims, int32_t max_seq_len, reader_attn_plan_t *plan) {
+    int err = 0;
+    if (!plan) return READER_EINVAL;
+    if (!dims_ok(dims, &err)) return err;
+    if (max_seq_len < 0) return READER_EINVAL;
+    const bool scalar = dims->variant == 1;
+    plan->rows_per_workgroup = scalar ? 0 : attn_rows_per_wg(*dims, max_seq_len);
+    plan->row_chunks = scalar ? 0 : row_chunks(*dims, max_seq_len);
+    plan->key_ranges = scalar ? 0 : attn_plan_ranges(*dims, max_seq_len);
+    plan->kernel = scalar ? READER_ATTN_KERNEL_SCALAR
+                          : plan->rows_per_workgroup == 128 ? READER_ATTN_KERNEL_ROWS128
+                          : attn_use_wide(*dims, plan->rows_per_workgroup) ? READER_ATTN_KERNEL_ROWS256_WAVES4
+                                                                           : READER_ATTN_KERNEL_ROWS256_WAVES8;
+    return READER_OK;
+}
+
 // Argument checks and kernel parameters of the attention step (shared by reader_tree_attn and
 // reader_verify_step).  Returns READER_OK and fills `p`, or an error code; *empty is set when
 // there is nothing to do.
@@ -251,10 +274,7 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     // few pairs, many ranges: a pair is cut into eight parts or more on average, the merge fetches them four abreast
     p.merge_groups = (long long)dims->B * dims->Hkv * 8 <= p.n_ranges ? 4 : 1;
     p.tree_in_cache = tree_in_cache ? 1 : 0;
-    // 256-row workgroups: four wavefronts of 64 rows at head dimension 128 (measured 2 to 4 % faster than eight of
-    // 32 rows at the two matrix-bound presets), eight of 32 at head dimension 64 (measured: no difference)
-    const int wide = tuning(READER_TUNE_ATTN_WIDE);
-    p.wide = p.rows_per_wg == 256 && (wide == 1 || (wide < 0 && dims->D == 128)) ? 1 : 0;
+    p.wide = attn_use_wide(*dims, p.rows_per_wg);
     p.redo_only = 0;
 #ifdef READER_WG_STAMPS
     p.stamps = g_wg_stamps.load(std::memory_order_relaxed);

@@ -63,6 +63,32 @@ def test_workspace_bytes_is_pure_and_monotone(R):
     assert R.reader_workspace_bytes(d, 64) <= a
 
 
+def test_attention_plan_follows_the_query_rows_and_the_overrides(R):
+    # few query rows per kv head: 128-row workgroups with copying wavefronts; many rows on a long context: 256-row
+    # workgroups, four wavefronts at head dimension 128 and eight at 64; the override names either
+    small = R.reader_attn_plan(R.make_dims(16, 32, 32, 8, 128, 260, 7, 3000), 4096)
+    assert small["kernel_id"] == 1 and small["rows_per_workgroup"] == 128 and small["row_chunks"] == 1
+    assert 1 <= small["key_ranges"] <= 256
+    big = R.reader_attn_plan(R.make_dims(64, 64, 64, 8, 128, 520, 7, 30000), 8192)
+    assert big["kernel_id"] == 3 and big["rows_per_workgroup"] == 256 and big["row_chunks"] == 2
+    assert big["kernel"] == "tree_attn_wide_kernel<128>"
+    big64 = R.reader_attn_plan(R.make_dims(64, 64, 64, 8, 64, 520, 7, 30000), 8192)
+    assert big64["kernel_id"] == 2
+    try:
+        R.reader_tuning_override(R.TUNE_ATTN_WIDE, 0)
+        assert R.reader_attn_plan(R.make_dims(64, 64, 64, 8, 128, 520, 7, 30000), 8192)["kernel_id"] == 2
+        R.reader_tuning_override(R.TUNE_ATTN_ROWS, 128)
+        forced = R.reader_attn_plan(R.make_dims(64, 64, 64, 8, 128, 520, 7, 30000), 8192)
+        assert forced["kernel_id"] == 1 and forced["row_chunks"] == 4
+    finally:
+        R.reader_tuning_override(R.TUNE_ATTN_WIDE, -1)
+        R.reader_tuning_override(R.TUNE_ATTN_ROWS, -1)
+    scalar = R.reader_attn_plan(R.make_dims(2, 8, 8, 2, 64, 10, 4, 20, variant=1), 100)
+    assert scalar["kernel_id"] == 0
+    with pytest.raises(RuntimeError):
+        R.reader_attn_plan(R.make_dims(2, 8, 8, 2, 96, 10, 4, 20), 100)
+
+
 @pytest.mark.parametrize("change,code", [
     (dict(T=0), -1), (dict(T=129), -2), (dict(D=96), -2), (dict(Hkv=3), -1), (dict(page_size=32), -2),
     (dict(max_path=0), -1), (dict(max_path=33), -1), (dict(Hq=64, Hkv=2), -2), (dict(B=-1), -1),
