@@ -276,6 +276,9 @@ int reader_kv_compact(const reader_dims *dims,
  * not increase strictly, or that would touch a position outside the page table or a page id
  * out of range is left untouched (cache and seq_lens) and READER_STATUS_BAD_PATH /
  * READER_STATUS_BAD_PAGE is set.  Bit-exact copy.  dims->Hq and dims->sm_scale are not used.
+ * One kernel launch: the workgroup of a sequence that finishes last writes its new length, found through
+ * per-sequence counters that are device memory of the library (zero between calls).  Two calls that run on
+ * one GPU at the same time (different streams) would share those counters: order them.
  * Returns READER_OK, READER_EINVAL (bad dims, num_layers outside 0..65535, null pointer).
  */
 int reader_kv_compact_layers(const reader_dims *dims, int32_t num_layers,
@@ -297,8 +300,8 @@ int reader_kv_compact_layers(const reader_dims *dims, int32_t num_layers,
  *
  * k_tree and v_tree both NULL: the in-cache layout of reader_tree_attn, one layer.  The step
  * is then reader_tree_attn -> reader_accept_path -> reader_kv_compact_layers(num_layers = 1)
- * on k_cache, v_cache [num_pages, Hkv, page_size, D]: the accepted rows move in place (two
- * more small launches).  A model with several layers runs the attention of each layer, and
+ * on k_cache, v_cache [num_pages, Hkv, page_size, D]: the accepted rows move in place (one
+ * more small launch).  A model with several layers runs the attention of each layer, and
  * after the last one reader_accept_path and one reader_kv_compact_layers over all of them.
  */
 int reader_verify_step(const reader_dims *dims,

@@ -9,8 +9,12 @@
 // earlier one, so the rows of a pass are all read before any is written (a barrier between the
 // two halves); passes take the rows in increasing j, which keeps that guarantee across passes.
 //
-// Two launches: the move, one workgroup per (sequence, layer); then the new lengths (every
-// workgroup of the first launch needs the old ones).
+// One launch, one workgroup per (sequence, layer).  Every workgroup of a sequence needs its old
+// length, so the new one is written by whichever of them finishes last: each takes a ticket per
+// sequence when its rows are moved, and the holder of the last ticket writes the length and
+// puts the ticket counter back to zero.  The counters are device memory of the library itself
+// (one word per possible sequence, zero when the library is loaded and after every call), which
+// is why calls on the same GPU must not overlap in time.
 #include "internal.h"
 
 namespace reader {
@@ -19,6 +23,9 @@ namespace {
 
 constexpr int kMoveThreads = 256;
 constexpr int kMovePerThread = 8;      // 16-byte chunks a thread carries through one pass
+
+// tickets taken by the workgroups of sequence b in the call that is running (0 between calls)
+__device__ unsigned g_tickets[READER_MAX_B];
 
 struct MoveShared {
     int L, n, bad;
@@ -29,6 +36,10 @@ struct MoveShared {
 // Checks everything the sequence would touch before anything is written; called by at least
 // READER_MAX_T threads, with a barrier behind it.  Result in sh (bad: status bits, 0 = go).
 __device__ inline void check_sequence(const CompactLayersParams &p, int b, int tid, MoveShared &sh) {
+    // (the path entries are asked for together with the two scalars, not after them: one memory round trip less)
+    const int32_t *path = p.path + (size_t)b * p.max_path;
+    const int my_node = tid < p.max_path ? path[tid] : -1;
+    const int before = tid >= 1 && tid < p.max_path ? path[tid - 1] : -1;
     if (tid == 0) {
         sh.L = p.seq_lens[b];
         sh.n = p.accept_len[b];
@@ -42,9 +53,8 @@ __device__ inline void check_sequence(const CompactLayersParams &p, int b, int t
         bad = READER_STATUS_BAD_PATH;
     } else if (tid <= n) {
         const int j = tid;
-        const int32_t *path = p.path + (size_t)b * p.max_path;
-        const int node = path[j];
-        const bool ok = node >= 0 && node < p.T && (j == 0 ? node == 0 : node > path[j - 1]) && (long long)L + node < mapped;
+        const int node = my_node;
+        const bool ok = node >= 0 && node < p.T && (j == 0 ? node == 0 : node > before) && (long long)L + node < mapped;
         if (!ok) {
             bad = READER_STATUS_BAD_PATH;
         } else {
@@ -100,6 +110,14 @@ __global__ __launch_bounds__(kMoveThreads) void compact_layers_move_kernel(Compa
         for (int r = 0; r < kMovePerThread; ++r)
             if (cache_of[r]) *reinterpret_cast<uint4 *>(cache_of[r] + dst[r]) = held[r];
     }
+    // the last workgroup of the sequence to get here writes the new length (nobody needs the old one any more)
+    if (tid == 0) {
+        const unsigned ticket = atomicAdd(&g_tickets[b], 1u);
+        if (ticket == (unsigned)p.NL - 1u) {
+            g_tickets[b] = 0u;
+            p.seq_lens[b] = L + n + 1;
+        }
+    }
 }
 
 __global__ __launch_bounds__(128) void compact_layers_lengths_kernel(CompactLayersParams p) {
@@ -107,7 +125,7 @@ __global__ __launch_bounds__(128) void compact_layers_lengths_kernel(CompactLaye
     const int b = blockIdx.x, tid = threadIdx.x;
     check_sequence(p, b, tid, sh);
     if (sh.bad) {
-        if (p.NL == 0 && tid == 0 && p.status) atomicOr(p.status, sh.bad);   // (no move kernel ran to report it)
+        if (tid == 0 && p.status) atomicOr(p.status, sh.bad);
         return;
     }
     if (tid == 0) p.seq_lens[b] = sh.L + sh.n + 1;
@@ -118,10 +136,9 @@ __global__ __launch_bounds__(128) void compact_layers_lengths_kernel(CompactLaye
 hipError_t launch_kv_compact_layers(const CompactLayersParams &p, hipStream_t stream) {
     if (p.NL > 0) {
         hipLaunchKernelGGL(compact_layers_move_kernel, dim3(p.B, p.NL), dim3(kMoveThreads), 0, stream, p);
-        const hipError_t e = note_hip_error("launch compact_layers_move_kernel", hipGetLastError());
-        if (e != hipSuccess) return e;
+        return note_hip_error("launch compact_layers_move_kernel", hipGetLastError());
     }
-    hipLaunchKernelGGL(compact_layers_lengths_kernel, dim3(p.B), dim3(128), 0, stream, p);
+    hipLaunchKernelGGL(compact_layers_lengths_kernel, dim3(p.B), dim3(128), 0, stream, p);   // no layers: only the lengths
     return note_hip_error("launch compact_layers_lengths_kernel", hipGetLastError());
 }
 
