@@ -95,3 +95,30 @@ def test_serving_shape(R, oracle_mod):
     s = W.make_incache_step("serving", B=16, T=32, Hkv=8, D=128, num_layers=32,
                             seq_lens=[int(x) for x in rng.integers(64, 257, size=16)], max_path=9, seed=9)
     check(R, oracle_mod, s)
+
+
+def test_two_calls_in_a_row_on_the_same_tensors(R, oracle_mod):
+    # The workgroups of a sequence elect the one that writes the new length through counters inside the library,
+    # which must be back at zero when a call ends: a second call (lengths put back, caches as the first call
+    # left them) has to move its rows and grow the lengths exactly like the oracle does.
+    import torch
+    s = W.make_incache_step("twice", B=6, T=16, Hkv=4, D=128, num_layers=5, seq_lens=[3, 40, 41, 100, 15, 16],
+                            max_path=8, seed=11)
+    k_ref, v_ref, L_ref = s.k_cache.copy(), s.v_cache.copy(), s.seq_lens.copy()
+    NL, num_pages, Hkv, page_size, D = s.k_cache.shape
+    dims = R.make_dims(6, s.T, Hkv, Hkv, D, s.page_table.shape[1], s.max_path, num_pages)
+    k = torch.from_numpy(s.k_cache.view(np.int16)).cuda().view(torch.bfloat16)
+    v = torch.from_numpy(s.v_cache.view(np.int16)).cuda().view(torch.bfloat16)
+    L = torch.from_numpy(s.seq_lens.copy()).cuda()
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    path, acc, table = torch.from_numpy(s.path).cuda(), torch.from_numpy(s.accept_len).cuda(), torch.from_numpy(s.page_table).cuda()
+    bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+    for call in range(2):
+        L.copy_(torch.from_numpy(s.seq_lens))
+        L_ref[:] = s.seq_lens
+        oracle_mod.kv_compact_layers(k_ref, v_ref, s.path, s.accept_len, s.page_table, L_ref)
+        R.reader_kv_compact_layers(dims, path, acc, k, v, table, L, status)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        assert np.array_equal(L.cpu().numpy(), L_ref), "lengths after call %d" % call
+        assert np.array_equal(bits(k), k_ref) and np.array_equal(bits(v), v_ref), "caches after call %d" % call
