@@ -306,17 +306,43 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
         }
     };
 
+    // The same for a caller that holds the item's descriptor words already: a whole prefix tile (the common
+    // item) is asked for with its copy instructions and nothing else.
+    auto issue_known = [&](const CopyLane<D, CW> &cl, int i, unsigned stage_lds, int blk, int nv, int fl) {
+        const bool plain = !(fl & (kDescQ | kDescMasks | kDescTree)) && blk >= 0 && (cw + 1) * G::kRowsPerWave <= nv;
+        if (plain) {
+            const size_t boff = (size_t)blk * (16 * G::kRowBytes);
+            const char *kb = reinterpret_cast<const char *>(p.k_cache) + boff;
+            const char *vb = reinterpret_cast<const char *>(p.v_cache) + boff;
+            const unsigned dst = stage_lds + cw * G::kRowsPerWave * G::kRowBytes;
+#pragma unroll
+            for (int c = 0; c < G::kCopies; ++c) copy16_uniform(kb, cl.k_cache_off[c], dst + c * 1024);
+#pragma unroll
+            for (int c = 0; c < G::kCopies; ++c) copy16_uniform(vb, cl.v_cache_off[c], dst + G::kTileBytes + c * 1024);
+        } else {
+            issue_item(cl, i, stage_lds);
+        }
+    };
+
     // prologue: the first kS - 1 items are put in flight
     if (is_copier) {
         const CopyLane<D, CW> cl = make_copy_lane<D, CW>(p, cw, lane);
         READER_STAMP(kStampCopyReady, kDma ? 256 : 0);
         if (kDma) {
-#pragma unroll
             // (item 0, the first pair's query unit, is not copied: the computing wavefronts, idle until the
             // first tile arrives, read their rows straight into registers meanwhile, and the first
             // K/V tiles are asked for that much sooner)
+            int4 words[kS - 1];          // (asked for together: one LDS round trip for both items)
+#pragma unroll
             for (int i = 1; i < kS - 1; ++i) {
-                if (i < n_iter) issue_item(cl, i, ring_lds + i * G::kStageBytes);
+                const TileDesc *d = desc_of(i);
+                words[i] = make_int4(d->blk[cw], d->n_valid, d->flags, 0);
+            }
+#pragma unroll
+            for (int i = 1; i < kS - 1; ++i) {
+                if (i < n_iter)
+                    issue_known(cl, i, ring_lds + i * G::kStageBytes, __builtin_amdgcn_readfirstlane(words[i].x),
+                                __builtin_amdgcn_readfirstlane(words[i].y), __builtin_amdgcn_readfirstlane(words[i].z));
                 if (i == 1) READER_STAMP(kStampItem0Issued, 256);
             }
         } else {
@@ -632,21 +658,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             // item it + kS - 1 goes into the stage that item it - 1 has left
             if (it == 8) READER_STAMP(kStampLoopIssue, 256);
             if (it + kS - 1 < n_iter) {
-                const unsigned stage_lds = ring_lds + ((it + kS - 1) % kS) * G::kStageBytes;
-                const bool plain = !(c_flags & (kDescQ | kDescMasks | kDescTree)) && c_blk >= 0 &&
-                                   (cw + 1) * G::kRowsPerWave <= c_valid;
-                if (plain) {
-                    const size_t boff = (size_t)c_blk * (16 * G::kRowBytes);
-                    const char *kb = reinterpret_cast<const char *>(p.k_cache) + boff;
-                    const char *vb = reinterpret_cast<const char *>(p.v_cache) + boff;
-                    const unsigned dst = stage_lds + cw * G::kRowsPerWave * G::kRowBytes;
-#pragma unroll
-                    for (int i = 0; i < G::kCopies; ++i) copy16_uniform(kb, cl.k_cache_off[i], dst + i * 1024);
-#pragma unroll
-                    for (int i = 0; i < G::kCopies; ++i) copy16_uniform(vb, cl.v_cache_off[i], dst + G::kTileBytes + i * 1024);
-                } else {
-                    issue_item(cl, it + kS - 1, stage_lds);
-                }
+                issue_known(cl, it + kS - 1, ring_lds + ((it + kS - 1) % kS) * G::kStageBytes, c_blk, c_valid, c_flags);
             }
             if (it == 8) READER_STAMP(kStampLoopIssued, 256);
         }

@@ -13,9 +13,10 @@
 // A wavefront has nobody to hide its waiting behind, so nothing in the tile may wait:
 //   - the ring has 4 stages and tiles are asked for three tiles ahead;
 //   - operand fragments are read from LDS ahead of the matrix instructions that use them;
-//   - the softmax of a score block runs between the matrix instructions of the next one
-//     (a wavefront's vector instructions do issue under its own matrix instructions when the
-//     two kinds alternate finely; in long runs of one kind they do not).
+//   - whole prefix tiles run as a software pipeline over two tiles: the scores of the next
+//     tile, the products of the current one and, one per matrix instruction, the softmax
+//     weights in between (a wavefront's vector instructions do issue under its own matrix
+//     instructions when the two kinds alternate finely; in long runs of one kind they do not).
 #include <hip/hip_ext.h>
 
 #include <mutex>
@@ -31,20 +32,6 @@ namespace {
 constexpr int kWideThreads = 256;   // 4 wavefronts
 constexpr int kWideStages = 4;      // tile buffers in the ring
 constexpr int kWideRows = 256;      // query rows per workgroup
-
-// The 32 pairs of weights of a tile are spread over the slots [first, end) of its matrix instructions:
-// pair j goes to slot first + j * (end - first) / 32.
-constexpr int weight_slot(int j, int first, int end) { return first + j * (end - first) / 32; }
-constexpr int first_weight_in_slot(int m, int first, int end) {
-    for (int j = 0; j < 32; ++j)
-        if (weight_slot(j, first, end) == m) return j;
-    return 32;
-}
-constexpr int weights_in_slot(int m, int first, int end) {
-    int n = 0;
-    for (int j = 0; j < 32; ++j) n += weight_slot(j, first, end) == m ? 1 : 0;
-    return n;
-}
 
 // The accumulation registers (a0..a255 of every lane) are managed by hand in this kernel: the compiler is
 // told never to use them (-amdgpu-spill-vgpr-to-agpr=0 and no operand of that class anywhere), the
