@@ -345,7 +345,10 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
     // this order is the other key block (of the same tile for wkb = 1, of the tile before for wkb = 0).
     auto weight_slot = [&](auto wkbc, auto ec) {
         constexpr int wkb = decltype(wkbc)::value, e = decltype(ec)::value;
-        const float p_cur = __builtin_amdgcn_exp2f(w_x);
+        // (written out for the same reason as the argument: left to the compiler the exponential moves up to just
+        // behind the instruction that makes its argument, one slot earlier, and waits for it there)
+        float p_cur;
+        asm volatile("v_exp_f32 %0, %1" : "=v"(p_cur) : "v"(w_x));
         // the next argument: score e + 1 of this block, or score 0 of the other one (complete by now: its last
         // matrix instruction was issued at least two matrix instructions ago)
         constexpr int nb = e == 31 ? 1 - wkb : wkb, ne = (e + 1) & 31;
