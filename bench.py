@@ -568,6 +568,16 @@ def main():
         del wo, r
         torch.cuda.empty_cache()
     line["other_workloads"] = others
+    # what a bare copy ring and a bare matrix loop reach on this GPU (beside the published peaks of the roofline objects)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    scratch = torch.empty(1 << 19, dtype=torch.uint8, device="cuda")
+    peaks = [R.reader_measure_peaks(src, scratch) for _ in range(3)][1:]
+    line["measured_peaks"] = {"hbm_read_gbs": max(p["hbm_read_gbs"] for p in peaks),
+                              "mfma_bf16_tflops": max(p["mfma_bf16_tflops"] for p in peaks),
+                              "mfma_clock_mhz": peaks[-1]["mfma_clock_mhz"],
+                              "note": "bare LDS copy ring over 1 GiB; bare v_mfma_f32_32x32x16_bf16 loop, one wavefront per SIMD"}
+    del src, scratch
+    torch.cuda.empty_cache()
     if not args.no_scaled_shapes:
         # The batched HBM-bound shape (cfg2) with more bytes per launch (longer contexts, or more sequences): the
         # fixed part of a launch (start, first latency, end) weighs less, the achieved fraction of the HBM peak rises.

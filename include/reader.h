@@ -478,6 +478,24 @@ int reader_profile_collect(double *kernel_ms_sum, int32_t *launches);
 int reader_profile_collect_each(float *ms_each, int32_t capacity, int32_t *launches);
 
 /*
+ * What this GPU gives the two things the attention kernels are made of, for the roofline discussion
+ * (not an operation of the method).  Runs two bare loops on `stream` and waits for them:
+ *   - every compute unit copies 32 KB tiles of `src` into a ring of LDS buffers with the instruction
+ *     and the ring depth of the attention kernel and does nothing else: *hbm_read_gbs (src should be
+ *     larger than the last-level cache, 256 MB, for the figure to be an HBM figure; the first
+ *     src_bytes rounded down to a multiple of 8 MB are read);
+ *   - one wavefront per SIMD issues the matrix instruction (v_mfma_f32_32x32x16_bf16) back to back on
+ *     register operands: *mfma_bf16_tflops, and the shader clock the part runs at under that load in
+ *     *mfma_clock_mhz (it lowers its clock under matrix load).
+ *   src      device, src_bytes >= 32 MB, read only;  scratch  device, >= 262160 bytes, overwritten
+ *   the three results are HOST doubles.
+ * Creates and destroys two events; synchronises the host with the stream.  READER_OK, READER_EINVAL
+ * (null pointer, sizes too small), READER_EHIP.
+ */
+int reader_measure_peaks(const void *src, size_t src_bytes, void *scratch, size_t scratch_bytes,
+                         double *hbm_read_gbs, double *mfma_bf16_tflops, double *mfma_clock_mhz, void *stream);
+
+/*
  * Launch-planner overrides for tests and experiments (not operations of the method; a caller
  * never needs them).  The planner of reader_tree_attn / reader_verify_step picks the number of
  * query rows per workgroup, the number of key ranges, the cost it books for the start of a

@@ -33,7 +33,7 @@ EXPORTS = (
     "reader_trie_extract_tree", "reader_tree_attach_path", "reader_self_repetition", "reader_tree_prune_order",
     "reader_tree_select",
     "reader_profile_enable", "reader_profile_collect", "reader_profile_collect_each", "reader_tuning_override",
-    "reader_attn_plan",
+    "reader_attn_plan", "reader_measure_peaks",
 )
 
 
@@ -87,6 +87,8 @@ def load():
     lib.reader_validate_tree.argtypes = [vp, i32, i32]
     lib.reader_workspace_bytes.restype = ctypes.c_size_t
     lib.reader_workspace_bytes.argtypes = [dp, i32]
+    lib.reader_measure_peaks.restype = ctypes.c_int
+    lib.reader_measure_peaks.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t] + [ctypes.POINTER(ctypes.c_double)] * 3 + [vp]
     lib.reader_attn_plan.restype = ctypes.c_int
     lib.reader_attn_plan.argtypes = [dp, i32, ctypes.POINTER(ReaderAttnPlan)]
     lib.reader_tree_attn.restype = ctypes.c_int
@@ -200,6 +202,15 @@ def reader_attn_plan(dims: ReaderDims, max_seq_len: int) -> dict:
     return {"kernel": ATTN_KERNEL_NAMES[int(plan.kernel)].replace("D", str(int(dims.D))), "kernel_id": int(plan.kernel),
             "rows_per_workgroup": int(plan.rows_per_workgroup), "row_chunks": int(plan.row_chunks),
             "key_ranges": int(plan.key_ranges)}
+
+
+def reader_measure_peaks(src, scratch) -> dict:
+    """HBM read rate of a bare LDS copy ring over `src` and the bf16 matrix rate (with the clock under that load)."""
+    out = [ctypes.c_double(0.0) for _ in range(3)]
+    code = load().reader_measure_peaks(_dev(src), src.numel() * src.element_size(), _dev(scratch),
+                                       scratch.numel() * scratch.element_size(), *[ctypes.byref(x) for x in out], _stream())
+    _check(code, "reader_measure_peaks")
+    return {"hbm_read_gbs": out[0].value, "mfma_bf16_tflops": out[1].value, "mfma_clock_mhz": out[2].value}
 
 
 def reader_workspace_bytes(dims: ReaderDims, max_seq_len: int) -> int:

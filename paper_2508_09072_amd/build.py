@@ -18,7 +18,7 @@ LIB = os.path.join(HERE, "libreader_hip.so")
 # the same library with per-workgroup time stamps in the 128-row attention kernel (python -m ...build --stamps;
 # used by wg_timeline.py only)
 STAMPS_LIB = os.path.join(HERE, "libreader_hip_stamps.so")
-SOURCES = ["reader_api.hip", "trie_drafter.cpp", "tree_shape.cpp", "accept_compact.hip", "kv_compact_layers.hip", "kv_rearrange.hip", "target_argmax.hip", "target_sample.hip", "tree_attn_scalar.hip", "tree_attn_mfma.hip", "tree_attn_wide.hip"]
+SOURCES = ["reader_api.hip", "trie_drafter.cpp", "tree_shape.cpp", "accept_compact.hip", "kv_compact_layers.hip", "kv_rearrange.hip", "target_argmax.hip", "target_sample.hip", "tree_attn_scalar.hip", "tree_attn_mfma.hip", "tree_attn_wide.hip", "peak_probes.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions

@@ -130,6 +130,11 @@ struct CompactLayersParams {
 };
 hipError_t launch_kv_compact_layers(const CompactLayersParams &p, hipStream_t stream);
 
+// peak_probes.hip: the bare copy ring and the bare matrix loop behind reader_measure_peaks
+hipError_t launch_probe_copy(const void *src, size_t bytes, void *scratch, hipStream_t stream, size_t *bytes_moved);
+hipError_t launch_probe_mfma(int iters, void *scratch, hipStream_t stream);
+constexpr size_t kProbeScratchBytes = (size_t)kNumCU * 256 * sizeof(float) + 16;
+
 struct RearrangeParams {
     uint16_t *k_pad, *v_pad;   // [NL, B, S, Hkv, D]
     uint8_t *valid;            // [B, S]

@@ -448,6 +448,49 @@ extern "C" int reader_profile_collect_each(float *ms_each, int32_t capacity, int
     return rc;
 }
 
+extern "C" int reader_measure_peaks(const void *src, size_t src_bytes, void *scratch, size_t scratch_bytes,
+                                    double *hbm_read_gbs, double *mfma_bf16_tflops, double *mfma_clock_mhz, void *stream) {
+    if (!src || !scratch || !hbm_read_gbs || !mfma_bf16_tflops || !mfma_clock_mhz) return READER_EINVAL;
+    if (src_bytes < (size_t)kNumCU * 32768 * 4 || scratch_bytes < kProbeScratchBytes) return READER_EINVAL;
+    forget_stale_error();
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipEvent_t a = nullptr, b = nullptr;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+        if (a) (void)hipEventDestroy(a);
+        (void)hipGetLastError();
+        return READER_EHIP;
+    }
+    int rc = READER_OK;
+    auto timed = [&](auto &&launch, float *ms) {
+        // one untimed run, then one between two events
+        for (int rep = 0; rep < 2 && rc == READER_OK; ++rep) {
+            if (rep == 1 && hipEventRecord(a, st) != hipSuccess) rc = READER_EHIP;
+            if (rc == READER_OK && launch() != hipSuccess) rc = READER_EHIP;
+            if (rep == 1 && rc == READER_OK && hipEventRecord(b, st) != hipSuccess) rc = READER_EHIP;
+        }
+        if (rc == READER_OK && (hipEventSynchronize(b) != hipSuccess || hipEventElapsedTime(ms, a, b) != hipSuccess)) rc = READER_EHIP;
+    };
+    float copy_ms = 0.f, mfma_ms = 0.f;
+    size_t moved = 0;
+    timed([&]() { return launch_probe_copy(src, src_bytes, scratch, st, &moved); }, &copy_ms);
+    constexpr int kIters = 2000;   // x 64 matrix instructions per wavefront: about 2 ms
+    timed([&]() { return launch_probe_mfma(kIters, scratch, st); }, &mfma_ms);
+    long long clocks[2] = {0, 0};
+    if (rc == READER_OK &&
+        hipMemcpyAsync(clocks, static_cast<const char *>(scratch) + (size_t)kNumCU * 256 * sizeof(float), sizeof clocks,
+                       hipMemcpyDeviceToHost, st) != hipSuccess)
+        rc = READER_EHIP;
+    if (rc == READER_OK && hipStreamSynchronize(st) != hipSuccess) rc = READER_EHIP;
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    if (rc != READER_OK) { (void)hipGetLastError(); return rc; }
+    *hbm_read_gbs = copy_ms > 0.f ? (double)moved / (copy_ms * 1e-3) / 1e9 : 0.0;
+    const double flops = (double)kNumCU * 4.0 * kIters * 64.0 * 32768.0;
+    *mfma_bf16_tflops = mfma_ms > 0.f ? flops / (mfma_ms * 1e-3) / 1e12 : 0.0;
+    *mfma_clock_mhz = clocks[1] > 0 ? (double)clocks[0] / ((double)clocks[1] / 100.0) : 0.0;
+    return READER_OK;
+}
+
 extern "C" int reader_accept_path(const reader_dims *dims, const int32_t *draft_tokens,
                                   const int32_t *target_tokens, const int32_t *parents,
                                   int32_t *accept_len, int32_t *path, int32_t *bonus_token,

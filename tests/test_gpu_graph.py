@@ -101,3 +101,24 @@ def test_an_error_left_behind_by_somebody_else_is_not_taken_for_a_failed_launch(
     R.reader_target_argmax(logits, tok)
     torch.cuda.synchronize()
     assert torch.equal(tok.long(), logits.float().argmax(-1))
+
+
+def test_measured_peaks_are_plausible_and_bad_sizes_are_refused():
+    # the two bare loops behind the roofline discussion: a copy ring (HBM -> LDS) and a matrix-instruction loop
+    import torch
+    from paper_2508_09072_amd import binding as R
+    R.load()
+    src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(3)
+    scratch = torch.empty(1 << 19, dtype=torch.uint8, device="cuda")
+    R.reader_measure_peaks(src, scratch)
+    got = R.reader_measure_peaks(src, scratch)
+    print("measured peaks:", got, flush=True)
+    assert 2000.0 < got["hbm_read_gbs"] < 8000.0
+    assert 800.0 < got["mfma_bf16_tflops"] < 2600.0
+    assert 900.0 < got["mfma_clock_mhz"] < 2600.0
+    # the rate is what 1024 matrix pipes do at that clock, one 32-cycle instruction after the other
+    assert abs(got["mfma_bf16_tflops"] - 1024 * 32768 / 32 * got["mfma_clock_mhz"] * 1e-6) < 0.05 * got["mfma_bf16_tflops"]
+    with pytest.raises(RuntimeError):
+        R.reader_measure_peaks(src[: 1 << 20], scratch)
+    with pytest.raises(RuntimeError):
+        R.reader_measure_peaks(src, scratch[:1024])
