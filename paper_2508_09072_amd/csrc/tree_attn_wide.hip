@@ -269,7 +269,7 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
     auto issue_tile_at = [&](int i) {
         const TileDesc *d = desc_of(i);
         issue_tile(__builtin_amdgcn_readfirstlane(d->blk[cw]), __builtin_amdgcn_readfirstlane(d->n_valid),
-                   __builtin_amdgcn_readfirstlane(d->flags), ring_lds + (i % kS) * G::kStageBytes);
+                   __builtin_amdgcn_readfirstlane(d->flags), ring_lds + ((unsigned)i % kS) * G::kStageBytes);
     };
 
     // prologue: the first kS - 1 tiles are put in flight
@@ -642,7 +642,9 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
     int2 d_nxt = *reinterpret_cast<const int2 *>(&desc_of(1)->n_valid);
     int2 d_cpy = *reinterpret_cast<const int2 *>(&desc_of(kS - 1)->n_valid);
     int d_blk = desc_of(kS - 1)->blk[cw];
-    auto is_whole = [](int valid, int flags) { return valid == kTile && !(flags & (kDescTree | kDescFresh | kDescHoles)); };
+    // (integer arithmetic on purpose: conditions kept as booleans become 64-bit lane masks and pairs of
+    // compare/select instructions, and this runs once per tile on the only wavefront of its SIMD)
+    auto is_whole = [](int valid, int flags) { return ((valid ^ kTile) | (flags & (kDescTree | kDescFresh | kDescHoles))) == 0; };
 
     // What every iteration starts with, whichever tile code follows: wait for the tiles, barrier, the tile
     // list, the copies of the tile three ahead (unless they go inside a pipelined tile).
@@ -680,7 +682,7 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
         // behind a pipelined tile has its copy instructions spread over that tile's matrix instructions;
         // every other tile is asked for here.
         const bool copy_next = it + kS - 1 < n_iter;
-        I.copy_stage_lds = ring_lds + ((it + kS - 1) % kS) * G::kStageBytes;
+        I.copy_stage_lds = ring_lds + ((unsigned)(it + kS - 1) % kS) * G::kStageBytes;
         I.whole = is_whole(I.t_valid, I.t_flags);
         I.pipelined = wave_active && I.whole && !I.last_iter && is_whole(n_valid, n_flags);
         const bool whole_next = I.c_blk >= 0 && !(c_flags & kDescTree) && (cw + 1) * G::kRowsPerWave <= c_valid;
@@ -689,7 +691,7 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
         if (I.pair_ends && !I.last_iter) prefetch_q(desc_b(it + 1), desc_hkv(it + 1));
         return I;
     };
-    auto stage_of = [&](int it) { return ring + (it % kS) * G::kStageBytes; };
+    auto stage_of = [&](int it) { return ring + ((unsigned)it % kS) * G::kStageBytes; };   // (unsigned: a mask, not a signed remainder)
 
     for (int it = 0; it < n_iter; ++it) {
         Iter I = begin_iteration(it);
