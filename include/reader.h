@@ -506,7 +506,9 @@ int reader_measure_peaks(const void *src, size_t src_bytes, void *scratch, size_
  * and the code path differ.  Stored atomically: a call sees the old or the new value.
  *   READER_TUNE_ATTN_ROWS       128 or 256 query rows per workgroup (other values: planner decides)
  *   READER_TUNE_ATTN_RANGES     >= 1 key ranges asked for (capped at the number of compute units)
- *   READER_TUNE_ATTN_PAIR_COST  0..64 tile times booked per pair start
+ *   READER_TUNE_ATTN_PAIR_COST  0..64 tile times booked per pair beyond its tiles
+ *   READER_TUNE_ATTN_PAIR_FRONT how many of them are booked to the workgroup that starts the pair (the rest to
+ *                               the one that finishes it); capped at the pair cost
  *   READER_TUNE_ATTN_AXIS64     1 = cut the ranges in 64-bit arithmetic even where 32 bits suffice
  *   READER_TUNE_ATTN_WIDE       which kernel 256-row workgroups run: 1 = four wavefronts with 64 rows each (one per
  *                               SIMD, the accumulation registers managed by hand), 0 = eight with 32 rows each;
@@ -519,7 +521,8 @@ enum {
     READER_TUNE_ATTN_PAIR_COST = 2,
     READER_TUNE_ATTN_AXIS64 = 3,
     READER_TUNE_ATTN_WIDE = 4,
-    READER_TUNE_COUNT_ = 5
+    READER_TUNE_ATTN_PAIR_FRONT = 5,
+    READER_TUNE_COUNT_ = 6
 };
 int reader_tuning_override(int32_t which, int32_t value);
 

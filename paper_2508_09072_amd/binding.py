@@ -23,7 +23,7 @@ READER_EHIP = -4
 STATUS_BAD_TREE = 1
 STATUS_BAD_PAGE = 2
 STATUS_BAD_PATH = 4
-TUNE_ATTN_ROWS, TUNE_ATTN_RANGES, TUNE_ATTN_PAIR_COST, TUNE_ATTN_AXIS64, TUNE_ATTN_WIDE = 0, 1, 2, 3, 4
+TUNE_ATTN_ROWS, TUNE_ATTN_RANGES, TUNE_ATTN_PAIR_COST, TUNE_ATTN_AXIS64, TUNE_ATTN_WIDE, TUNE_ATTN_PAIR_FRONT = 0, 1, 2, 3, 4, 5
 
 EXPORTS = (
     "reader_version", "reader_strerror", "reader_last_error_detail", "reader_validate_tree", "reader_workspace_bytes",

@@ -39,7 +39,8 @@ struct AttnParams {
 #ifdef READER_WG_STAMPS
     long long *stamps;       // profiling build only: kWgStamps time stamps per workgroup (100 MHz counter), or null
 #endif
-    int32_t pair_cost;       // what the start of a pair costs a workgroup, in tiles, when the ranges are cut
+    int32_t pair_cost;       // what a pair costs beyond its tiles, in tile times, when the ranges are cut
+    int32_t pair_front;      // the part of it booked in front of the pair's tiles (the rest behind them)
     int32_t axis32;          // 1: every position of the cost axis times n_ranges fits in an int
     int32_t ranges_shift;    // log2(n_ranges) when it is a power of two (the even cut is then a shift), else -1
     int32_t merge_groups;    // thread groups that share a query row's partial records in the merge: 1, or 4 when pairs are cut into many parts
@@ -81,7 +82,9 @@ enum WgStamp {
     kStampLoopWait = 10,    // (copying wavefront, iteration 8) at the top of the iteration, before the wait for its copies
     kStampLoopIssue = 11,   // ... past the barrier, about to ask for the item three ahead
     kStampLoopIssued = 12,  // ... that item asked for
-    kWgStamps = 13
+    kStampTileLanded = 13,  // first key tile complete in LDS (past the barrier that says so)
+    kStampTileDone = 14,    // first key tile computed by this wavefront (before the next barrier)
+    kWgStamps = 15
 };
 #endif
 constexpr int kMaxRowChunks = 8;                           // ceil(READER_MAX_T * 16 grouped heads / 256 rows)

@@ -16,7 +16,7 @@ namespace reader {
 static char g_error_detail[256] = "";
 
 // Planner overrides set through reader_tuning_override (tests, experiments); -1 = the planner decides.
-static std::atomic<int32_t> g_tuning[READER_TUNE_COUNT_] = {{-1}, {-1}, {-1}, {-1}, {-1}};
+static std::atomic<int32_t> g_tuning[READER_TUNE_COUNT_] = {{-1}, {-1}, {-1}, {-1}, {-1}, {-1}};
 #ifdef READER_WG_STAMPS
 static std::atomic<long long *> g_wg_stamps{nullptr};
 #endif
@@ -258,10 +258,15 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
     p.n_row_chunks = row_chunks(*dims, max_seq_len);
     p.n_ranges = attn_plan_ranges(*dims, max_seq_len);
     {
-        // A pair that starts inside a range costs its workgroup extra (query rows to fetch, a
-        // segment to finish): about four tiles' time when dedicated wavefronts copy, one otherwise.
+        // A pair costs the workgroups that start and finish it extra, mostly the one that finishes it (the ragged
+        // last prefix tile, the masks of the tree tiles, normalising and writing the rows; the start has the
+        // query rows to fetch): with dedicated copy wavefronts about one tile time in front of the pair's
+        // tiles and two behind them, otherwise one in front.
         const int forced_cost = tuning(READER_TUNE_ATTN_PAIR_COST);
-        p.pair_cost = forced_cost >= 0 && forced_cost <= 64 ? forced_cost : (p.rows_per_wg == 128 ? 4 : 1);
+        p.pair_cost = forced_cost >= 0 && forced_cost <= 64 ? forced_cost : (p.rows_per_wg == 128 ? 3 : 1);
+        const int forced_front = tuning(READER_TUNE_ATTN_PAIR_FRONT);
+        p.pair_front = forced_front >= 0 ? forced_front : 1;
+        if (p.pair_front > p.pair_cost) p.pair_front = p.pair_cost;
         // the kernel cuts the ranges with 32-bit arithmetic when nothing on the cost axis can overflow it
         const long long axis_max = (long long)p.Hkv * p.B * ((max_seq_len + kTile - 1) / kTile + p.n_tree_tiles + p.pair_cost);
         p.axis32 = (axis_max + 2) * (p.n_ranges + 1) < 0x7fffffffLL ? 1 : 0;

@@ -74,11 +74,14 @@ __device__ inline void scan_units(const AttnParams &p, const int32_t *__restrict
 }
 
 // Cutting the tile axis into ranges of equal cost.  Every pair (sequence b, kv head) is given
-// E extra positions in front of its tiles (E = pair_cost: what starting a pair costs a
-// workgroup, in tiles), and the axis of these "cost positions" is cut evenly; a workgroup owns
-// the tiles whose positions fall into its share.  The pair's n_b tiles and its padding start at
+// E extra positions (E = pair_cost: what a pair costs the workgroups that start and finish it
+// beyond its tiles, in tile times), F of them in front of its tiles (F = pair_front: the query
+// rows to fetch, the first tile's row maxima) and E - F behind them (the ragged last prefix tile,
+// the masks of the tree tiles, normalising and writing the rows), and the axis of these "cost
+// positions" is cut evenly; a workgroup owns the tiles whose positions fall into its share.  The
+// pair's n_b tiles and its padding start at
 //     Hkv * (pref[b] + b * E) + hkv * (n_b + E),
-// the first E positions are padding, tile t sits at padding + t.
+// tile t sits F + t positions further.
 // I is the integer type of the axis: int when the host has checked that every position times
 // the number of ranges fits (64-bit division costs a workgroup a good part of a microsecond).
 template <typename I>
@@ -99,7 +102,7 @@ __device__ inline I cost_total(const AttnParams &p, const int *s_pref) {
 template <typename I>
 __device__ inline I cost_pos_of_tile(const AttnParams &p, const int *s_pref, int b, int hkv, int t) {
     const int n_b = s_pref[b + 1] - s_pref[b];
-    return (I)p.Hkv * (s_pref[b] + (I)b * p.pair_cost) + (I)hkv * (n_b + p.pair_cost) + p.pair_cost + t;
+    return (I)p.Hkv * (s_pref[b] + (I)b * p.pair_cost) + (I)hkv * (n_b + p.pair_cost) + p.pair_front + t;
 }
 
 // Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel-primitive moves:
@@ -137,10 +140,10 @@ __device__ inline TilePos locate(const AttnParams &p, const int *s_pref, I v) {
     const int rel = (int)(v - (I)p.Hkv * (s_pref[b] + (I)b * p.pair_cost));   // < Hkv * (n_b + E)
     int hkv = rel / (n_b + p.pair_cost);
     hkv = hkv > p.Hkv - 1 ? p.Hkv - 1 : hkv;
-    const int rr = rel - hkv * (n_b + p.pair_cost) - p.pair_cost;
+    const int rr = rel - hkv * (n_b + p.pair_cost) - p.pair_front;
     r.b = b; r.hkv = hkv; r.t = rr > 0 ? (rr < n_b ? rr : n_b) : 0;
     r.flat = p.Hkv * s_pref[b] + hkv * n_b + r.t;
-    if (r.t == n_b) {   // (not reached: rr < n_b by construction; kept so that t is always a tile of the pair)
+    if (r.t == n_b) {   // a position in the padding behind the pair's tiles: the next pair's first tile
         r.t = 0;
         if (++r.hkv == p.Hkv) { r.hkv = 0; ++r.b; }
     }
@@ -500,9 +503,13 @@ __device__ __forceinline__ void setup_range(const AttnParams &p, const int32_t *
             const int span = __builtin_amdgcn_readlane(units, b) + p.pair_cost;   // cost positions per pair
             const int rel = pos - __builtin_amdgcn_readlane(base, b);
             const int hkv = __popcll(__ballot(lane < p.Hkv && lane * span <= rel)) - 1;
-            const int rr = rel - hkv * span - p.pair_cost;
-            r.b = b; r.hkv = hkv; r.t = rr > 0 ? rr : 0;
-            r.flat = p.Hkv * __builtin_amdgcn_readlane(excl, b) + hkv * (span - p.pair_cost) + r.t;
+            const int rr = rel - hkv * span - p.pair_front, n_b = span - p.pair_cost;
+            r.b = b; r.hkv = hkv; r.t = rr > 0 ? (rr < n_b ? rr : n_b) : 0;
+            r.flat = p.Hkv * __builtin_amdgcn_readlane(excl, b) + hkv * n_b + r.t;
+            if (r.t == n_b) {   // a position in the padding behind the pair's tiles: the next pair's first tile
+                r.t = 0;
+                if (++r.hkv == p.Hkv) { r.hkv = 0; ++r.b; }
+            }
             return r;
         };
         auto cut = [&](int w) {   // where range w starts on the cost axis

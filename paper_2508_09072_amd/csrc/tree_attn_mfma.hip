@@ -673,6 +673,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             const bool pair_ends = (t_flags & kDescPairEnd) != 0;
             __syncthreads();   // item `it` is complete in LDS
             if (it == 0) READER_STAMP(kStampFirstItem, 0);
+            if (it == 1) READER_STAMP(kStampTileLanded, 0);
             if (it == 2) READER_STAMP(kStampFirstTile, 0);   // (item 0 is the query unit: item 1, the first key tile, is done)
             d_cur = *reinterpret_cast<const int2 *>(&desc_of(it + 1)->n_valid);
 
@@ -686,6 +687,7 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
             }
             if (wave_active) {
                 compute_tile(stage, t_flags, t_valid, [](int) {});
+                if (it == 1) READER_STAMP(kStampTileDone, 0);
                 if (last_iter) READER_STAMP(kStampLastTile, 0);
                 if (pair_ends || last_iter) finish_segment(it, pair_ends);
             }

@@ -23,8 +23,9 @@ import numpy as np
 
 STAMP_NAMES = ["entry", "range known", "list written", "first two key tiles asked for", "first item in LDS",
                "first tile computed", "last tile computed", "exit", "copy constants made", "first key tile asked for",
-               "iteration 8: copier at the top", "iteration 8: copier past the barrier", "iteration 8: next item asked for"]
-ORDER = [0, 1, 2, 8, 9, 3, 4, 5, 10, 11, 12, 6, 7]     # in the order a workgroup reaches them
+               "iteration 8: copier at the top", "iteration 8: copier past the barrier", "iteration 8: next item asked for",
+               "first key tile in LDS", "first key tile computed (one wavefront)"]
+ORDER = [0, 1, 2, 8, 9, 3, 4, 13, 14, 5, 10, 11, 12, 6, 7]     # in the order a workgroup reaches them
 N_STAMPS = len(STAMP_NAMES)
 MAX_WG = 2048
 

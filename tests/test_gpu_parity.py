@@ -128,6 +128,21 @@ def test_attn_ranges_cut_with_64_bit_arithmetic(R, oracle_mod, T, Hq, tune):
     check_attn(R, oracle_mod, w)
 
 
+@pytest.mark.parametrize("cost,front", [(0, 0), (1, 0), (3, 0), (3, 3), (5, 2), (9, 0), (9, 9)])
+@pytest.mark.parametrize("axis64", [0, 1])
+def test_attn_pair_cost_in_front_of_and_behind_the_tiles(R, oracle_mod, cost, front, axis64, tune):
+    # what a pair costs beyond its tiles is booked partly in front of its tiles and partly behind them when
+    # the ranges are cut: any split gives the same result, whichever padding a cut falls into (ranges that
+    # end up empty included), in the 32-bit cut (found by votes) and the 64-bit one (found by search)
+    tune(R.TUNE_ATTN_PAIR_COST, cost)
+    tune(R.TUNE_ATTN_PAIR_FRONT, front)
+    if axis64:
+        tune(R.TUNE_ATTN_AXIS64, 1)
+    w = W.make_custom("pair_cost", B=6, Hq=8, Hkv=4, D=128, T=24, seq_lens=[0, 64, 700, 3, 129, 260], tree="trie",
+                      depth=5, seed=409)
+    check_attn(R, oracle_mod, w, variants=(0,))
+
+
 @pytest.mark.parametrize("case", range(16))
 def test_attn_seeded_random_shapes(R, oracle_mod, case):
     # a seeded sweep over batch, tree size, head layout and length mix (empty sequences included), both
