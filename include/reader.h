@@ -331,7 +331,9 @@ int reader_verify_step(const reader_dims *dims,
  *   new_len       i32  [B]                  out
  *   scratch       >= reader_kv_rearrange_scratch_bytes(B, S) bytes of device memory,
  *                 4-byte aligned; contents meaningless between calls
- * D must be 64 or 128.  Returns READER_OK or a READER_E* code (nothing is enqueued then).
+ * D must be 64 or 128 and NL * B * (Hkv + 1) below 2^31 (READER_EUNSUPPORTED otherwise).
+ * Two launches (scan of the flags; the moves and the clearing).  Returns READER_OK or a READER_E* code
+ * (nothing is enqueued then).
  */
 size_t reader_kv_rearrange_scratch_bytes(int32_t B, int32_t S);
 int reader_kv_rearrange(int32_t NL, int32_t B, int32_t S, int32_t Hkv, int32_t D,

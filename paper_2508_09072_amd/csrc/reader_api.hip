@@ -552,7 +552,8 @@ extern "C" int reader_kv_rearrange(int32_t NL, int32_t B, int32_t S, int32_t Hkv
                                    size_t scratch_bytes, void *stream) {
     if (NL < 0 || B < 0 || S < 0 || Hkv < 1 || D < 1) return READER_EINVAL;
     if (D != 64 && D != 128) return READER_EUNSUPPORTED;
-    if ((long long)B * Hkv > 0x7fffffffLL || NL > 65535) return READER_EUNSUPPORTED;
+    if ((long long)B * ((long long)Hkv + 1) > 0x7fffffffLL || (long long)B * ((long long)Hkv + 1) * (NL > 0 ? NL : 1) > 0x7fffffffLL)
+        return READER_EUNSUPPORTED;
     if (B == 0 || S == 0) return READER_OK;
     if (!valid || !new_len || (NL > 0 && (!k_pad || !v_pad))) return READER_EINVAL;
     if (!scratch || ((uintptr_t)scratch & 3) != 0 || scratch_bytes < reader_kv_rearrange_scratch_bytes(B, S))

@@ -55,6 +55,12 @@ def test_many_steps_ragged_batch(R, oracle_mod):
     check(R, oracle_mod, c)
 
 
+def test_more_slots_than_one_round_of_the_scan(R, oracle_mod):
+    # the flags are scanned in rounds of 8192 slots per sample: two rounds here, with holes in both
+    c = W.make_padded_cache("long", NL=2, B=3, Hkv=2, D=64, prompt_lens=[9000, 100, 8190], steps=30, p_long=0.2, seed=33)
+    check(R, oracle_mod, c)
+
+
 def test_hand_made_patterns(R, oracle_mod):
     # no hole; nothing valid; a single far entry; alternating flags; a hole of exactly one pass
     NL, B, S, Hkv, D = 1, 6, 200, 2, 128

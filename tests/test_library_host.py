@@ -150,6 +150,8 @@ def test_rearrange_arguments_are_checked_on_the_host(R):
     assert lib.reader_kv_rearrange(1, 2, 8, 2, 128, one, one, one, one, None, 0, None) == R.READER_EWORKSPACE
     assert lib.reader_kv_rearrange(1, 2, 8, 2, 128, one, one, one, one, one, 16, None) == R.READER_EWORKSPACE
     assert lib.reader_kv_rearrange(1, 0, 8, 2, 128, None, None, None, None, None, 0, None) == R.READER_OK   # empty batch
+    # more workgroups than one launch holds: layers x samples x (kv heads + 1) must stay below 2^31
+    assert lib.reader_kv_rearrange(40000, 8192, 8, 8, 128, one, one, one, one, one, 1 << 20, None) == R.READER_EUNSUPPORTED
 
 
 
