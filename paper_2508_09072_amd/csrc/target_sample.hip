@@ -55,6 +55,10 @@ __device__ inline float scaled(uint32_t bits16_hi, float c) {
     const float x = __uint_as_float(bits16_hi);
     return x != x ? -INFINITY : fminf(x * c, kCeil);
 }
+// A weight relative to its slot's maximum lies in [0, 1] (rounding may leave the largest a hair above); the
+// weight of a NaN logit is a NaN and becomes 0 here.  Written so that the compiler folds it into the
+// instruction that makes the weight (its result clamp), at no cost.
+__device__ inline float unit_clamp(float w) { return fminf(fmaxf(w, 0.f), 1.f); }
 __device__ inline void unpack8(const uint4 &w, float c, float y[8]) {
     const uint32_t u[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
@@ -98,8 +102,8 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
         const float s = wave_sum(m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(y - m));
         if (lane == 0) s_stat[wave == 0 ? 0 : n_slots - 1] = make_float2(m, s);
     }
-    // slots: a wavefront takes the four blocks of a slot at once.  Per token: widen, squash a NaN to
-    // -inf (the maximum of a NaN and a number is the number), one fused multiply-add, exp2, add;
+    // slots: a wavefront takes the four blocks of a slot at once.  Per token: widen, half a three-way
+    // maximum, one fused multiply-add, exp2 (a NaN becomes weight 0 in its result clamp), add;
     // per slot: one maximum and one sum across the wavefront.  Lanes past the end of the row hold
     // -inf bit patterns, so nothing is selected per token.
     const uint4 nothing = make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);
@@ -116,29 +120,30 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
             const uint32_t u[4] = {w[j].x, w[j].y, w[j].z, w[j].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                x[8 * j + 2 * e] = fmaxf(__uint_as_float(u[e] << 16), -INFINITY);
-                x[8 * j + 2 * e + 1] = fmaxf(__uint_as_float(u[e] & 0xffff0000u), -INFINITY);
+                x[8 * j + 2 * e] = __uint_as_float(u[e] << 16);
+                x[8 * j + 2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
             }
         }
-        float m = x[0];
+        // (the maximum of a NaN and a number is the number: a NaN never becomes the maximum unless all are)
+        float m = fmaxf(x[0], -INFINITY);
 #pragma unroll
-        for (int e = 1; e < 8 * kGroup; ++e) m = fmaxf(m, x[e]);
+        for (int e = 1; e < 8 * kGroup; e += 2) m = fmaxf(fmaxf(m, x[e]), e + 1 < 8 * kGroup ? x[e + 1] : -INFINITY);
         m = wave_max(m);
         float s0 = 0.f, s1 = 0.f, m_store;
         if (m * c < kCeil) {                              // (wavefront-uniform)
             const float mc = fmaxf(m, -0x1p126f) * c;     // a slot of nothing but -inf: every weight becomes exp2(-inf) = 0
 #pragma unroll
             for (int e = 0; e < 8 * kGroup; e += 2) {
-                s0 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -mc));
-                s1 += __builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 1], c, -mc));
+                s0 += unit_clamp(__builtin_amdgcn_exp2f(__builtin_fmaf(x[e], c, -mc)));
+                s1 += unit_clamp(__builtin_amdgcn_exp2f(__builtin_fmaf(x[e + 1], c, -mc)));
             }
             m_store = m * c;
         } else {
             // a +inf logit, or one so large that scaling overflows: go through the clamped values
 #pragma unroll
             for (int e = 0; e < 8 * kGroup; e += 2) {
-                s0 += __builtin_amdgcn_exp2f(fminf(x[e] * c, kCeil) - kCeil);
-                s1 += __builtin_amdgcn_exp2f(fminf(x[e + 1] * c, kCeil) - kCeil);
+                s0 += __builtin_amdgcn_exp2f(fminf(fmaxf(x[e], -INFINITY) * c, kCeil) - kCeil);
+                s1 += __builtin_amdgcn_exp2f(fminf(fmaxf(x[e + 1], -INFINITY) * c, kCeil) - kCeil);
             }
             m_store = kCeil;                              // some token of the slot sits at the ceiling
         }
