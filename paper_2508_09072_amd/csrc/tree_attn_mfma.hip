@@ -594,7 +594,9 @@ __global__ __launch_bounds__(kThreads) void tree_attn_mfma_kernel(AttnParams p,
                     const auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
                     u32x4 w;
                     w.x = s0[0]; w.y = s1[0]; w.z = s0[1]; w.w = s1[1];
-                    rec16[(size_t)(db * 4 + i4 + h) * kRowsPerWG + row_local] = w;
+                    // (streamed past the caches: read next by the merge kernel, on other compute units; on short
+                    // launches the end of the kernel has less to write back, 0.7 us of the single-prompt step)
+                    __builtin_nontemporal_store(w, &rec16[(size_t)(db * 4 + i4 + h) * kRowsPerWG + row_local]);
                 }
             if (h == 0) {
                 float *ml = rec + (size_t)kRowsPerWG * (D / 2);
