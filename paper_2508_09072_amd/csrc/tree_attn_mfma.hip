@@ -795,7 +795,20 @@ __device__ inline void merge_body(const AttnParams &p, int pair, int block_y) {
     const int tid = threadIdx.x, grp = tid / group_threads, t2 = tid - grp * group_threads;
     const int blocks_per_chunk = p.rows_per_wg / rows_per_block;
     const int row_chunk = block_y / blocks_per_chunk;
-    const int row_local = (block_y - row_chunk * blocks_per_chunk) * rows_per_block + t2 / kC, c = t2 % kC;
+    const int block_in_chunk = block_y - row_chunk * blocks_per_chunk;
+    // Thread -> (row, 8-wide chunk).  One group: a workgroup takes rows_per_block whole rows, a row's chunks on
+    // neighbouring threads.  Four groups (one wavefront each): a record is laid out [chunk][row], so a wavefront
+    // takes 16 consecutive rows of four chunks (256 contiguous bytes per chunk and load) instead of four whole
+    // rows (64), and the workgroups of a row block take a quarter of the chunks each; same number of workgroups.
+    int row_local, c;
+    if (groups == 1) {
+        row_local = block_in_chunk * rows_per_block + t2 / kC;
+        c = t2 % kC;
+    } else {
+        constexpr int kQuarters = kC / 4;
+        row_local = (block_in_chunk / kQuarters) * 16 + (t2 & 15);
+        c = (block_in_chunk % kQuarters) * 4 + (t2 >> 4);
+    }
     const int m_row = row_chunk * p.rows_per_wg + row_local;
     const bool live = m_row < p.M;
     const int node = live ? m_row / p.G : 0, group = live ? m_row - node * p.G : 0;
