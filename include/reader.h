@@ -188,8 +188,11 @@ int reader_tree_attn(const reader_dims *dims,
  * until the process ends).  The call allocates and frees nothing, on the host or the device.
  *
  *  - Dims whose reader_workspace_bytes(dims, max_seq_len) exceeds READER_NOALLOC_WORKSPACE_BYTES
- *    are refused with READER_EWORKSPACE (reader_last_error_detail says by how much); the limit
- *    covers e.g. B = 64, Hq = 64, Hkv = 8, T = 64, D = 128 at any length.
+ *    are refused with READER_EWORKSPACE (reader_last_error_detail says by how much).  The planner
+ *    keeps key ranges x row chunks within the number of compute units, so the records never need
+ *    more than 34.7 MB and the limit covers every shape with B * Hkv up to about 600,000 (the
+ *    header holds 8 bytes per (sequence, kv head)); more ranges forced with
+ *    reader_tuning_override can exceed it.
  *  - All calls on one GPU share that GPU's workspace: calls that may overlap in time (different
  *    streams, or host threads without ordering) race on it and must be ordered by the caller.
  *  - The first call on a device looks up the workspace's device address (this may load the
@@ -198,7 +201,7 @@ int reader_tree_attn(const reader_dims *dims,
  * dims->variant must be 0.  Returns as reader_tree_attn, READER_EUNSUPPORTED for a device index
  * above 63.
  */
-#define READER_NOALLOC_WORKSPACE_BYTES (72u << 20)
+#define READER_NOALLOC_WORKSPACE_BYTES (40u << 20)
 int reader_tree_attn_noalloc(const reader_dims *dims,
                              const void *q, const void *k_tree, const void *v_tree,
                              const void *k_cache, const void *v_cache,

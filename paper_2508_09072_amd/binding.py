@@ -231,7 +231,7 @@ def reader_tree_attn(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_
     _check(code, "reader_tree_attn")
 
 
-NOALLOC_WORKSPACE_BYTES = 72 << 20
+NOALLOC_WORKSPACE_BYTES = 40 << 20
 
 
 def reader_tree_attn_noalloc(dims, q, k_tree, v_tree, k_cache, v_cache, page_table, seq_lens, parents, out, lse,

@@ -69,16 +69,18 @@ int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len) {
     // compute unit, so at most 256 ranges; short problems get fewer so that a range holds
     // at least two tiles (what a workgroup spends before its first tile arrives is worth
     // several tiles, so tiny problems want many short ranges; measured), and when the rows
-    // are cut into 128-row chunks (small problems only) all workgroups fit the chip at once.
+    // are cut into chunks, so few that all workgroups run at once: a second round of
+    // workgroups pays the start of a workgroup again and cuts twice as many pairs (measured:
+    // 128 ranges x 2 chunks against 256 x 2 is 4-5 % faster on long contexts, the same on large batches).
     const int forced = tuning(READER_TUNE_ATTN_RANGES);
     long long tiles_per_pair = (max_seq_len + kTile - 1) / kTile + (d.T + kTile - 1) / kTile;
     long long units = (long long)d.B * d.Hkv * tiles_per_pair;
     long long n = forced > 0 ? forced : units / 2;
     if (n > kNumCU) n = kNumCU;
     const int M = d.T * (d.Hq / d.Hkv);
-    if (forced <= 0 && M > 128 && attn_rows_per_wg(d, max_seq_len) == 128) {
-        const int chunks = (M + 127) / 128;
-        if (n > kNumCU / chunks) n = kNumCU / chunks;
+    if (forced <= 0) {
+        const int rows = attn_rows_per_wg(d, max_seq_len), chunks = (M + rows - 1) / rows;
+        if (chunks > 1 && n > kNumCU / chunks) n = kNumCU / chunks;
     }
     if (n > units) n = units;
     if (n < 1) n = 1;

@@ -65,17 +65,23 @@ def test_noalloc_equals_the_workspace_entry_point_twice_in_a_row(R, oracle_mod):
 
 def test_noalloc_refuses_what_does_not_fit(R):
     import torch
-    # 2048 query rows per kv head in 256 ranges need far more than the built-in workspace: refused on
-    # the host, nothing is launched, the detail text says why
+    # 2048 query rows per kv head (eight row chunks) in 256 ranges need far more than the built-in workspace:
+    # refused on the host, nothing is launched, the detail text says why.  (The planner itself keeps
+    # ranges x chunks within the number of compute units, which always fits: the ranges are forced here.)
     dims = R.make_dims(64, 128, 128, 8, 128, 600, 16, 64 * 600)
-    need = R.reader_workspace_bytes(dims, 8192)
-    assert need > R.NOALLOC_WORKSPACE_BYTES
     x = torch.zeros(16, dtype=torch.bfloat16, device="cuda")
     i = torch.zeros(16, dtype=torch.int32, device="cuda")
-    with pytest.raises(R.ReaderError) as e:
-        R.reader_tree_attn_noalloc(dims, x, x, x, x, x, i, i, i, x, None, 8192)
-    assert e.value.code == R.READER_EWORKSPACE
-    assert "workspace" in R.load().reader_last_error_detail().decode()
+    assert R.reader_workspace_bytes(dims, 8192) <= R.NOALLOC_WORKSPACE_BYTES
+    R.reader_tuning_override(R.TUNE_ATTN_RANGES, 256)
+    try:
+        need = R.reader_workspace_bytes(dims, 8192)
+        assert need > R.NOALLOC_WORKSPACE_BYTES
+        with pytest.raises(R.ReaderError) as e:
+            R.reader_tree_attn_noalloc(dims, x, x, x, x, x, i, i, i, x, None, 8192)
+        assert e.value.code == R.READER_EWORKSPACE
+        assert "workspace" in R.load().reader_last_error_detail().decode()
+    finally:
+        R.reader_tuning_override(R.TUNE_ATTN_RANGES, -1)
     dims = R.make_dims(1, 8, 8, 8, 128, 4, 4, 4, variant=1)
     with pytest.raises(R.ReaderError) as e:
         R.reader_tree_attn_noalloc(dims, x, x, x, x, x, i, i, i, x, None, 16)
