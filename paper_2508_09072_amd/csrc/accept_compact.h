@@ -181,23 +181,33 @@ __device__ inline void kv_compact_body(const CompactParams &p, int b, int tid, i
 
     const int chunks_per_head = p.D / 8;                 // 16-byte chunks
     const int chunks_per_row = p.Hkv * chunks_per_head;  // one position, all kv heads, K or V
-    const int total = (n + 1) * 2 * chunks_per_row;
-    for (int idx = tid; idx < total; idx += 256) {
-        const int j = idx / (2 * chunks_per_row);
-        const int rem = idx - j * 2 * chunks_per_row;
+    // A thread keeps its place inside a position (K or V, head, chunk) and walks the path entries, eight at a
+    // time: their rows are asked for together and stored afterwards (taken one by one, every accepted token
+    // costs a trip to memory).  The loads carry no condition (an entry past the path reads the last one
+    // again), so that they stay together in front of the stores.
+    constexpr int kBatch = 8;
+    for (int rem = tid; rem < 2 * chunks_per_row; rem += 256) {
         const int which = rem / chunks_per_row;
         const int c = rem - which * chunks_per_row;
         const int h = c / chunks_per_head;
         const int dc = c - h * chunks_per_head;
-        const int node = path[j];
-        const int pos = L + j;
-        const long long page = cs.page[j];
-        const int slot = pos % READER_PAGE_SIZE;
-        const size_t src = (((size_t)b * p.T + node) * p.Hkv + h) * p.D + dc * 8;
-        const size_t dst = (((size_t)page * p.Hkv + h) * READER_PAGE_SIZE + slot) * p.D + dc * 8;
-        const uint16_t *tree = which ? p.v_tree : p.k_tree;
-        uint16_t *cache = which ? p.v_cache : p.k_cache;
-        *reinterpret_cast<uint4 *>(cache + dst) = *reinterpret_cast<const uint4 *>(tree + src);
+        const uint16_t *tree = (which ? p.v_tree : p.k_tree) + ((size_t)b * p.T * p.Hkv + h) * p.D + dc * 8;
+        uint16_t *cache = (which ? p.v_cache : p.k_cache) + (size_t)h * READER_PAGE_SIZE * p.D + dc * 8;
+        for (int j0 = 0; j0 <= n; j0 += kBatch) {
+            uint4 held[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u)
+                held[u] = *reinterpret_cast<const uint4 *>(tree + (size_t)path[min(j0 + u, n)] * p.Hkv * p.D);
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                const int j = j0 + u;
+                if (j <= n) {
+                    const long long page = cs.page[j];
+                    const int slot = (L + j) % READER_PAGE_SIZE;
+                    *reinterpret_cast<uint4 *>(cache + ((size_t)page * p.Hkv * READER_PAGE_SIZE + slot) * p.D) = held[u];
+                }
+            }
+        }
     }
     if (tid == 0) p.seq_lens[b] = L + n + 1;
 }
