@@ -49,10 +49,11 @@ static bool dims_ok(const reader_dims *d, int *err) {
 
 // Query rows a workgroup carries: 128 (four computing wavefronts, four that move data) or 256
 // (all eight compute and copy).  Up to 128 rows per (sequence, kv head) there is nothing to
-// choose.  Beyond that 256-row workgroups do more matrix work per byte they fetch and win as
-// soon as a workgroup has a few tiles to stream; a small problem (a single prompt of a few
+// choose.  Beyond that 256-row workgroups do more matrix work per byte they fetch and win once
+// a workgroup has some tens of tiles to stream; a small problem (one or two prompts of a few
 // thousand tokens) is over sooner when it is cut into more, lighter workgroups (measured
-// crossover: about 1100 workgroup-tiles).
+// crossover with 256 and with 512 rows per kv head: about 10000 workgroup-tiles, i.e. 40 per
+// workgroup; at a fifth of that the 128-row workgroups are a quarter faster).
 int attn_rows_per_wg(const reader_dims &d, int32_t max_seq_len) {
     const int forced = tuning(READER_TUNE_ATTN_ROWS);
     if (forced == 128 || forced == 256) return forced;
@@ -60,7 +61,7 @@ int attn_rows_per_wg(const reader_dims &d, int32_t max_seq_len) {
     if (M <= 128) return 128;
     const long long tiles_per_pair = (max_seq_len + kTile - 1) / kTile + (d.T + kTile - 1) / kTile;
     const long long units = (long long)d.B * d.Hkv * tiles_per_pair;
-    return units * ((M + 127) / 128) <= 1100 ? 128 : 256;
+    return units * ((M + 127) / 128) <= 10000 ? 128 : 256;
 }
 
 int attn_plan_ranges(const reader_dims &d, int32_t max_seq_len) {

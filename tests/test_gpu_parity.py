@@ -344,11 +344,14 @@ def test_attn_scores_that_outgrow_the_fixed_reference_are_computed_again(R, orac
 
 def test_attn_full_size_head_dim_64_with_256_row_workgroups(R, oracle_mod):
     # D = 64 on a problem large enough for the planner to pick 256-row workgroups by itself (512 query rows per
-    # kv head, > 1100 workgroup-tiles), ragged lengths, stratified sample of rows
+    # kv head, > 10000 workgroup-tiles), ragged lengths, stratified sample of rows
     rng = np.random.Generator(np.random.PCG64(77))
-    L = [int(x) for x in rng.integers(3000, 5000, size=8)]
-    w = W.make_custom("d64_rows256", B=8, Hq=32, Hkv=4, D=64, T=64, seq_lens=L, tree="trie", depth=8, branch=4, seed=460)
+    L = [int(x) for x in rng.integers(3000, 5000, size=16)]
+    w = W.make_custom("d64_rows256", B=16, Hq=32, Hkv=4, D=64, T=64, seq_lens=L, tree="trie", depth=8, branch=4, seed=460)
     print("full-size attn:", w.name, "L", L, flush=True)
+    plan = R.reader_attn_plan(R.make_dims(w.B, w.T, w.Hq, w.Hkv, w.D, w.page_table.shape[1], w.max_path, w.k_cache.shape[0]),
+                              int(max(L)))
+    assert plan["rows_per_workgroup"] == 256, plan
     out, lse = run_attn(R, w)
     check_sampled_rows(oracle_mod, w, out, lse, stratified_rows(w, rng), w.name)
 
