@@ -249,7 +249,16 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
         const bool edge = slot == 0 || slot == n_slots - 1;      // head or tail: up to 7 tokens, one per lane
         float carry = front;
         int pick = 0x7fffffff, last_pos = -1;
-        for (int j = 0; j < (edge ? 1 : kGroup); ++j) {
+        // (the four blocks of the slot are asked for together: one trip to memory, not four)
+        uint4 again[kGroup];
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            const int g = ((slot - 1) * kGroup + j) * 64 + lane;
+            again[j] = (!edge && g < n_vec) ? vec[g] : nothing;
+        }
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            if (edge && j > 0) break;
             float y[8];
             int first, cnt;              // this lane's tokens: indices first .. first + cnt - 1
             if (edge) {
@@ -263,8 +272,7 @@ __global__ __launch_bounds__(kSampleThreads) void target_sample_kernel(const uin
                 const int g = ((slot - 1) * kGroup + j) * 64 + lane;
                 cnt = g < n_vec ? 8 : 0;
                 first = head + g * 8;
-                const uint4 w = cnt ? vec[g] : nothing;
-                unpack8(w, c, y);
+                unpack8(again[j], c, y);
                 if (!cnt) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) y[e] = -INFINITY;
