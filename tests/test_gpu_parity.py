@@ -143,6 +143,18 @@ def test_attn_pair_cost_in_front_of_and_behind_the_tiles(R, oracle_mod, cost, fr
     check_attn(R, oracle_mod, w, variants=(0,))
 
 
+@pytest.mark.parametrize("lens", [[300, 40], [2500]])
+def test_attn_most_query_rows_per_kv_head(R, oracle_mod, lens):
+    # 128 nodes x 16 grouped heads = 2048 query rows per kv head: sixteen 128-row chunks (short contexts) or
+    # eight 256-row chunks per key range, and so few ranges that all workgroups run at once
+    w = W.make_custom("rows2048", B=len(lens), Hq=32, Hkv=2, D=128, T=128, seq_lens=lens, tree="trie", depth=9,
+                      branch=3, seed=411)
+    plan = R.reader_attn_plan(R.make_dims(w.B, w.T, w.Hq, w.Hkv, w.D, w.page_table.shape[1], w.max_path, w.k_cache.shape[0]),
+                              int(max(lens)))
+    assert plan["row_chunks"] * plan["key_ranges"] <= 256, plan
+    check_attn(R, oracle_mod, w, variants=(0,))
+
+
 @pytest.mark.parametrize("case", range(16))
 def test_attn_seeded_random_shapes(R, oracle_mod, case):
     # a seeded sweep over batch, tree size, head layout and length mix (empty sequences included), both
