@@ -264,11 +264,15 @@ static int attn_prepare(const reader_dims *dims, const void *q, const void *k_tr
         // A pair costs the workgroups that start and finish it extra, mostly the one that finishes it (the ragged
         // last prefix tile, the masks of the tree tiles, normalising and writing the rows; the start has the
         // query rows to fetch): with dedicated copy wavefronts about one tile time in front of the pair's
-        // tiles and two behind them, otherwise one in front.
+        // tiles and two behind them; with four wavefronts of 64 rows, whose tiles at the ends of a pair leave the
+        // software pipeline and whose accumulators are read out of the other half of the register file, four and
+        // four (measured at the large-batch preset: kernel 703 -> 685 us against one in front; 16 and more lose
+        // again); otherwise one in front.
+        const bool wide = attn_use_wide(*dims, p.rows_per_wg);
         const int forced_cost = tuning(READER_TUNE_ATTN_PAIR_COST);
-        p.pair_cost = forced_cost >= 0 && forced_cost <= 64 ? forced_cost : (p.rows_per_wg == 128 ? 3 : 1);
+        p.pair_cost = forced_cost >= 0 && forced_cost <= 64 ? forced_cost : (p.rows_per_wg == 128 ? 3 : (wide ? 8 : 1));
         const int forced_front = tuning(READER_TUNE_ATTN_PAIR_FRONT);
-        p.pair_front = forced_front >= 0 ? forced_front : 1;
+        p.pair_front = forced_front >= 0 ? forced_front : (wide ? 4 : 1);
         if (p.pair_front > p.pair_cost) p.pair_front = p.pair_cost;
         // the kernel cuts the ranges with 32-bit arithmetic when nothing on the cost axis can overflow it
         const long long axis_max = (long long)p.Hkv * p.B * ((max_seq_len + kTile - 1) / kTile + p.n_tree_tiles + p.pair_cost);
