@@ -175,18 +175,23 @@ __global__ __launch_bounds__(kWideThreads) void tree_attn_wide_kernel(AttnParams
     // The query rows of this lane (one per row block) as B operands of the first product: loaded once per
     // segment into the accumulation registers, where they stay.
     auto load_q = [&](int b, int hkv) {
+        // (the rows of both row blocks are asked for before any is put away: one trip to memory, not two; the score
+        // and weight registers are free at this point)
+        u32x4 w[2][G::kKSteps];
         static_for<2>([&](auto rc) {
             constexpr int r = decltype(rc)::value;
             const uint16_t *qrow = p.q + (((size_t)b * p.T + node_of(rc)) * p.Hq + hkv * p.G + group_of(rc)) * D;
-            u32x4 w[G::kKSteps];
 #pragma unroll
-            for (int kk = 0; kk < G::kKSteps; ++kk) w[kk] = keep_if(row_real[r], ld16(qrow + kk * 16 + h * 8));
+            for (int kk = 0; kk < G::kKSteps; ++kk) w[r][kk] = keep_if(row_real[r], ld16(qrow + kk * 16 + h * 8));
+        });
+        static_for<2>([&](auto rc) {
+            constexpr int r = decltype(rc)::value;
             static_for<G::kKSteps>([&](auto kc) {
                 constexpr int kk = decltype(kc)::value;
-                acc_write<Acc::q(r, kk)>(w[kk].x);
-                acc_write<Acc::q(r, kk) + 1>(w[kk].y);
-                acc_write<Acc::q(r, kk) + 2>(w[kk].z);
-                acc_write<Acc::q(r, kk) + 3>(w[kk].w);
+                acc_write<Acc::q(r, kk)>(w[r][kk].x);
+                acc_write<Acc::q(r, kk) + 1>(w[r][kk].y);
+                acc_write<Acc::q(r, kk) + 2>(w[r][kk].z);
+                acc_write<Acc::q(r, kk) + 3>(w[r][kk].w);
             });
         });
         asm volatile("s_nop 3");
